@@ -1,0 +1,166 @@
+"""ctypes front end of the CPU oracle (oracle/lantern_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+bench's CPU-baseline leg; never by the product package.  All arithmetic lives
+in the C file; this module widens inputs to fp32 storage (exact for bf16 and
+fp32 values), calls the C routines and names the diagnostic columns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lantern_oracle.c")
+_LIB = os.path.join(_HERE, "liblantern_oracle.so")
+
+DIAG_NAMES = (
+    "accept_prob", "mass", "g_tok", "t_tok", "tvd_walk", "tvd_direct", "resid_z",
+    "a_size", "margin_accept", "margin_cut", "margin_cdf", "zero_resid",
+)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  FP contraction is off so that the table's
+    squared distances are separately rounded fp64 operations."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.oracle_build_knn_rows.argtypes = [f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p,
+                                              ctypes.c_int]
+        lib.oracle_build_knn_rows.restype = ctypes.c_int
+        lib.oracle_softmax.argtypes = [f32p, ctypes.c_int, f64p]
+        lib.oracle_softmax.restype = ctypes.c_int
+        lib.oracle_verify_probs.argtypes = [f64p, f64p, ctypes.c_int, ctypes.c_int, i32p,
+                                            ctypes.c_int, ctypes.c_double, ctypes.c_double,
+                                            ctypes.c_double, i32p, i32p, f64p, f64p, f64p]
+        lib.oracle_verify_probs.restype = ctypes.c_int
+        lib.oracle_verify.argtypes = [f32p, f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                      i32p, i32p, ctypes.c_int, ctypes.c_double, f32p, i32p, i32p,
+                                      f64p, ctypes.c_int]
+        lib.oracle_verify.restype = ctypes.c_int
+        lib.oracle_diag_count.restype = ctypes.c_int
+        lib.oracle_max_threads.restype = ctypes.c_int
+        assert lib.oracle_diag_count() == len(DIAG_NAMES)
+        _lib = lib
+    return _lib
+
+
+def _as_f32(a) -> np.ndarray:
+    """fp32 or bf16 values (numpy array or torch tensor) -> C-contiguous fp32 array."""
+    if hasattr(a, "detach"):  # torch tensor; bf16 -> fp32 is exact
+        a = a.detach().to("cpu").float().numpy()
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _as_i32(a) -> np.ndarray:
+    if hasattr(a, "detach"):
+        a = a.detach().to("cpu").numpy()
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def build_knn(codebook, k: int, rows=None, metric: str = "l2", threads: int = 1) -> np.ndarray:
+    """Rows [rows[0], rows[1]) (default all) of the neighbour table, int32 [R, k]."""
+    lib = _load()
+    cb = _as_f32(codebook)
+    V, d = cb.shape
+    r0, r1 = (0, V) if rows is None else rows
+    out = np.empty((r1 - r0, k), dtype=np.int32)
+    rc = lib.oracle_build_knn_rows(_p(cb, ctypes.c_float), V, d, k, {"l2": 0, "cosine": 1}[metric],
+                                   r0, r1, _p(out, ctypes.c_int32), threads)
+    if rc != 0:
+        raise ValueError("oracle_build_knn_rows: bad arguments")
+    return out
+
+
+def softmax(logits) -> np.ndarray:
+    lib = _load()
+    l = _as_f32(logits).reshape(-1)
+    out = np.empty(l.shape[0], dtype=np.float64)
+    rc = lib.oracle_softmax(_p(l, ctypes.c_float), l.shape[0], _p(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("oracle_softmax: unusable row")
+    return out
+
+
+def verify_probs(t, g, xt: int, nbrs, delta: float, u_acc: float, u_res: float,
+                 want_dists: bool = False) -> dict:
+    """One verification on explicit probability vectors."""
+    lib = _load()
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    nb = _as_i32(nbrs)
+    V = t.shape[0]
+    acc = np.zeros(1, dtype=np.int32)
+    res = np.zeros(1, dtype=np.int32)
+    diag = np.empty(len(DIAG_NAMES), dtype=np.float64)
+    rho = np.empty(V, dtype=np.float64) if want_dists else None
+    ta = np.empty(V, dtype=np.float64) if want_dists else None
+    rc = lib.oracle_verify_probs(_p(t, ctypes.c_double), _p(g, ctypes.c_double), V, int(xt),
+                                 _p(nb, ctypes.c_int32), nb.shape[0], float(delta), float(u_acc),
+                                 float(u_res), _p(acc, ctypes.c_int32), _p(res, ctypes.c_int32),
+                                 _p(diag, ctypes.c_double),
+                                 _p(rho, ctypes.c_double) if want_dists else None,
+                                 _p(ta, ctypes.c_double) if want_dists else None)
+    if rc != 0:
+        raise ValueError("oracle_verify_probs: bad arguments")
+    out = {"accept": int(acc[0]), "resample": int(res[0])}
+    out.update({n: float(v) for n, v in zip(DIAG_NAMES, diag)})
+    out["a_size"] = int(out["a_size"])
+    if want_dists:
+        out["residual"] = rho
+        out["distorted_target"] = ta
+    return out
+
+
+def verify(target_logits, draft_logits, draft_tokens, knn, k: int, delta: float, uniforms,
+           threads: int = 1, want_diag: bool = True):
+    """N verifications from logits.  Returns (accept int32[N], resample int32[N], diag dict|None)."""
+    lib = _load()
+    tl = _as_f32(target_logits)
+    dl = _as_f32(draft_logits)
+    if tl.ndim != 2 or tl.shape != dl.shape:
+        raise ValueError("logits must be two [N, V] arrays of equal shape")
+    N, V = tl.shape
+    tok = _as_i32(draft_tokens).reshape(-1)
+    tab = _as_i32(knn)
+    un = _as_f32(uniforms).reshape(-1)
+    if tok.shape[0] != N or un.shape[0] != 2 * N or tab.size != V * k:
+        raise ValueError("shape mismatch")
+    acc = np.empty(N, dtype=np.int32)
+    res = np.empty(N, dtype=np.int32)
+    diag = np.empty((N, len(DIAG_NAMES)), dtype=np.float64) if want_diag else None
+    rc = lib.oracle_verify(_p(tl, ctypes.c_float), _p(dl, ctypes.c_float), N, V, V,
+                           _p(tok, ctypes.c_int32), _p(tab, ctypes.c_int32), int(k), float(delta),
+                           _p(un, ctypes.c_float), _p(acc, ctypes.c_int32), _p(res, ctypes.c_int32),
+                           _p(diag, ctypes.c_double) if want_diag else None, int(threads))
+    if rc != 0:
+        raise ValueError("oracle_verify: bad arguments")
+    d = {n: diag[:, i] for i, n in enumerate(DIAG_NAMES)} if want_diag else None
+    return acc, res, d

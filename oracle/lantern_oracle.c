@@ -1,0 +1,399 @@
+/*
+ * CPU oracle for LANTERN's relaxed-acceptance verification and its codebook
+ * nearest-neighbour table.  TEST INFRASTRUCTURE ONLY: it exists so the tests,
+ * the smoke check and the bench's CPU-baseline leg have an independent, slow,
+ * obviously-correct result to compare the HIP library against.  The product
+ * path never calls it, and it shares no code with the HIP sources.
+ *
+ * Everything is evaluated in fp64, one row at a time, in the order the paper
+ * states its steps.  Inputs arrive as fp32 arrays (bf16 and fp32 logits are
+ * both exactly representable in fp32) and are widened to fp64 on read.
+ *
+ * Notation.  The paper writes p for the drafter and q for the target model
+ * (Section 2, "Notations").  To keep that from being confused with the
+ * opposite convention used elsewhere, this file writes
+ *     t(x)  target probability      (the paper's q)
+ *     g(x)  drafter probability     (the paper's p)
+ *     xt    the draft token         (the paper's x-tilde)
+ *
+ * Build with -ffp-contract=off: the squared distance of the table build is
+ * defined as a sequence of separately rounded fp64 subtract, multiply and add
+ * operations, so that an IEEE-754 fp64 implementation elsewhere can reproduce
+ * the ordering of near-ties bit for bit.
+ *
+ * Parity pins (tests marked "not gpu"): hand-derived rows under tests/golden,
+ * reduction to standard speculative acceptance at k = 1 and delta = 0, the TVD
+ * invariant, brute-force neighbour search, residuals that sum to one, exact
+ * enumeration and Monte-Carlo recovery of the target law at k = 1.
+ * Parity unpinned: behaviour on real LlamaGen / Anole logits and codebooks.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* Codebook neighbour table  B_k  (Section 4.2; Algorithm 2, precompute part) */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+    double dist;
+    int32_t idx;
+} dist_idx;
+
+static int by_dist_then_idx(const void* pa, const void* pb) {
+    const dist_idx* a = (const dist_idx*)pa;
+    const dist_idx* b = (const dist_idx*)pb;
+    if (a->dist < b->dist) return -1;
+    if (a->dist > b->dist) return 1;
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+/* Squared l2 distance between codes i and j: differences, squares and the
+ * running sum are each rounded to fp64, coordinates taken in index order.
+ * Squared distance orders pairs exactly as the l2 distance does. */
+static double sq_dist(const float* ci, const float* cj, int d) {
+    double acc = 0.0;
+    for (int c = 0; c < d; ++c) {
+        double diff = (double)ci[c] - (double)cj[c];
+        double sq = diff * diff;
+        acc = acc + sq;
+    }
+    return acc;
+}
+
+/* Rows [row_begin, row_end) of the table.  Row i holds i itself first, then
+ * the k-1 other tokens in increasing distance; equal distances are ordered by
+ * the lower token index.  out is [(row_end-row_begin), k].
+ * metric 0: squared l2 (the paper's choice, Section 5.1).
+ * metric 1: cosine similarity, larger is nearer (ablation of Section 5.3.1);
+ *           the key is -cos so that the same ascending order applies.
+ * Returns 0, or -1 on bad arguments. */
+int oracle_build_knn_rows(const float* codebook, int V, int d, int k, int metric,
+                          int row_begin, int row_end, int32_t* out, int threads) {
+    if (!codebook || !out || V < 1 || d < 1 || k < 1 || k > V) return -1;
+    if (row_begin < 0 || row_end > V || row_begin > row_end) return -1;
+    if (metric != 0 && metric != 1) return -1;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads > 0 ? threads : 1)
+#endif
+    {
+        dist_idx* others = (dist_idx*)malloc(sizeof(dist_idx) * (size_t)(V > 1 ? V - 1 : 1));
+        if (!others) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 4)
+#endif
+            for (int i = row_begin; i < row_end; ++i) {
+                const float* ci = codebook + (size_t)i * d;
+                double ni = 0.0;
+                if (metric == 1) {
+                    for (int c = 0; c < d; ++c) ni = ni + (double)ci[c] * (double)ci[c];
+                    ni = sqrt(ni);
+                }
+                int m = 0;
+                for (int j = 0; j < V; ++j) {
+                    if (j == i) continue;
+                    const float* cj = codebook + (size_t)j * d;
+                    double key;
+                    if (metric == 0) {
+                        key = sq_dist(ci, cj, d);
+                    } else {
+                        double dot = 0.0, nj = 0.0;
+                        for (int c = 0; c < d; ++c) {
+                            dot = dot + (double)ci[c] * (double)cj[c];
+                            nj = nj + (double)cj[c] * (double)cj[c];
+                        }
+                        nj = sqrt(nj);
+                        key = -(dot / (ni * nj));
+                    }
+                    others[m].dist = key;
+                    others[m].idx = j;
+                    ++m;
+                }
+                qsort(others, (size_t)m, sizeof(dist_idx), by_dist_then_idx);
+                int32_t* row = out + (size_t)(i - row_begin) * k;
+                row[0] = i;
+                for (int s = 1; s < k; ++s) row[s] = others[s - 1].idx;
+            }
+        }
+        free(others);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Row softmax (Section 2: the model's next-token likelihoods)                */
+/* ------------------------------------------------------------------------- */
+
+/* Returns 0 when the row is usable: no NaN, no +inf, at least one finite
+ * logit.  -inf logits (tokens removed by top-k / top-p filtering upstream)
+ * get probability exactly zero. */
+static int softmax_row(const float* logits, int V, double* prob) {
+    double mx = -INFINITY;
+    for (int x = 0; x < V; ++x) {
+        double l = (double)logits[x];
+        if (isnan(l) || l == INFINITY) return -1;
+        if (l > mx) mx = l;
+    }
+    if (mx == -INFINITY) return -1;
+    double z = 0.0;
+    for (int x = 0; x < V; ++x) {
+        double e = exp((double)logits[x] - mx);
+        prob[x] = e;
+        z = z + e;
+    }
+    for (int x = 0; x < V; ++x) prob[x] = prob[x] / z;
+    return 0;
+}
+
+int oracle_softmax(const float* logits, int V, double* prob) {
+    if (!logits || !prob || V < 1) return -1;
+    return softmax_row(logits, V, prob);
+}
+
+/* ------------------------------------------------------------------------- */
+/* One verification on given probability vectors                              */
+/* ------------------------------------------------------------------------- */
+
+enum {
+    DIAG_ACCEPT_PROB = 0, /* min(1, mass / g(xt))                                   */
+    DIAG_MASS = 1,        /* sum of t over A_{k,delta}(xt)                          */
+    DIAG_G_TOK = 2,       /* g(xt)                                                  */
+    DIAG_T_TOK = 3,       /* t(xt)                                                  */
+    DIAG_TVD_WALK = 4,    /* cumulative TVD kept while walking the neighbourhood    */
+    DIAG_TVD_DIRECT = 5,  /* 1/2 * sum |t_A - t| evaluated from the definition      */
+    DIAG_RESID_Z = 6,     /* normaliser of the residual, 0 when accepted            */
+    DIAG_A_SIZE = 7,      /* number of table slots taken into A                     */
+    DIAG_MARGIN_ACCEPT = 8, /* |u_acc*g(xt) - mass|                                 */
+    DIAG_MARGIN_CUT = 9,    /* min over tested slots of |D_TV + inc - delta|        */
+    DIAG_MARGIN_CDF = 10,   /* min over CDF edges of |cum - u_res*Z| (rejected rows)*/
+    DIAG_ZERO_RESID = 11,   /* 1 when the residual had no mass and t_A was sampled  */
+    DIAG_COUNT = 12
+};
+
+int oracle_diag_count(void) { return DIAG_COUNT; }
+
+/*
+ * t, g: probability vectors of length V.  nbrs: the k table entries of row xt,
+ * nearest first.  scratch: V doubles.
+ *
+ * Steps (Section 4.3; Algorithm 2, inference part; Algorithm 1, verification):
+ *  1. Walk the neighbourhood nearest-first keeping the cumulative TVD.  Adding
+ *     a neighbour x != xt moves t(x) from x onto xt, which by the definition
+ *     of the distorted target raises 1/2*sum|t_A - t| by exactly t(x); adding
+ *     xt itself changes nothing.  A neighbour is taken while the TVD after
+ *     adding it stays strictly below delta; the first one that does not fit
+ *     ends the walk.  xt itself is always taken.
+ *  2. mass = t(xt) + cumulative TVD = sum of t over A.
+ *  3. Accept iff u_acc < min(1, mass / g(xt)), evaluated as u_acc*g(xt) < mass
+ *     (identical for u_acc in [0,1) and g(xt) > 0, and defined at g(xt) = 0).
+ *  4. On rejection build the distorted target t_A (mass at xt, zero on the
+ *     rest of A, t elsewhere), the residual rho = max(0, t_A - g), and return
+ *     the first token, in index order, whose cumulative rho exceeds u_res*Z.
+ *     A residual with no mass at all falls back to sampling t_A.
+ * optional outputs (may be NULL): rho_out[V] normalised residual, ta_out[V].
+ */
+static void verify_probs(const double* t, const double* g, int V, int xt,
+                         const int32_t* nbrs, int k, double delta,
+                         double u_acc, double u_res,
+                         int32_t* out_accept, int32_t* out_resample,
+                         double* diag, double* scratch,
+                         double* rho_out, double* ta_out) {
+    double d_tv = 0.0;
+    int a = 0;
+    double margin_cut = INFINITY;
+    for (int j = 0; j < k; ++j) {
+        int x = nbrs[j];
+        if (x == xt) {
+            a = j + 1;
+            continue;
+        }
+        double inc = t[x];
+        double cand = d_tv + inc;
+        double mg = fabs(cand - delta);
+        if (mg < margin_cut) margin_cut = mg;
+        if (cand < delta) {
+            d_tv = cand;
+            a = j + 1;
+        } else {
+            break;
+        }
+    }
+    double mass = t[xt] + d_tv;
+    double gx = g[xt];
+    double accept_prob;
+    if (gx > 0.0) {
+        accept_prob = mass / gx;
+        if (accept_prob > 1.0) accept_prob = 1.0;
+    } else {
+        accept_prob = mass > 0.0 ? 1.0 : 0.0;
+    }
+    int accepted = (u_acc * gx < mass) ? 1 : 0;
+
+    /* distorted target from its definition, used for the direct TVD and the residual */
+    double* ta = scratch;
+    memcpy(ta, t, sizeof(double) * (size_t)V);
+    for (int j = 0; j < a; ++j)
+        if (nbrs[j] != xt) ta[nbrs[j]] = 0.0;
+    ta[xt] = mass;
+    double tvd_direct = 0.0;
+    for (int x = 0; x < V; ++x) tvd_direct = tvd_direct + fabs(ta[x] - t[x]);
+    tvd_direct = 0.5 * tvd_direct;
+    if (ta_out) memcpy(ta_out, ta, sizeof(double) * (size_t)V);
+
+    double z = 0.0;
+    int zero_resid = 0;
+    int resample = -1;
+    double margin_cdf = INFINITY;
+    if (!accepted || rho_out) {
+        for (int x = 0; x < V; ++x) {
+            double r = ta[x] - g[x];
+            if (!(r > 0.0)) r = 0.0;
+            z = z + r;
+        }
+        if (!(z > 0.0)) zero_resid = 1;
+        double zz = 0.0;
+        if (zero_resid)
+            for (int x = 0; x < V; ++x) zz = zz + ta[x];
+        else
+            zz = z;
+        if (rho_out)
+            for (int x = 0; x < V; ++x) {
+                double r = zero_resid ? ta[x] : ta[x] - g[x];
+                if (!(r > 0.0)) r = 0.0;
+                rho_out[x] = r / zz;
+            }
+        if (!accepted) {
+            double c = u_res * zz;
+            double cum = 0.0;
+            for (int x = 0; x < V; ++x) {
+                double r = zero_resid ? ta[x] : ta[x] - g[x];
+                if (!(r > 0.0)) r = 0.0;
+                cum = cum + r;
+                double mg = fabs(cum - c);
+                if (r > 0.0 && mg < margin_cdf) margin_cdf = mg;
+                if (resample < 0 && cum > c) resample = x;
+            }
+        }
+        z = zz;
+    }
+
+    *out_accept = accepted;
+    *out_resample = accepted ? -1 : resample;
+    if (diag) {
+        diag[DIAG_ACCEPT_PROB] = accept_prob;
+        diag[DIAG_MASS] = mass;
+        diag[DIAG_G_TOK] = gx;
+        diag[DIAG_T_TOK] = t[xt];
+        diag[DIAG_TVD_WALK] = d_tv;
+        diag[DIAG_TVD_DIRECT] = tvd_direct;
+        diag[DIAG_RESID_Z] = accepted ? 0.0 : z;
+        diag[DIAG_A_SIZE] = (double)a;
+        diag[DIAG_MARGIN_ACCEPT] = fabs(u_acc * gx - mass);
+        diag[DIAG_MARGIN_CUT] = margin_cut;
+        diag[DIAG_MARGIN_CDF] = margin_cdf;
+        diag[DIAG_ZERO_RESID] = (double)(zero_resid && !accepted);
+    }
+}
+
+static int row_args_ok(int V, int xt, const int32_t* nbrs, int k) {
+    if (xt < 0 || xt >= V) return 0;
+    for (int j = 0; j < k; ++j)
+        if (nbrs[j] < 0 || nbrs[j] >= V) return 0;
+    return 1;
+}
+
+/* Single verification on probabilities given directly (lets the tests use
+ * dyadic, exactly representable rows).  Returns 0, or -1 on bad arguments. */
+int oracle_verify_probs(const double* t, const double* g, int V, int xt,
+                        const int32_t* nbrs, int k, double delta,
+                        double u_acc, double u_res,
+                        int32_t* out_accept, int32_t* out_resample,
+                        double* diag, double* rho_out, double* ta_out) {
+    if (!t || !g || !nbrs || !out_accept || !out_resample) return -1;
+    if (V < 1 || k < 1 || k > V || !(delta >= 0.0)) return -1;
+    if (!row_args_ok(V, xt, nbrs, k)) return -1;
+    double* scratch = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!scratch) return -1;
+    verify_probs(t, g, V, xt, nbrs, k, delta, u_acc, u_res, out_accept, out_resample,
+                 diag, scratch, rho_out, ta_out);
+    free(scratch);
+    return 0;
+}
+
+/*
+ * N independent verifications from logits.  Row i uses target_logits and
+ * draft_logits at offset i*row_stride, token draft_tokens[i], table row
+ * knn[draft_tokens[i]*k .. +k), uniforms[2i] for acceptance and uniforms[2i+1]
+ * for resampling.  out_accept[i] is 1 or 0; out_resample[i] is the resampled
+ * token, or -1 when accepted.  A row whose token or table entries fall outside
+ * [0,V), or whose logits hold NaN, +inf or nothing finite, gets -1 in both.
+ * diag is NULL or [N, oracle_diag_count()].  Returns 0, or -1 on bad arguments.
+ */
+int oracle_verify(const float* target_logits, const float* draft_logits, int N, int V,
+                  int64_t row_stride, const int32_t* draft_tokens, const int32_t* knn, int k,
+                  double delta, const float* uniforms,
+                  int32_t* out_accept, int32_t* out_resample, double* diag, int threads) {
+    if (N < 0 || V < 1 || k < 1 || k > V || row_stride < V || !(delta >= 0.0)) return -1;
+    if (N == 0) return 0;
+    if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms || !out_accept ||
+        !out_resample)
+        return -1;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads > 0 ? threads : 1)
+#endif
+    {
+        double* buf = (double*)malloc(sizeof(double) * 3 * (size_t)V);
+        if (!buf) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+            double* t = buf;
+            double* g = buf + V;
+            double* scratch = buf + 2 * (size_t)V;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (int i = 0; i < N; ++i) {
+                double* dg = diag ? diag + (size_t)i * DIAG_COUNT : NULL;
+                if (dg)
+                    for (int c = 0; c < DIAG_COUNT; ++c) dg[c] = NAN;
+                int xt = draft_tokens[i];
+                int ok = (xt >= 0 && xt < V) && row_args_ok(V, xt, knn + (size_t)xt * k, k);
+                if (ok) ok = softmax_row(target_logits + (size_t)i * row_stride, V, t) == 0;
+                if (ok) ok = softmax_row(draft_logits + (size_t)i * row_stride, V, g) == 0;
+                if (!ok) {
+                    out_accept[i] = -1;
+                    out_resample[i] = -1;
+                    continue;
+                }
+                verify_probs(t, g, V, xt, knn + (size_t)xt * k, k, delta,
+                             (double)uniforms[2 * (size_t)i], (double)uniforms[2 * (size_t)i + 1],
+                             &out_accept[i], &out_resample[i], dg, scratch, NULL, NULL);
+            }
+        }
+        free(buf);
+    }
+    return failed ? -1 : 0;
+}
+
+int oracle_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
