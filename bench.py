@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Throughput of LANTERN's relaxed verification on one MI355X.
+
+A step is one lantern_verify call over one batch of synthetic rows of the
+stress workload (V=16384 codebook, k=1000 neighbours, delta=0.4, 3840 draft
+candidates per step, bf16 logits, neighbour table resident in HBM).  Inputs
+are generated on the device before the timed region; several distinct step
+buffers are rotated so that reads come from HBM rather than from the 256 MB
+last-level cache.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--variant plain|reject|peaked]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "relaxed verifications/sec at V=16384,k=1000 (bf16 logits); % HBM peak"
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_verification(V: int, k: int, logit_bytes: int) -> int:
+    """Both logit rows once, one table row, token, two uniforms, two outputs."""
+    return 2 * V * logit_bytes + 4 * k + 20
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=576)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent"])
+    ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
+    ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
+    ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch from rocprofv3 counters, if known")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for "
+              "how the path would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2410_03355_amd as lantern
+    from synth import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        return 2
+    lantern.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = workloads.CONFIGS[args.workload]
+    delta = 0.0 if args.variant == "reject" else cfg.delta
+    stream = torch.cuda.current_stream()
+
+    # ---- neighbour table: built once on the device, stays resident ----
+    codebook = workloads.make_codebook(cfg, device=dev)
+    lantern.build_knn(codebook, cfg.k)  # warm-up (module load)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    knn = lantern.build_knn(codebook, cfg.k)
+    e1.record()
+    torch.cuda.synchronize()
+    knn_build_ms = e0.elapsed_time(e1)
+
+    # ---- step inputs, resident in HBM before the timed region ----
+    nbuf = max(1, args.buffers)
+    bufs = [workloads.make_step(cfg, step=s, device=dev, variant=args.variant) for s in range(nbuf)]
+    out_acc = [torch.empty(cfg.rows, dtype=torch.int32, device=dev) for _ in range(nbuf)]
+    out_res = [torch.empty(cfg.rows, dtype=torch.int32, device=dev) for _ in range(nbuf)]
+    torch.cuda.synchronize()
+
+    def step(i: int):
+        b = bufs[i % nbuf]
+        lantern.verify(b.target_logits, b.draft_logits, b.draft_tokens, knn, delta, b.uniforms,
+                       out_accept=out_acc[i % nbuf], out_resample=out_res[i % nbuf], stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # events bracket every launch on the stream the kernel runs on
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record(stream)
+        step(i)
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    kernel_ms_avg = sum(kernel_ms) / len(kernel_ms)
+
+    rows = cfg.rows
+    logit_bytes = 2 if cfg.logit_dtype == "bf16" else 4
+    bytes_per_launch = algorithmic_bytes_per_verification(cfg.V, cfg.k, logit_bytes) * rows
+    achieved_gbs = bytes_per_launch / (kernel_ms_avg * 1e-3) / 1e9
+    value = rows * args.steps / wall
+
+    acc_all = torch.stack(out_acc[: min(nbuf, args.steps)])
+    accept_frac = float((acc_all == 1).float().mean().item())
+
+    result = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "verifications/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}/{args.variant}: V={cfg.V} d={cfg.d} k={cfg.k} delta={delta} "
+                        f"rows_per_step={rows} logits={cfg.logit_dtype}",
+            "rows_per_step": rows,
+            "distinct_step_buffers": nbuf,
+            "accepted_fraction": accept_frac,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "verify_fast",
+            "achieved": achieved_gbs,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved_gbs / HBM_PEAK_GBS,
+            "traffic": args.traffic_bytes,
+            "algorithmic_bytes_per_launch": bytes_per_launch,
+            "kernel_ms_avg": kernel_ms_avg,
+        },
+        "knn_build_ms": knn_build_ms,
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle  # CPU baseline leg only
+        threads = min(os.cpu_count() or 1, 16, oracle.max_threads())
+        n_cpu = max(1, min(args.cpu_steps, nbuf))
+        knn_host = knn.cpu().numpy()
+        host = [(b.target_logits.float().cpu().numpy(), b.draft_logits.float().cpu().numpy(),
+                 b.draft_tokens.cpu().numpy(), b.uniforms.cpu().numpy()) for b in bufs[:n_cpu]]
+        c0 = time.perf_counter()
+        mism = 0
+        for i, (tl, dl, tok, un) in enumerate(host):
+            acc, res, _ = oracle.verify(tl, dl, tok, knn_host, cfg.k, delta, un, threads=threads,
+                                        want_diag=False)
+            if args.steps > i:
+                mism += int((acc != out_acc[i].cpu().numpy()).sum() + (res != out_res[i].cpu().numpy()).sum())
+        c1 = time.perf_counter()
+        # the comparison above is outside what is timed below: time the oracle alone on the same rows
+        c0 = time.perf_counter()
+        for tl, dl, tok, un in host:
+            oracle.verify(tl, dl, tok, knn_host, cfg.k, delta, un, threads=threads, want_diag=False)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": n_cpu * rows / (c1 - c0),
+            "unit": "verifications/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"{n_cpu} step(s) of {rows} rows of the same workload, rows split over "
+                      f"{threads} threads",
+            "mismatches_vs_gpu": mism,
+        }
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

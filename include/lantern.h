@@ -1,0 +1,160 @@
+/*
+ * lantern.h - C ABI of the MI355X (gfx950) library for LANTERN's relaxed
+ * speculative-decoding verification (arXiv 2410.03355).
+ *
+ * Two operations:
+ *   lantern_build_knn  the latent-space neighbour table B_k of the VQ codebook
+ *                      (Section 4.2; Algorithm 2, "Precompute B_k" part)
+ *   lantern_verify     one relaxed verification per row: TVD-bounded
+ *                      neighbourhood A_{k,delta}, acceptance test, residual
+ *                      resampling (Section 4.3; Algorithm 2, inference part;
+ *                      Algorithm 1, the accept / resample branch)
+ *
+ * Naming.  The paper writes p for the drafter and q for the target model.
+ * Other texts use the letters the other way round, so this header uses
+ * neither: arguments are called target_* and draft_*.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller and must stay
+ *     valid until the work enqueued on the stream has finished.  The library
+ *     allocates nothing, frees nothing and keeps no state between calls.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls only enqueue kernels; they do not synchronise.
+ *   - The return value is a lantern_status.  Argument errors are found on the
+ *     host before anything is launched; then nothing is written.
+ *   - Row-level problems that only the device can see (see lantern_verify) are
+ *     reported per row through sentinel outputs, not through the status.
+ */
+#ifndef LANTERN_H
+#define LANTERN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LANTERN_F32 = 0,  /* IEEE binary32                       */
+    LANTERN_BF16 = 1  /* bfloat16 (upper 16 bits of binary32) */
+} lantern_dtype;
+
+typedef enum {
+    LANTERN_OK = 0,
+    LANTERN_E_NULL = -1,      /* a required pointer is NULL                           */
+    LANTERN_E_SHAPE = -2,     /* V<1, d<1, N<0, k<1, k>V, row stride < V, V too large  */
+    LANTERN_E_DTYPE = -3,     /* dtype is not one of lantern_dtype                     */
+    LANTERN_E_DELTA = -4,     /* delta is NaN or negative                              */
+    LANTERN_E_WORKSPACE = -6, /* workspace missing, misaligned or too small            */
+    LANTERN_E_DEVICE = -7     /* a HIP call failed (launch error, no device)           */
+} lantern_status;
+
+typedef enum {
+    LANTERN_METRIC_L2 = 0,    /* squared l2 distance, the paper's choice (Section 5.1) */
+    LANTERN_METRIC_COSINE = 1 /* cosine similarity (ablation, Section 5.3.1)           */
+} lantern_metric;
+
+/* Largest vocabulary lantern_verify accepts (bitmask of one row must fit in LDS). */
+#define LANTERN_MAX_VOCAB (1 << 20)
+
+/*
+ * Bytes of device workspace lantern_build_knn needs for this problem, or 0 if
+ * the arguments are invalid.  The workspace holds approximate distances for a
+ * block of query rows plus candidate lists; its contents are scratch.
+ */
+size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k);
+
+/*
+ * Neighbour table of the codebook (Section 4.2: "B_k(x): the k nearest tokens
+ * to x in latent space, including x itself"; Algorithm 2, precompute part).
+ *
+ *   codebook   [V, d] row-major, dtype cb_dtype, device memory, 16-byte aligned
+ *   out_knn    [V, k] row-major int32, device memory.  Row i holds i itself in
+ *              slot 0, then the k-1 other tokens in increasing distance.  The
+ *              distance that decides the order is the squared l2 distance
+ *              evaluated in fp64 as sum over coordinates, in index order, of
+ *              (c_i[t]-c_j[t])^2 with every operation rounded separately;
+ *              equal distances are ordered by the lower token index.
+ *   workspace  device memory of at least lantern_build_knn_workspace_bytes,
+ *              256-byte aligned
+ *
+ * An approximate distance from a matrix-core contraction only pre-selects
+ * candidates; the order written is always the fp64 one, so the result does
+ * not depend on the contraction's rounding.
+ * Errors: E_NULL, E_SHAPE (k>V, V<1, d<1, k<1), E_DTYPE, E_WORKSPACE, E_DEVICE.
+ */
+int lantern_build_knn(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
+                      int32_t* out_knn, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* As lantern_build_knn with a choice of metric. */
+int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
+                             int metric, int32_t* out_knn, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/*
+ * N independent relaxed verifications (Section 4.3, final rule):
+ *   t = softmax(target row), g = softmax(draft row), xt = draft token
+ *   walk knn[xt, 0..k) nearest first; a neighbour x != xt is taken while the
+ *   total variation distance after moving t(x) onto xt stays strictly below
+ *   delta; the first that does not fit ends the walk; xt is always taken
+ *   mass = sum of t over the taken set A
+ *   accept iff u_accept * g(xt) < mass          (i.e. u < min(1, mass/g(xt)))
+ *   else resample from max(0, t_A - g) normalised, where t_A is t with mass at
+ *   xt and zero on A \ {xt}: the first token, in index order, whose cumulative
+ *   residual exceeds u_resample * (total residual)
+ *
+ *   target_logits, draft_logits  [N, V] with row_stride_elems elements between
+ *                rows (>= V), dtype logits_dtype.  -inf marks a filtered token.
+ *   draft_tokens [N] int32
+ *   knn          [V, k] int32 neighbour table (entries of a row distinct)
+ *   delta        TVD bound, >= 0.  delta = 0 or k = 1 gives standard
+ *                speculative acceptance min(1, t(xt)/g(xt)).
+ *   uniforms     [N, 2] float32 in [0,1): column 0 acceptance draw, column 1
+ *                resampling draw.  The library draws no random numbers.
+ *   out_accept   [N] int32: 1 accepted, 0 rejected
+ *   out_resample [N] int32: resampled token when rejected, -1 when accepted
+ *
+ * Rows the device finds unusable - draft token or a table entry outside
+ * [0,V), a NaN or +inf logit, or no finite logit - get out_accept = -1 and
+ * out_resample = -1; other rows are unaffected.
+ *
+ * Decisions are exact with respect to fp64 evaluation of the rule above: a
+ * fast fp32 pass settles every row whose comparisons clear a proven rounding
+ * margin, and the remaining rows (and all rejected rows, whose inverse-CDF
+ * bucket cannot be settled in fp32) are evaluated in fp64.
+ *
+ * Errors: E_NULL, E_SHAPE (also V > LANTERN_MAX_VOCAB), E_DTYPE, E_DELTA,
+ * E_DEVICE.  N = 0 is valid and does nothing.
+ */
+int lantern_verify(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                   int N, int V, int64_t row_stride_elems, const int32_t* draft_tokens,
+                   const int32_t* knn, int k, float delta, const float* uniforms,
+                   int32_t* out_accept, int32_t* out_resample, void* hip_stream);
+
+/*
+ * lantern_verify plus optional per-row diagnostics (each pointer may be NULL):
+ *   out_accept_prob [N] float  min(1, mass/g(xt))
+ *   out_mass        [N] float  sum of t over A_{k,delta}(xt)
+ *   out_g_tok       [N] float  g(xt)
+ *   out_a_size      [N] int32  number of table slots taken into A
+ *   out_path        [N] int32  0: settled by the fp32 pass, 1: evaluated in fp64
+ * Unusable rows get NaN / -1 in the diagnostics.
+ */
+int lantern_verify_ex(const void* target_logits, const void* draft_logits,
+                      lantern_dtype logits_dtype, int N, int V, int64_t row_stride_elems,
+                      const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                      const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                      float* out_accept_prob, float* out_mass, float* out_g_tok,
+                      int32_t* out_a_size, int32_t* out_path, void* hip_stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* lantern_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int lantern_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LANTERN_H */

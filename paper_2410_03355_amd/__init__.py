@@ -1,0 +1,10 @@
+"""MI355X-native relaxed speculative-decoding verification (LANTERN, arXiv 2410.03355).
+
+Python names mirror the C ABI of include/lantern.h: build_knn, verify,
+verify_ex.  The work is done by hand-written gfx950 kernels in liblantern.so.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, MAX_VOCAB, METRIC_COSINE, METRIC_L2, EXPORTS, LanternError, build_knn,
+    knn_workspace_bytes, load, status_string, verify, verify_ex,
+)
+from .build import LIB_PATH, build  # noqa: F401

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of liblantern.so: argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the
+verification path runs in the library's kernels.  There is no CPU fallback: if
+the library is missing, load() raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+F32, BF16 = 0, 1
+METRIC_L2, METRIC_COSINE = 0, 1
+MAX_VOCAB = 1 << 20
+
+OK = 0
+E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -7
+
+EXPORTS = (
+    "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
+    "lantern_verify", "lantern_verify_ex", "lantern_status_string", "lantern_version",
+)
+
+_lib = None
+
+
+class LanternError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2410_03355_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    lib.lantern_build_knn_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.lantern_build_knn_workspace_bytes.restype = sz
+    lib.lantern_build_knn.argtypes = [vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.lantern_build_knn.restype = i32
+    lib.lantern_build_knn_metric.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.lantern_build_knn_metric.restype = i32
+    lib.lantern_verify.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp, vp]
+    lib.lantern_verify.restype = i32
+    lib.lantern_verify_ex.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp,
+                                      vp, vp, vp, vp, vp, vp]
+    lib.lantern_verify_ex.restype = i32
+    lib.lantern_status_string.argtypes = [i32]
+    lib.lantern_status_string.restype = ctypes.c_char_p
+    lib.lantern_version.argtypes = []
+    lib.lantern_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().lantern_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16 expected")
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _need_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must live in device memory")
+
+
+def knn_workspace_bytes(cb_dtype: int, V: int, d: int, k: int) -> int:
+    return int(load().lantern_build_knn_workspace_bytes(cb_dtype, V, d, k))
+
+
+def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None) -> torch.Tensor:
+    """lantern_build_knn on a [V, d] device tensor; returns int32 [V, k] on the device."""
+    lib = load()
+    _need_cuda(codebook)
+    if codebook.dim() != 2 or not codebook.is_contiguous():
+        raise ValueError("codebook must be a contiguous [V, d] tensor")
+    V, d = codebook.shape
+    code = _dtype_code(codebook)
+    nbytes = knn_workspace_bytes(code, V, d, k)
+    if nbytes == 0:
+        raise LanternError(E_SHAPE, "lantern_build_knn_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=codebook.device)
+    out = torch.empty((V, k), dtype=torch.int32, device=codebook.device)
+    rc = lib.lantern_build_knn_metric(codebook.data_ptr(), code, V, d, k,
+                                      {"l2": METRIC_L2, "cosine": METRIC_COSINE}[metric],
+                                      out.data_ptr(), ws.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_build_knn")
+    ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    return out
+
+
+def _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms):
+    _need_cuda(target_logits, draft_logits, draft_tokens, knn, uniforms)
+    if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape:
+        raise ValueError("logits must be two [N, V] tensors of equal shape")
+    if target_logits.dtype != draft_logits.dtype:
+        raise TypeError("target and draft logits must share a dtype")
+    if target_logits.stride(1) != 1 or draft_logits.stride(1) != 1 or \
+            target_logits.stride(0) != draft_logits.stride(0):
+        raise ValueError("logit rows must be dense and both tensors must share the row stride")
+    N, V = target_logits.shape
+    if draft_tokens.dtype != torch.int32 or knn.dtype != torch.int32 or uniforms.dtype != torch.float32:
+        raise TypeError("draft_tokens and knn must be int32, uniforms float32")
+    if draft_tokens.numel() != N or uniforms.numel() != 2 * N or knn.dim() != 2 or knn.shape[0] != V:
+        raise ValueError("shape mismatch between logits, tokens, uniforms and the table")
+    if not (draft_tokens.is_contiguous() and knn.is_contiguous() and uniforms.is_contiguous()):
+        raise ValueError("draft_tokens, knn and uniforms must be contiguous")
+    return N, V, int(knn.shape[1])
+
+
+def verify(target_logits, draft_logits, draft_tokens, knn, delta: float, uniforms,
+           out_accept=None, out_resample=None, stream=None):
+    """lantern_verify; returns (accept int32[N], resample int32[N]) device tensors."""
+    lib = load()
+    N, V, k = _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms)
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev) if out_accept is None else out_accept
+    res = torch.empty(N, dtype=torch.int32, device=dev) if out_resample is None else out_resample
+    rc = lib.lantern_verify(target_logits.data_ptr(), draft_logits.data_ptr(),
+                            _dtype_code(target_logits), N, V, target_logits.stride(0) if N > 1 else V,
+                            draft_tokens.data_ptr(), knn.data_ptr(), k, float(delta),
+                            uniforms.data_ptr(), acc.data_ptr(), res.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify")
+    return acc, res
+
+
+def verify_ex(target_logits, draft_logits, draft_tokens, knn, delta: float, uniforms, stream=None):
+    """lantern_verify_ex; returns a dict of device tensors with all diagnostics."""
+    lib = load()
+    N, V, k = _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms)
+    dev = target_logits.device
+    out = {
+        "accept": torch.empty(N, dtype=torch.int32, device=dev),
+        "resample": torch.empty(N, dtype=torch.int32, device=dev),
+        "accept_prob": torch.empty(N, dtype=torch.float32, device=dev),
+        "mass": torch.empty(N, dtype=torch.float32, device=dev),
+        "g_tok": torch.empty(N, dtype=torch.float32, device=dev),
+        "a_size": torch.empty(N, dtype=torch.int32, device=dev),
+        "path": torch.empty(N, dtype=torch.int32, device=dev),
+    }
+    rc = lib.lantern_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(),
+                               _dtype_code(target_logits), N, V,
+                               target_logits.stride(0) if N > 1 else V, draft_tokens.data_ptr(),
+                               knn.data_ptr(), k, float(delta), uniforms.data_ptr(),
+                               out["accept"].data_ptr(), out["resample"].data_ptr(),
+                               out["accept_prob"].data_ptr(), out["mass"].data_ptr(),
+                               out["g_tok"].data_ptr(), out["a_size"].data_ptr(),
+                               out["path"].data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_ex")
+    return out

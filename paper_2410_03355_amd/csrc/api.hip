@@ -1,0 +1,122 @@
+// C ABI of the library: argument validation on the host, then kernel launches.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "knn_args.h"
+#include "lantern.h"
+#include "verify_args.h"
+
+namespace {
+
+bool dtype_ok(int dt) { return dt == LANTERN_F32 || dt == LANTERN_BF16; }
+
+int verify_impl(const void* target_logits, const void* draft_logits, int logits_dtype, int N, int V,
+                int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
+                float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                float* out_accept_prob, float* out_mass, float* out_g_tok, int32_t* out_a_size,
+                int32_t* out_path, void* hip_stream) {
+    if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
+    if (N < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
+        return LANTERN_E_SHAPE;
+    if (!(delta >= 0.0f)) return LANTERN_E_DELTA;  // also rejects NaN
+    if (N == 0) return LANTERN_OK;
+    if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms || !out_accept ||
+        !out_resample)
+        return LANTERN_E_NULL;
+    lantern::VerifyArgs a;
+    a.target = target_logits;
+    a.draft = draft_logits;
+    a.N = N;
+    a.V = V;
+    a.stride = row_stride_elems;
+    a.tokens = draft_tokens;
+    a.knn = knn;
+    a.k = k;
+    a.delta = delta;
+    a.uniforms = uniforms;
+    a.out_accept = out_accept;
+    a.out_resample = out_resample;
+    a.out_prob = out_accept_prob;
+    a.out_mass = out_mass;
+    a.out_gtok = out_g_tok;
+    a.out_asize = out_a_size;
+    a.out_path = out_path;
+    const hipError_t e = lantern::launch_verify(a, logits_dtype, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lantern_verify(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                   int N, int V, int64_t row_stride_elems, const int32_t* draft_tokens,
+                   const int32_t* knn, int k, float delta, const float* uniforms,
+                   int32_t* out_accept, int32_t* out_resample, void* hip_stream) {
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+                       draft_tokens, knn, k, delta, uniforms, out_accept, out_resample, nullptr,
+                       nullptr, nullptr, nullptr, nullptr, hip_stream);
+}
+
+int lantern_verify_ex(const void* target_logits, const void* draft_logits,
+                      lantern_dtype logits_dtype, int N, int V, int64_t row_stride_elems,
+                      const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                      const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                      float* out_accept_prob, float* out_mass, float* out_g_tok,
+                      int32_t* out_a_size, int32_t* out_path, void* hip_stream) {
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+                       draft_tokens, knn, k, delta, uniforms, out_accept, out_resample,
+                       out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
+}
+
+size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k) {
+    if (!dtype_ok((int)cb_dtype) || V < 1 || d < 1 || k < 1 || k > V) return 0;
+    return lantern::knn_workspace_bytes(V, d, k);
+}
+
+int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
+                             int metric, int32_t* out_knn, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+    if (!dtype_ok((int)cb_dtype)) return LANTERN_E_DTYPE;
+    if (V < 1 || d < 1 || k < 1 || k > V) return LANTERN_E_SHAPE;
+    if (metric != LANTERN_METRIC_L2 && metric != LANTERN_METRIC_COSINE) return LANTERN_E_SHAPE;
+    if (!codebook || !out_knn) return LANTERN_E_NULL;
+    const size_t need = lantern::knn_workspace_bytes(V, d, k);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return LANTERN_E_WORKSPACE;
+    lantern::KnnArgs a;
+    a.codebook = codebook;
+    a.cb_dtype = (int)cb_dtype;
+    a.V = V;
+    a.d = d;
+    a.k = k;
+    a.metric = metric;
+    a.out = out_knn;
+    a.workspace = workspace;
+    const hipError_t e = lantern::launch_build_knn(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
+int lantern_build_knn(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
+                      int32_t* out_knn, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return lantern_build_knn_metric(codebook, cb_dtype, V, d, k, LANTERN_METRIC_L2, out_knn,
+                                    workspace, workspace_bytes, hip_stream);
+}
+
+const char* lantern_status_string(int status) {
+    switch (status) {
+        case LANTERN_OK: return "ok";
+        case LANTERN_E_NULL: return "null pointer argument";
+        case LANTERN_E_SHAPE: return "invalid shape argument";
+        case LANTERN_E_DTYPE: return "unsupported dtype";
+        case LANTERN_E_DELTA: return "delta is NaN or negative";
+        case LANTERN_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LANTERN_E_DEVICE: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int lantern_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,319 @@
+// Codebook neighbour table B_k (Section 4.2; Algorithm 2, precompute part).
+//
+// Pipeline per block of query rows:
+//   1. approximate keys (fp32) for every pair (query i, token j) into the
+//      workspace: squared l2 distance, or minus cosine similarity
+//   2. per row: radix-select the (k-1+pad) smallest approximate keys, recompute
+//      the survivors' keys in fp64 exactly as the definition states (coordinate
+//      order, every operation rounded separately), sort them by (key, index)
+//      and emit the first k-1 after the token itself.  A row is emitted only if
+//      the approximation's error bound proves no discarded token could belong
+//      to it; otherwise it is flagged.
+//   3. flagged rows: fp64 keys for all V tokens and ranking by counting.
+// The written order is therefore always the fp64 one.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "device_utils.h"
+#include "knn_args.h"
+
+namespace lantern {
+
+constexpr int ROW_BLOCK = 2048;   // query rows per pass through the workspace
+constexpr int CAND_CAP = 4096;    // candidate slots per row held in LDS
+constexpr int SLOW_WGS = 128;     // workgroups (and fp64 row buffers) of the exact pass
+
+__host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct KnnLayout {
+    size_t norms, nmax, dist, flags, slow, total;
+    int row_block;
+};
+
+static KnnLayout knn_layout(int V) {
+    KnnLayout L;
+    L.row_block = V < ROW_BLOCK ? V : ROW_BLOCK;
+    size_t off = 0;
+    L.norms = off; off = align_up(off + sizeof(float) * (size_t)V, 256);
+    L.nmax = off;  off = align_up(off + 256, 256);
+    L.dist = off;  off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
+    L.flags = off; off = align_up(off + sizeof(int) * (size_t)L.row_block, 256);
+    L.slow = off;  off = align_up(off + sizeof(double) * (size_t)SLOW_WGS * V, 256);
+    L.total = off;
+    return L;
+}
+
+size_t knn_workspace_bytes(int V, int, int) { return knn_layout(V).total; }
+
+template <typename CT> __device__ __forceinline__ float cb_f32(const CT* p, int64_t i);
+template <> __device__ __forceinline__ float cb_f32<float>(const float* p, int64_t i) { return p[i]; }
+template <> __device__ __forceinline__ float cb_f32<uint16_t>(const uint16_t* p, int64_t i) {
+    return __uint_as_float(static_cast<uint32_t>(p[i]) << 16);
+}
+
+// order-preserving map float -> uint32 (ascending)
+__device__ __forceinline__ uint32_t ord_key(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float ord_inv(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// ---- exact fp64 key of the pair (i, j): the definition, operation by operation ----
+template <typename CT>
+__device__ double exact_key(const CT* cb, int d, int i, int j, int metric) {
+#pragma clang fp contract(off)
+    const CT* ci = cb + (int64_t)i * d;
+    const CT* cj = cb + (int64_t)j * d;
+    if (metric == 0) {
+        double acc = 0.0;
+        for (int t = 0; t < d; ++t) {
+            const double diff = (double)cb_f32<CT>(ci, t) - (double)cb_f32<CT>(cj, t);
+            const double sq = diff * diff;
+            acc = acc + sq;
+        }
+        return acc;
+    }
+    double ni = 0.0, nj = 0.0, dot = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double x = (double)cb_f32<CT>(ci, t);
+        const double y = (double)cb_f32<CT>(cj, t);
+        const double xx = x * x;
+        const double yy = y * y;
+        const double xy = x * y;
+        ni = ni + xx;
+        nj = nj + yy;
+        dot = dot + xy;
+    }
+    ni = sqrt(ni);
+    nj = sqrt(nj);
+    const double den = ni * nj;
+    return -(dot / den);
+}
+
+// ---- stage 1 (generic shapes): approximate keys by direct evaluation in fp32 ----
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_dist_direct(const CT* cb, int V, int d, int r0, int metric,
+                                                      float* dist) {
+    const int row = blockIdx.y;
+    const int i = r0 + row;
+    const int j = blockIdx.x * NT + threadIdx.x;
+    if (j >= V) return;
+    const CT* ci = cb + (int64_t)i * d;
+    const CT* cj = cb + (int64_t)j * d;
+    float key;
+    if (metric == 0) {
+        float acc = 0.f;
+        for (int t = 0; t < d; ++t) {
+            const float diff = cb_f32<CT>(ci, t) - cb_f32<CT>(cj, t);
+            acc = fmaf(diff, diff, acc);
+        }
+        key = acc;
+    } else {
+        float ni = 0.f, nj = 0.f, dot = 0.f;
+        for (int t = 0; t < d; ++t) {
+            const float x = cb_f32<CT>(ci, t), y = cb_f32<CT>(cj, t);
+            ni = fmaf(x, x, ni);
+            nj = fmaf(y, y, nj);
+            dot = fmaf(x, y, dot);
+        }
+        key = -dot / sqrtf(ni * nj);
+    }
+    dist[(int64_t)row * V + j] = key;
+}
+
+// ---- stage 2: select, re-rank exactly, emit ----
+struct SelectShared {
+    double key[CAND_CAP];
+    int idx[CAND_CAP];
+    unsigned hist[256];
+    int digit;
+    int remaining;
+    int count;
+};
+
+// err_rel, err_abs: |approximate key - exact key| <= err_rel * |exact key| + err_abs
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
+                                                 const float* dist, float err_rel, float err_abs,
+                                                 int32_t* out, int* flags) {
+    __shared__ SelectShared sh;
+    const int row = blockIdx.x;
+    const int i = r0 + row;
+    const int tid = threadIdx.x;
+    const float* drow = dist + (int64_t)row * V;
+    int32_t* orow = out + (int64_t)i * k;
+    const int need = k - 1;
+    if (tid == 0) {
+        orow[0] = i;
+        flags[row] = 0;
+    }
+    if (need == 0) return;
+    const int pad = 32 + need / 32;
+    const int want = min(V - 1, need + pad);
+    if (want > CAND_CAP) {
+        if (tid == 0) flags[row] = 1;
+        return;
+    }
+
+    // radix select: key of the want-th smallest approximate key among j != i
+    uint32_t prefix = 0;
+    int remaining = want;
+    for (int pass = 3; pass >= 0; --pass) {
+        const int shift = pass * 8;
+        const uint32_t himask = pass == 3 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        sh.hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < V; j += NT) {
+            if (j == i) continue;
+            const uint32_t key = ord_key(drow[j]);
+            if ((key & himask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int cum = 0, b = 0;
+            for (; b < 255; ++b) {
+                const int h = (int)sh.hist[b];
+                if (cum + h >= remaining) break;
+                cum += h;
+            }
+            sh.digit = b;
+            sh.remaining = remaining - cum;
+        }
+        __syncthreads();
+        prefix |= (uint32_t)sh.digit << shift;
+        remaining = sh.remaining;
+        __syncthreads();
+    }
+    const uint32_t thr_key = prefix;
+    const float thr = ord_inv(thr_key);
+
+    // compaction of every j != i with approximate key <= threshold
+    if (tid == 0) sh.count = 0;
+    __syncthreads();
+    for (int j = tid; j < V; j += NT) {
+        if (j == i) continue;
+        if (ord_key(drow[j]) <= thr_key) {
+            const int slot = atomicAdd(&sh.count, 1);
+            if (slot < CAND_CAP) sh.idx[slot] = j;
+        }
+    }
+    __syncthreads();
+    const int count = sh.count;
+    if (count > CAND_CAP) {  // too many ties at the threshold
+        if (tid == 0) flags[row] = 1;
+        return;
+    }
+    int P = 1;
+    while (P < count) P <<= 1;
+    for (int c = tid; c < P; c += NT) {
+        if (c < count) {
+            sh.key[c] = exact_key<CT>(cb, d, i, sh.idx[c], metric);
+        } else {
+            sh.key[c] = INFINITY;
+            sh.idx[c] = INT_MAX;
+        }
+    }
+    // bitonic sort ascending by (key, idx)
+    for (int size = 2; size <= P; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = tid; t < (P >> 1); t += NT) {
+                const int l = 2 * t - (t & (stride - 1));
+                const int r = l + stride;
+                const bool up = (l & size) == 0;
+                const double kl = sh.key[l], kr = sh.key[r];
+                const int il = sh.idx[l], ir = sh.idx[r];
+                const bool l_after_r = (kl > kr) || (kl == kr && il > ir);
+                if (l_after_r == up) {
+                    sh.key[l] = kr; sh.key[r] = kl;
+                    sh.idx[l] = ir; sh.idx[r] = il;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // proof that no discarded token belongs to the row: every discarded j has an
+    // approximate key above thr, hence an exact key above thr - err; the last
+    // token taken must lie at or below that.
+    bool ok = true;
+    if (count < V - 1) {
+        const double last = sh.key[need - 1];
+        const double num = (double)thr - (double)err_abs;
+        const double floor_discarded = num - 1.01 * (double)err_rel * fabs(num);
+        ok = last <= floor_discarded;
+    }
+    if (!ok) {
+        if (tid == 0) flags[row] = 1;
+        return;
+    }
+    for (int s = tid; s < need; s += NT) orow[1 + s] = sh.idx[s];
+}
+
+// ---- stage 3: flagged rows, all V keys in fp64, rank by counting ----
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d, int k, int metric, int r0,
+                                                     int rows, const int* flags, double* bufs,
+                                                     int32_t* out) {
+    const int tid = threadIdx.x;
+    double* buf = bufs + (int64_t)blockIdx.x * V;
+    const int need = k - 1;
+    for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+        if (!flags[row]) continue;  // uniform
+        const int i = r0 + row;
+        __syncthreads();
+        for (int j = tid; j < V; j += NT)
+            buf[j] = (j == i) ? INFINITY : exact_key<CT>(cb, d, i, j, metric);
+        __threadfence_block();
+        __syncthreads();
+        int32_t* orow = out + (int64_t)i * k;
+        for (int j = tid; j < V; j += NT) {
+            if (j == i) continue;
+            const double kj = buf[j];
+            int rank = 0;
+            for (int o = 0; o < V; ++o) {
+                const double ko = buf[o];
+                rank += (ko < kj || (ko == kj && o < j)) ? 1 : 0;
+            }
+            if (rank < need) orow[1 + rank] = j;
+        }
+    }
+}
+
+template <typename CT>
+static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
+    const KnnLayout L = knn_layout(a.V);
+    unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+    float* dist = reinterpret_cast<float*>(ws + L.dist);
+    int* flags = reinterpret_cast<int*>(ws + L.flags);
+    double* slow = reinterpret_cast<double*>(ws + L.slow);
+    const CT* cb = static_cast<const CT*>(a.codebook);
+    // direct fp32 evaluation: (d + 4) roundings of at most 2^-23 each, relative to the key for
+    // squared l2 (a sum of squares); absolute, against |cos| <= 1, for the cosine key
+    const float gamma = (float)(a.d + 8) * 1.1920929e-7f;
+    const float err_rel = a.metric == 0 ? gamma : 0.f;
+    const float err_abs = a.metric == 0 ? 0.f : 2.f * gamma;
+    for (int r0 = 0; r0 < a.V; r0 += L.row_block) {
+        const int rows = (a.V - r0) < L.row_block ? (a.V - r0) : L.row_block;
+        hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
+                           cb, a.V, a.d, r0, a.metric, dist);
+        hipLaunchKernelGGL((knn_select<CT>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k, a.metric,
+                           r0, dist, err_rel, err_abs, a.out, flags);
+        const int wgs = rows < SLOW_WGS ? rows : SLOW_WGS;
+        hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
+                           a.metric, r0, rows, flags, slow, a.out);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream) {
+    if (a.cb_dtype == 0) return build_typed<float>(a, stream);
+    return build_typed<uint16_t>(a, stream);
+}
+
+}  // namespace lantern

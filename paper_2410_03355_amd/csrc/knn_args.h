@@ -1,0 +1,24 @@
+// Argument block and host entry of the neighbour-table build.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lantern {
+
+struct KnnArgs {
+    const void* codebook;  // [V, d]
+    int cb_dtype;          // 0 fp32, 1 bf16
+    int V;
+    int d;
+    int k;
+    int metric;            // 0 squared l2, 1 cosine
+    int32_t* out;          // [V, k]
+    void* workspace;
+};
+
+size_t knn_workspace_bytes(int V, int d, int k);
+hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream);
+
+}  // namespace lantern

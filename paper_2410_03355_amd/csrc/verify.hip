@@ -1,0 +1,639 @@
+// Relaxed-acceptance verification (Section 4.3; Algorithm 2, inference part;
+// Algorithm 1, accept / resample branch) for gfx950.
+//
+// One workgroup per row, two code paths inside the same launch:
+//   fast path   fp32.  Streams the target and draft rows from HBM once with
+//               16-byte loads, keeps the raw target row in LDS, gathers the
+//               draft token's k neighbours from LDS, prefix-scans them and
+//               takes the TVD cut and the acceptance test.  Each comparison
+//               carries a rounding margin; a row is settled here only when it
+//               is accepted and every comparison it took cleared its margin.
+//   exact path  fp64.  The workgroup of a row the fast path did not settle
+//               (ambiguous comparison, unusable input, every rejected row)
+//               re-evaluates it: same rule, then the residual and its
+//               inverse CDF.
+// Shapes the fast path does not cover (rows not 16-byte aligned, V not a
+// multiple of the vector width, rows beyond the register budget) run the
+// exact path for every row (kernel verify_exact).
+// Letters: t = target probability (the paper's q), g = drafter probability
+// (the paper's p), xt = draft token.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "device_utils.h"
+#include "verify_args.h"
+
+namespace lantern {
+
+constexpr float LOG2E_F = 1.44269504088896340736f;
+
+// ---- rounding margins of the fp32 pass -------------------------------------
+// One unnormalised term e = 2^((l - M) * log2e): the subtraction, the product
+// with the rounded constant and v_exp_f32 give a relative error below
+// (2.3 |l - M| + 2) * 2^-24.  Terms with l - M < -32 are below e^-32 each, so
+// bounding |l - M| by 32 costs at most V * 1.3e-14 relative to the sum (>= 1).
+// Sums are trees of depth <= 32 (per thread, wave butterfly, across waves,
+// rescale), adding 32 * 2^-24.  TAU_CUT and TAU_ACC cover one sum against
+// another with both bounds, with about 30 % headroom.
+constexpr float TAU_CUT = 2.0e-5f;
+constexpr float TAU_ACC = 3.0e-5f;
+// v_exp_f32 flushes results below 2^-126; absolute slack for products of such
+// terms with sums bounded by V.
+constexpr float ABS_SLACK = 1.0e-30f;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read once: non-temporal, so the streamed rows
+// do not evict the neighbour table from the caches.
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <typename LT>
+struct Lane;
+
+template <>
+struct Lane<float> {
+    static constexpr int EPV = 4;  // elements per 16-byte vector
+    static constexpr uint32_t NEG_INF_WORD = 0xFF800000u;
+    __device__ static __forceinline__ float get(const uint4& v, int e) {
+        const uint32_t w = e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+        return __uint_as_float(w);
+    }
+    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
+        return reinterpret_cast<const float*>(row)[x];
+    }
+    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
+        return reinterpret_cast<const float*>(row)[x];
+    }
+};
+
+template <>
+struct Lane<uint16_t> {  // bfloat16 storage
+    static constexpr int EPV = 8;
+    static constexpr uint32_t NEG_INF_WORD = 0xFF80FF80u;
+    __device__ static __forceinline__ float get(const uint4& v, int e) {
+        const int wi = e >> 1;
+        const uint32_t w = wi == 0 ? v.x : wi == 1 ? v.y : wi == 2 ? v.z : v.w;
+        return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
+    }
+    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
+    }
+};
+
+// LDS layout of verify_fast after the raw row
+struct FastShared {
+    float wmax_t[NW], wsum_t[NW], wmax_g[NW], wsum_g[NW];
+    float wtot[NW];       // per-wave totals of the neighbour scan
+    float w_s[NW];        // exclusive sum at the wave's first not-passing slot
+    int w_np[NW];         // first slot that does not definitely pass
+    int w_df[NW];         // first slot that definitely fails
+    int w_bad[NW];        // table entry outside [0,V)
+};
+
+template <typename LT>
+__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem);
+
+template <typename LT, int NV>
+__global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
+    using L = Lane<LT>;
+    constexpr int EPV = L::EPV;
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* s_row = smem;
+    const int row_bytes = (a.V * (int)sizeof(LT) + 15) & ~15;
+    FastShared& sh = *reinterpret_cast<FastShared*>(smem + row_bytes);
+
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
+    const int V = a.V;
+    const int k = a.k;
+
+    const int xt = a.tokens[row];
+    const bool tok_ok = (unsigned)xt < (unsigned)V;
+    const int xs = tok_ok ? xt : 0;
+
+    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
+    const LT* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
+    const uint4* tv = reinterpret_cast<const uint4*>(trow);
+    const uint4* gv = reinterpret_cast<const uint4*>(grow);
+    const int nvec = V / EPV;
+
+    // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
+    uint4 T[NV], G[NV];
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int vi = c * NT + tid;
+        if (vi < nvec) {
+            T[c] = load_stream16(tv + vi);
+            G[c] = load_stream16(gv + vi);
+        } else {
+            T[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+            G[c] = T[c];
+        }
+    }
+
+    // first chunk of the table row: 4 consecutive slots per thread
+    const int32_t* nrow = a.knn + (int64_t)xs * k;
+    const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
+    int nb[4];
+    {
+        const int j0 = tid * 4;
+        if (nvec_ok && j0 + 3 < k) {
+            const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
+            nb[0] = q.x; nb[1] = q.y; nb[2] = q.z; nb[3] = q.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
+        }
+    }
+    const float u_acc = a.uniforms[2 * (int64_t)row];
+    const float lg_tok = L::glob(grow, xs);
+
+    // ---- raw target row to LDS, wave-local maxima ----
+    float mt = neg_inf_f(), mg = neg_inf_f();
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int vi = c * NT + tid;
+        if (vi < nvec) reinterpret_cast<uint4*>(s_row)[vi] = T[c];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            mt = fmaxf(mt, L::get(T[c], e));
+            mg = fmaxf(mg, L::get(G[c], e));
+        }
+    }
+    mt = wave_max(mt);
+    mg = wave_max(mg);
+    // a slice that is all -inf contributes nothing; subtracting 0 keeps 2^-inf = 0
+    const float mt_s = (mt == neg_inf_f()) ? 0.f : mt;
+    const float mg_s = (mg == neg_inf_f()) ? 0.f : mg;
+
+    // ---- unnormalised exponentials relative to the wave maximum, summed ----
+    float st = 0.f, sg = 0.f;
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        float et[EPV], eg[EPV];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            et[e] = hw_exp2((L::get(T[c], e) - mt_s) * LOG2E_F);
+            eg[e] = hw_exp2((L::get(G[c], e) - mg_s) * LOG2E_F);
+        }
+#pragma unroll
+        for (int s = EPV / 2; s > 0; s >>= 1)
+#pragma unroll
+            for (int e = 0; e < s; ++e) {
+                et[e] += et[e + s];
+                eg[e] += eg[e + s];
+            }
+        st += et[0];
+        sg += eg[0];
+    }
+    st = wave_sum(st);
+    sg = wave_sum(sg);
+    if (lane == 0) {
+        sh.wmax_t[wave] = mt; sh.wsum_t[wave] = st;
+        sh.wmax_g[wave] = mg; sh.wsum_g[wave] = sg;
+    }
+    __syncthreads();
+
+    float Mt = neg_inf_f(), Mg = neg_inf_f();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        Mt = fmaxf(Mt, sh.wmax_t[w]);
+        Mg = fmaxf(Mg, sh.wmax_g[w]);
+    }
+    float Zt = 0.f, Zg = 0.f;  // sums of 2^((l - M) log2e) over the row; NaN if the row is unusable
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        Zt += sh.wsum_t[w] * hw_exp2((sh.wmax_t[w] - Mt) * LOG2E_F);
+        Zg += sh.wsum_g[w] * hw_exp2((sh.wmax_g[w] - Mg) * LOG2E_F);
+    }
+
+    // ---- neighbourhood walk as a prefix scan over the k table slots ----
+    const float R = a.delta * Zt;               // cut: inclusive sum < delta * Zt
+    const float cut_lo = R * (1.f - TAU_CUT) - ABS_SLACK;
+    const float cut_hi = R * (1.f + TAU_CUT) + ABS_SLACK;
+    float carry = 0.f;
+    int first_np = INT_MAX, first_df = INT_MAX;
+    float s_cut = 0.f;
+    int bad = tok_ok ? 0 : 1;
+
+    for (int base = 0; base < k; base += NT * 4) {
+        const int j0 = base + tid * 4;
+        if (base > 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
+        }
+        float p[4];
+        float run = 0.f;
+        int my_np = INT_MAX, my_df = INT_MAX;
+        bool is_self[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool valid = j0 + q < k;
+            const int n = nb[q];
+            const bool inr = (unsigned)n < (unsigned)V;
+            if (valid && !inr) bad = 1;
+            float e = 0.f;
+            is_self[q] = (n == xt) || !valid;
+            if (valid && inr && n != xt) e = hw_exp2((L::lds(s_row, n) - Mt) * LOG2E_F);
+            run += e;
+            p[q] = run;
+        }
+        const float incl = wave_scan_incl(run);
+        float excl = __shfl_up(incl, 1, WAVE);
+        if (lane == 0) excl = 0.f;
+        if (lane == WAVE - 1) sh.wtot[wave] = incl;
+        __syncthreads();
+        float woff = 0.f, ctot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float v = sh.wtot[w];
+            if (w < wave) woff += v;
+            ctot += v;
+        }
+        const float off = carry + woff + excl;
+        float my_s = 0.f;
+#pragma unroll
+        for (int q = 3; q >= 0; --q) {
+            if (!is_self[q]) {
+                const float I = off + p[q];
+                if (!(I < cut_lo)) { my_np = j0 + q; my_s = off + (q ? p[q - 1] : 0.f); }
+                if (I > cut_hi) my_df = j0 + q;
+            }
+        }
+        // wave-level first not-pass / first definite-fail
+        const int w_np = wave_min(my_np);
+        const int w_df = wave_min(my_df);
+        const unsigned long long owner = __ballot(my_np == w_np && my_np != INT_MAX);
+        float w_s = 0.f;
+        if (owner) w_s = __shfl(my_s, __ffsll((long long)owner) - 1, WAVE);
+        if (lane == 0) { sh.w_np[wave] = w_np; sh.w_df[wave] = w_df; sh.w_s[wave] = w_s; }
+        __syncthreads();
+        if (first_np == INT_MAX) {
+#pragma unroll
+            for (int w = NW - 1; w >= 0; --w) {
+                if (sh.w_np[w] != INT_MAX) { first_np = sh.w_np[w]; s_cut = sh.w_s[w]; }
+                if (sh.w_df[w] != INT_MAX) first_df = sh.w_df[w];
+            }
+        }
+        carry += ctot;
+        if (first_np != INT_MAX) break;  // uniform across the workgroup
+        __syncthreads();                 // wtot / w_np are rewritten by the next chunk
+    }
+    bad = wave_or(bad);
+    if (lane == 0) sh.w_bad[wave] = bad;
+    __syncthreads();
+    bad = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) bad |= sh.w_bad[w];
+
+    if (tid == 0) {
+        const bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
+        const int a_size = (first_np == INT_MAX) ? k : first_np;
+        const float S = (first_np == INT_MAX) ? carry : s_cut;
+        const float e_tx = hw_exp2((L::lds(s_row, xs) - Mt) * LOG2E_F);
+        const float e_gx = hw_exp2((lg_tok - Mg) * LOG2E_F);
+        const float MA = e_tx + S;              // mass * Zt
+        const float lhs = u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
+        const float rhs = MA * Zg;              // mass  * Zt * Zg
+        const bool accept = (lhs + ABS_SLACK) < rhs * (1.f - TAU_ACC);
+        const bool settled = !bad && cut_definite && accept;
+        if (settled) {
+            a.out_accept[row] = 1;
+            a.out_resample[row] = -1;
+            const float mass = MA / Zt;
+            const float gx = e_gx / Zg;
+            if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
+            if (a.out_mass) a.out_mass[row] = mass;
+            if (a.out_gtok) a.out_gtok[row] = gx;
+            if (a.out_asize) a.out_asize[row] = a_size;
+            if (a.out_path) a.out_path[row] = 0;
+        }
+        sh.w_bad[0] = settled ? 1 : 0;
+    }
+    __syncthreads();
+    if (sh.w_bad[0]) return;
+    // not settled in fp32: this workgroup evaluates the row in fp64 (LDS is reused)
+    exact_row<LT>(a, row, smem);
+}
+
+// ---------------------------------------------------------------------------
+// fp64 evaluation of unsettled rows
+// ---------------------------------------------------------------------------
+
+struct ExactShared {
+    double red[NW];
+    double red2[NW];
+    double bcast[4];
+    int ired[NW];
+    int ibcast[2];
+};
+
+__device__ __forceinline__ double block_sum(double v, double* red, int tid) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    return s;
+}
+
+__device__ __forceinline__ double block_max(double v, double* red, int tid) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    double s = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) s = fmax(s, red[w]);
+    return s;
+}
+
+__device__ __forceinline__ int block_min_i(int v, int* red, int tid) {
+    v = wave_min(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    int s = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) s = min(s, red[w]);
+    return s;
+}
+
+__device__ __forceinline__ int block_or_i(int v, int* red, int tid) {
+    v = wave_or(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    int s = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s |= red[w];
+    return s;
+}
+
+// Inclusive prefix sum over the workgroup in thread order; *total gets the sum.
+__device__ __forceinline__ double block_scan_incl(double v, double* red, int tid, double* total) {
+    const double incl = wave_scan_incl(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == WAVE - 1) red[tid >> 6] = incl;
+    __syncthreads();
+    double off = 0.0, tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const double x = red[w];
+        if (w < (tid >> 6)) off += x;
+        tot += x;
+    }
+    *total = tot;
+    return off + incl;
+}
+
+// Evaluates one row in fp64 with the whole workgroup.  smem: dynamic LDS of at
+// least exact_lds_bytes(V); its previous contents are dead.
+template <typename LT>
+__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
+    using L = Lane<LT>;
+    ExactShared& sh = *reinterpret_cast<ExactShared*>(smem);
+    uint32_t* mask = reinterpret_cast<uint32_t*>(smem + ((sizeof(ExactShared) + 15) & ~size_t(15)));
+
+    const int tid = threadIdx.x;
+    const int V = a.V;
+    const int k = a.k;
+    const void* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
+    const void* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
+    const int xt = a.tokens[row];
+    const double delta = (double)a.delta;
+    const double u_acc = (double)a.uniforms[2 * (int64_t)row];
+    const double u_res = (double)a.uniforms[2 * (int64_t)row + 1];
+
+    // ---- usability: token and table entries in range, logits free of NaN / +inf ----
+    int bad = ((unsigned)xt < (unsigned)V) ? 0 : 1;
+    const int32_t* nrow = a.knn + (int64_t)(bad ? 0 : xt) * k;
+    if (!bad)
+        for (int j = tid; j < k; j += NT)
+            if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
+    double mt = -INFINITY, mg = -INFINITY;
+    for (int x = tid; x < V; x += NT) {
+        const double lt = (double)L::glob(trow, x);
+        const double lg = (double)L::glob(grow, x);
+        if (isnan(lt) || isnan(lg) || lt == INFINITY || lg == INFINITY) bad = 1;
+        mt = fmax(mt, lt);
+        mg = fmax(mg, lg);
+    }
+    mt = block_max(mt, sh.red, tid);
+    mg = block_max(mg, sh.red2, tid);
+    if (mt == -INFINITY || mg == -INFINITY) bad = 1;
+    bad = block_or_i(bad, sh.ired, tid);
+    if (bad) {
+        if (tid == 0) {
+            a.out_accept[row] = -1;
+            a.out_resample[row] = -1;
+            if (a.out_prob) a.out_prob[row] = NAN;
+            if (a.out_mass) a.out_mass[row] = NAN;
+            if (a.out_gtok) a.out_gtok[row] = NAN;
+            if (a.out_asize) a.out_asize[row] = -1;
+            if (a.out_path) a.out_path[row] = 1;
+        }
+        return;
+    }
+
+    // ---- softmax normalisers ----
+    double zt = 0.0, zg = 0.0;
+    for (int x = tid; x < V; x += NT) {
+        zt += exp((double)L::glob(trow, x) - mt);
+        zg += exp((double)L::glob(grow, x) - mg);
+    }
+    zt = block_sum(zt, sh.red, tid);
+    zg = block_sum(zg, sh.red2, tid);
+
+    // ---- nearest-first walk: inclusive sums of t over the table slots ----
+    double carry = 0.0;
+    int a_size = k;
+    double S = 0.0;
+    bool cut_found = false;
+    for (int base = 0; base < k && !cut_found; base += NT) {
+        const int j = base + tid;
+        const bool valid = j < k;
+        const int n = valid ? nrow[j] : xt;
+        const bool self = (n == xt);
+        const double tj = self ? 0.0 : exp((double)L::glob(trow, n) - mt) / zt;
+        double ctot;
+        const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
+        const int fail_j = (valid && !self && !(incl < delta)) ? j : INT_MAX;
+        const int first = block_min_i(fail_j, sh.ired, tid);
+        if (first != INT_MAX) {
+            cut_found = true;
+            a_size = first;
+            // sum before the failing slot = inclusive sum of the slot before it
+            if (first == base) {
+                S = carry;
+            } else {
+                if (j == first - 1) sh.bcast[0] = incl;
+                __syncthreads();
+                S = sh.bcast[0];
+            }
+        } else {
+            carry += ctot;
+            S = carry;
+        }
+    }
+
+    const double t_tok = exp((double)L::glob(trow, xt) - mt) / zt;
+    const double g_tok = exp((double)L::glob(grow, xt) - mg) / zg;
+    const double mass = t_tok + S;
+    const bool accepted = (u_acc * g_tok < mass);
+    if (tid == 0) {
+        double ap;
+        if (g_tok > 0.0) ap = fmin(1.0, mass / g_tok);
+        else ap = mass > 0.0 ? 1.0 : 0.0;
+        if (a.out_prob) a.out_prob[row] = (float)ap;
+        if (a.out_mass) a.out_mass[row] = (float)mass;
+        if (a.out_gtok) a.out_gtok[row] = (float)g_tok;
+        if (a.out_asize) a.out_asize[row] = a_size;
+        if (a.out_path) a.out_path[row] = 1;
+    }
+    if (accepted) {
+        if (tid == 0) {
+            a.out_accept[row] = 1;
+            a.out_resample[row] = -1;
+        }
+        return;
+    }
+
+    // ---- rejected: distorted target t_A, residual max(0, t_A - g), inverse CDF ----
+    const int nwords = (V + 31) >> 5;
+    for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
+    __syncthreads();
+    for (int j = tid; j < a_size; j += NT) {
+        const int n = nrow[j];
+        if (n != xt) atomicOr(&mask[n >> 5], 1u << (n & 31));
+    }
+    __syncthreads();
+
+    // thread tid owns tokens [lo, hi): contiguous, so thread order is token order
+    const int per = (V + NT - 1) / NT;
+    const int lo = min(V, tid * per);
+    const int hi = min(V, lo + per);
+    int zero_resid = 0;
+    int result = -1;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        double local = 0.0;
+        for (int x = lo; x < hi; ++x) {
+            double ta;
+            if (x == xt) ta = mass;
+            else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
+            else ta = exp((double)L::glob(trow, x) - mt) / zt;
+            double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
+            if (!(r > 0.0)) r = 0.0;
+            local += r;
+        }
+        double Z;
+        const double incl = block_scan_incl(local, sh.red, tid, &Z);
+        if (!(Z > 0.0) && !zero_resid) {  // residual without mass: sample t_A itself
+            zero_resid = 1;
+            continue;
+        }
+        const double c = u_res * Z;
+        const int owner = block_min_i((incl > c) ? tid : INT_MAX, sh.ired, tid);
+        if (tid == owner) {
+            double cum = incl - local;
+            int found = -1;
+            for (int x = lo; x < hi; ++x) {
+                double ta;
+                if (x == xt) ta = mass;
+                else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
+                else ta = exp((double)L::glob(trow, x) - mt) / zt;
+                double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
+                if (!(r > 0.0)) r = 0.0;
+                cum += r;
+                if (cum > c) { found = x; break; }
+            }
+            if (found < 0) {  // rounding between the two summation orders: last token with mass
+                for (int x = hi - 1; x >= lo && found < 0; --x) {
+                    double ta;
+                    if (x == xt) ta = mass;
+                    else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
+                    else ta = exp((double)L::glob(trow, x) - mt) / zt;
+                    double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
+                    if (r > 0.0) found = x;
+                }
+            }
+            result = found;
+            a.out_accept[row] = 0;
+            a.out_resample[row] = result;
+        }
+        break;
+    }
+}
+
+// Every row through the exact path: for shapes the fast path does not cover.
+template <typename LT>
+__global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    exact_row<LT>(a, blockIdx.x, smem);
+}
+
+// ---------------------------------------------------------------------------
+// host-side launch
+// ---------------------------------------------------------------------------
+
+static size_t exact_lds_bytes(int V) {
+    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (size_t)((V + 31) / 32) * 4;
+}
+
+template <typename K>
+static hipError_t allow_lds(K kernel, size_t lds) {
+    if (lds <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+template <typename LT, int NV>
+static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
+    const size_t row_bytes = ((size_t)a.V * sizeof(LT) + 15) & ~size_t(15);
+    size_t lds = row_bytes + sizeof(FastShared);
+    if (lds < exact_lds_bytes(a.V)) lds = exact_lds_bytes(a.V);
+    const hipError_t e = allow_lds(&verify_fast<LT, NV>, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((verify_fast<LT, NV>), dim3(a.N), dim3(NT), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <typename LT>
+static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
+    constexpr int EPV = Lane<LT>::EPV;
+    const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
+                            (uintptr_t)(a.stride * (int64_t)sizeof(LT));
+    if ((align & 15) == 0 && (a.V % EPV) == 0) {
+        const int nvec = a.V / EPV;
+        const int nv = (nvec + NT - 1) / NT;
+        if (nv <= 1) return launch_fast_nv<LT, 1>(a, stream);
+        if (nv <= 2) return launch_fast_nv<LT, 2>(a, stream);
+        if (nv <= 4) return launch_fast_nv<LT, 4>(a, stream);
+        if (nv <= 8) return launch_fast_nv<LT, 8>(a, stream);
+        if (nv <= 16) return launch_fast_nv<LT, 16>(a, stream);
+    }
+    const size_t lds = exact_lds_bytes(a.V);
+    const hipError_t e = allow_lds(&verify_exact<LT>, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((verify_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {
+    if (logits_dtype == 0) return launch_typed<float>(a, stream);
+    return launch_typed<uint16_t>(a, stream);
+}
+
+}  // namespace lantern

@@ -1,0 +1,32 @@
+// Argument block passed by value to the verification kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lantern {
+
+struct VerifyArgs {
+    const void* target;       // [N, stride] logits of the target model
+    const void* draft;        // [N, stride] logits of the drafter
+    int N;
+    int V;
+    int64_t stride;           // elements between rows
+    const int32_t* tokens;    // [N] draft tokens
+    const int32_t* knn;       // [V, k] neighbour table
+    int k;
+    float delta;
+    const float* uniforms;    // [N, 2]
+    int32_t* out_accept;      // [N]
+    int32_t* out_resample;    // [N]
+    float* out_prob;          // optional diagnostics, may be null
+    float* out_mass;
+    float* out_gtok;
+    int32_t* out_asize;
+    int32_t* out_path;
+};
+
+// Enqueues the fp32 pass and the fp64 pass on the stream.  logits_dtype: 0 fp32, 1 bf16.
+hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream);
+
+}  // namespace lantern

@@ -1,0 +1,97 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments on the host before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lantern.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2410_03355_amd as lantern
+    if not os.path.exists(lantern.LIB_PATH):
+        lantern.build()
+    return lantern.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lantern_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(lib):
+    import paper_2410_03355_amd as lantern
+    declared = _declared_functions()
+    assert declared, "no functions found in the header"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in lantern.h but not exported"
+    assert sorted(lantern.EXPORTS) == declared
+
+
+def test_status_strings_and_version(lib):
+    import paper_2410_03355_amd as lantern
+    assert lib.lantern_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -6, -7):
+        s = lantern.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert lantern.status_string(-99) == "unknown status"
+
+
+def test_verify_argument_errors(lib):
+    import paper_2410_03355_amd as L
+    p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+
+    def call(tl=p, dl=p, dt=L.F32, N=4, V=16, stride=16, tok=p, knn=p, k=4, delta=0.1, un=p,
+             oa=p, orr=p):
+        return lib.lantern_verify(tl, dl, dt, N, V, stride, tok, knn, k, delta, un, oa, orr, nul)
+
+    assert call(dt=7) == L.binding.E_DTYPE
+    for kw in (dict(N=-1), dict(V=0), dict(k=0), dict(k=17), dict(stride=15), dict(V=L.MAX_VOCAB + 1,
+                                                                                  stride=L.MAX_VOCAB + 1)):
+        assert call(**kw) == L.binding.E_SHAPE
+    assert call(delta=-0.5) == L.binding.E_DELTA
+    assert call(delta=float("nan")) == L.binding.E_DELTA
+    for name in ("tl", "dl", "tok", "knn", "un", "oa", "orr"):
+        assert call(**{name: nul}) == L.binding.E_NULL
+    assert call(N=0, tl=nul, dl=nul) == L.binding.OK  # nothing to do
+
+
+def test_build_knn_argument_errors(lib):
+    import paper_2410_03355_amd as L
+    p = ctypes.c_void_p(4096)
+    nul = ctypes.c_void_p(0)
+    assert lib.lantern_build_knn_workspace_bytes(L.F32, 0, 8, 1) == 0
+    assert lib.lantern_build_knn_workspace_bytes(L.F32, 16, 8, 17) == 0
+    assert lib.lantern_build_knn_workspace_bytes(5, 16, 8, 4) == 0
+    need = lib.lantern_build_knn_workspace_bytes(L.F32, 1024, 8, 16)
+    assert need > 1024 * 4
+    assert lib.lantern_build_knn(p, 9, 16, 8, 4, p, p, 1 << 30, nul) == L.binding.E_DTYPE
+    assert lib.lantern_build_knn(p, L.F32, 16, 8, 17, p, p, 1 << 30, nul) == L.binding.E_SHAPE
+    assert lib.lantern_build_knn(p, L.F32, 16, 0, 4, p, p, 1 << 30, nul) == L.binding.E_SHAPE
+    assert lib.lantern_build_knn(nul, L.F32, 16, 8, 4, p, p, 1 << 30, nul) == L.binding.E_NULL
+    assert lib.lantern_build_knn(p, L.F32, 16, 8, 4, nul, p, 1 << 30, nul) == L.binding.E_NULL
+    assert lib.lantern_build_knn(p, L.F32, 16, 8, 4, p, nul, 1 << 30, nul) == L.binding.E_WORKSPACE
+    assert lib.lantern_build_knn(p, L.F32, 16, 8, 4, p, p, 16, nul) == L.binding.E_WORKSPACE
+    assert lib.lantern_build_knn(p, L.F32, 16, 8, 4, p, ctypes.c_void_p(4096 + 8), 1 << 30, nul) == \
+        L.binding.E_WORKSPACE
+    assert lib.lantern_build_knn_metric(p, L.F32, 16, 8, 4, 5, p, p, 1 << 30, nul) == L.binding.E_SHAPE
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2410_03355_amd as L
+    t = torch.zeros(2, 8)
+    with pytest.raises(ValueError):
+        L.verify(t, t, torch.zeros(2, dtype=torch.int32), torch.zeros(8, 1, dtype=torch.int32), 0.1,
+                 torch.zeros(2, 2))
+    with pytest.raises(ValueError):
+        L.build_knn(torch.zeros(8, 2), 2)

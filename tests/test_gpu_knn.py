@@ -1,0 +1,99 @@
+"""GPU parity of lantern_build_knn against the CPU oracle: indices must be identical."""
+import numpy as np
+import pytest
+import torch
+
+from synth import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_table(lantern, cb, k, metric="l2"):
+    out = lantern.build_knn(cb.cuda(), k, metric=metric)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _check_sampled(oracle, table, cb_np, k, rows, metric="l2"):
+    for r in rows:
+        want = oracle.build_knn(cb_np, k, rows=(int(r), int(r) + 1), metric=metric)[0]
+        np.testing.assert_array_equal(table[r], want, err_msg=f"row {r}")
+
+
+def _check_structure(table, V, k):
+    np.testing.assert_array_equal(table[:, 0], np.arange(V, dtype=np.int32))
+    assert table.min() >= 0 and table.max() < V
+    srt = np.sort(table, axis=1)
+    assert np.all(srt[:, 1:] != srt[:, :-1]), "a row repeats a token"
+
+
+def test_tiny_full_table(oracle_mod, lantern_gpu):
+    cfg = workloads.CONFIGS["tiny"]
+    cb = workloads.make_codebook(cfg)
+    got = _gpu_table(lantern_gpu, cb, cfg.k)
+    want = oracle_mod.build_knn(cb.numpy(), cfg.k, threads=8)
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("name", ["llamagen_step", "image_batch", "wide_latent"])
+def test_full_size_tables(oracle_mod, lantern_gpu, name):
+    """Full-size build on the GPU; the oracle recomputes a sample of rows one by one."""
+    cfg = workloads.CONFIGS[name]
+    cb = workloads.make_codebook(cfg)
+    got = _gpu_table(lantern_gpu, cb, cfg.k)
+    _check_structure(got, cfg.V, cfg.k)
+    rng = np.random.default_rng(cfg.index)
+    rows = np.concatenate([[0, 1, cfg.V - 1, 2047, 2048], rng.integers(0, cfg.V, 40)])
+    _check_sampled(oracle_mod, got, cb.float().numpy(), cfg.k, rows)
+
+
+@pytest.mark.parametrize("V,d,k,dtype", [
+    (1, 4, 1, torch.float32),
+    (2, 1, 2, torch.float32),
+    (17, 3, 17, torch.float32),      # k = V, odd width
+    (300, 5, 40, torch.bfloat16),    # width not a multiple of the vector size
+    (513, 64, 100, torch.bfloat16),
+    (2500, 16, 700, torch.float32),  # more than one block of query rows, ragged tail
+])
+def test_shapes(oracle_mod, lantern_gpu, V, d, k, dtype):
+    g = torch.Generator().manual_seed(V * 31 + d)
+    cb = torch.randn(V, d, generator=g).to(dtype)
+    got = _gpu_table(lantern_gpu, cb, k)
+    want = oracle_mod.build_knn(cb.float().numpy(), k, threads=8)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_exact_ties_and_duplicates(oracle_mod, lantern_gpu):
+    """Integer lattice (many exactly equal distances) and repeated codes: the
+    lower index wins and the token itself stays in slot 0."""
+    xs, ys, zs = np.meshgrid(np.arange(8), np.arange(8), np.arange(8), indexing="ij")
+    lattice = np.stack([xs.ravel(), ys.ravel(), zs.ravel()], axis=1).astype(np.float32)
+    for k in (7, 27, 200):
+        got = _gpu_table(lantern_gpu, torch.from_numpy(lattice), k)
+        want = oracle_mod.build_knn(lattice, k, threads=8)
+        np.testing.assert_array_equal(got, want)
+    rng = np.random.default_rng(5)
+    base = rng.standard_normal((40, 8)).astype(np.float32)
+    dup = base[rng.integers(0, 40, 600)]           # 600 codes, only 40 distinct
+    got = _gpu_table(lantern_gpu, torch.from_numpy(dup), 50)
+    want = oracle_mod.build_knn(dup, 50, threads=8)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_cosine_metric(oracle_mod, lantern_gpu):
+    g = torch.Generator().manual_seed(77)
+    cb = torch.randn(700, 12, generator=g) * (torch.rand(700, 1, generator=g) * 4 + 0.2)
+    got = _gpu_table(lantern_gpu, cb, 60, metric="cosine")
+    want = oracle_mod.build_knn(cb.numpy(), 60, metric="cosine", threads=8)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_table_feeds_verify(oracle_mod, lantern_gpu):
+    """End to end on the device: the table built by the library drives verification."""
+    from parity_utils import compare_verify
+    cfg = workloads.CONFIGS["tiny"]
+    cb = workloads.make_codebook(cfg)
+    table = _gpu_table(lantern_gpu, cb, cfg.k)
+    st = workloads.make_step(cfg, step=4)
+    compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens, table,
+                   cfg.delta, st.uniforms, label="gpu table")

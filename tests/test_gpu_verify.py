@@ -1,0 +1,220 @@
+"""GPU parity of lantern_verify / lantern_verify_ex against the CPU oracle, through the C ABI."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from synth import philox, workloads
+from parity_utils import compare_verify, random_table, sparse_table_from_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _step_and_table(oracle, cfg, rows, variant="plain", step=0):
+    st = workloads.make_step(cfg, step=step, rows=rows, variant=variant)
+    cb = workloads.make_codebook(cfg)
+    table = sparse_table_from_oracle(oracle, cb.float().numpy(), cfg.k, st.draft_tokens.numpy())
+    return st, table
+
+
+def test_tiny_config(oracle_mod, lantern_gpu):
+    """V=1024, k=16, delta=0.1, fp32 logits, 64 rows: cut and rejections occur naturally."""
+    cfg = workloads.CONFIGS["tiny"]
+    cb = workloads.make_codebook(cfg)
+    table = oracle_mod.build_knn(cb.numpy(), cfg.k, threads=8)
+    st = workloads.make_step(cfg)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                       st.draft_tokens, table, cfg.delta, st.uniforms, label="tiny")
+    assert (acc == 0).sum() > 0 and (acc == 1).sum() > 0
+    assert (diag["a_size"] < cfg.k).sum() > 0          # the TVD bound cuts some neighbourhoods
+
+
+@pytest.mark.parametrize("delta,k_use", [(0.0, 16), (0.1, 1), (0.02, 16), (0.5, 16), (2.0, 16)])
+def test_tiny_special_cases(oracle_mod, lantern_gpu, delta, k_use):
+    """delta=0 and k=1 reduce to standard speculative acceptance; delta>1 never binds."""
+    cfg = workloads.CONFIGS["tiny"]
+    cb = workloads.make_codebook(cfg)
+    table = oracle_mod.build_knn(cb.numpy(), k_use, threads=8)
+    st = workloads.make_step(cfg, step=3)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                       st.draft_tokens, table, delta, st.uniforms,
+                                       label=f"tiny d={delta} k={k_use}")
+    if delta == 0.0 or k_use == 1:
+        assert np.all(diag["a_size"] == 1)
+        t_over_g = np.minimum(1.0, diag["t_tok"] / diag["g_tok"])
+        np.testing.assert_allclose(g["accept_prob"], t_over_g, rtol=1e-5)
+    if delta == 2.0:
+        assert np.all(diag["a_size"] == k_use)
+
+
+@pytest.mark.parametrize("variant", ["plain", "peaked", "reject"])
+def test_llamagen_step(oracle_mod, lantern_gpu, variant):
+    """V=16384, k=1000, bf16 logits, one 60-candidate draft tree."""
+    cfg = workloads.CONFIGS["llamagen_step"]
+    st, table = _step_and_table(oracle_mod, cfg, cfg.rows, variant)
+    delta = 0.0 if variant == "reject" else cfg.delta
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                       st.draft_tokens, table, delta, st.uniforms,
+                                       label=f"llamagen {variant}")
+    if variant == "plain":
+        assert (acc == 1).mean() > 0.9 and np.all(g["path"][acc == 1] == 0)
+    if variant == "reject":
+        assert (acc == 0).mean() > 0.3
+    if variant == "peaked":
+        assert (diag["a_size"] < cfg.k).sum() > 0
+
+
+def test_image_batch_rows(oracle_mod, lantern_gpu):
+    """V=16384, k=300, delta=0.2, bf16: two steps of 960 rows of the 256-step job."""
+    cfg = workloads.CONFIGS["image_batch"]
+    for step in (0, 255):
+        st, table = _step_and_table(oracle_mod, cfg, 240, step=step)
+        compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                       table, cfg.delta, st.uniforms, label=f"image_batch step {step}")
+
+
+def test_wide_latent_rows(oracle_mod, lantern_gpu):
+    """V=8192, k=100, delta=0.3, fp32 logits (table rows from a d=256 bf16 codebook)."""
+    cfg = workloads.CONFIGS["wide_latent"]
+    for variant in ("plain", "peaked"):
+        st, table = _step_and_table(oracle_mod, cfg, 256, variant)
+        compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                       table, cfg.delta, st.uniforms, label=f"wide_latent {variant}")
+
+
+def test_stress_full_step(oracle_mod, lantern_gpu):
+    """One full 3840-row step of the stress configuration, in the bench's launch
+    configuration (V=16384, k=1000, bf16, all rows in one call), every row compared."""
+    cfg = workloads.CONFIGS["stress"]
+    st = workloads.make_step(cfg, step=17)
+    table = random_table(cfg.V, cfg.k, seed=5)  # any table with distinct rows is a valid input
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                       st.draft_tokens, table, cfg.delta, st.uniforms, threads=16,
+                                       label="stress step")
+    assert len(acc) == 3840
+
+
+def test_stress_reject_heavy(oracle_mod, lantern_gpu):
+    """Reject-heavy mix at full width: delta=0, acceptance draw just below one."""
+    cfg = workloads.CONFIGS["stress"]
+    st = workloads.make_step(cfg, step=2, rows=512, variant="reject")
+    table = random_table(cfg.V, cfg.k, seed=6)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                       st.draft_tokens, table, 0.0, st.uniforms, threads=16,
+                                       label="stress reject")
+    assert (acc == 0).mean() > 0.3
+    rej = acc == 0
+    assert np.all(res[rej] >= 0) and np.all(res[~rej] == -1)
+
+
+@pytest.mark.parametrize("V,k,N,dtype", [
+    (1, 1, 3, torch.float32),          # degenerate vocabulary
+    (7, 7, 5, torch.float32),          # ragged, k = V
+    (1000, 33, 37, torch.float32),     # V not a multiple of the vector width
+    (1003, 50, 20, torch.bfloat16),    # odd V, rows not 16-byte aligned
+    (4096, 2500, 9, torch.bfloat16),   # k spans several scan chunks
+    (2048, 2048, 4, torch.float32),    # k = V
+    (32768, 64, 6, torch.bfloat16),    # largest register-resident bf16 row
+    (16384, 128, 6, torch.float32),    # largest register-resident fp32 row
+    (40000, 100, 5, torch.float32),    # beyond the fast pass: fp64 pass only
+])
+def test_shapes(oracle_mod, lantern_gpu, V, k, N, dtype):
+    rng = np.random.default_rng(V * 7 + k)
+    scale = 2.5
+    t = torch.from_numpy((rng.standard_normal((N, V)) * scale).astype(np.float32))
+    g = t + torch.from_numpy(rng.standard_normal((N, V)).astype(np.float32))
+    t, g = t.to(dtype), g.to(dtype)
+    tokens = torch.from_numpy(rng.integers(0, V, N).astype(np.int32))
+    table = random_table(V, k, seed=V + k)
+    un = torch.from_numpy(philox.uniforms(V, N))
+    for delta in (0.05, 0.3):
+        compare_verify(oracle_mod, lantern_gpu, t, g, tokens, table, delta, un, label=f"V={V} k={k}")
+
+
+def test_strided_rows(oracle_mod, lantern_gpu):
+    """Rows taken from a wider buffer: row stride larger than V."""
+    rng = np.random.default_rng(3)
+    N, V, k, pitch = 12, 2048, 40, 2304
+    tb = torch.from_numpy((rng.standard_normal((N, pitch)) * 3).astype(np.float32)).to(torch.bfloat16)
+    gb = (tb.float() + torch.from_numpy(rng.standard_normal((N, pitch)).astype(np.float32))).to(torch.bfloat16)
+    tokens = torch.from_numpy(rng.integers(0, V, N).astype(np.int32))
+    table = random_table(V, k, seed=9)
+    un = torch.from_numpy(philox.uniforms(77, N))
+    acc_o, res_o, _ = oracle_mod.verify(tb[:, :V].contiguous(), gb[:, :V].contiguous(), tokens, table, k,
+                                        0.1, un)
+    td, gd = tb.cuda()[:, :V], gb.cuda()[:, :V]
+    assert td.stride(0) == pitch
+    acc, res = lantern_gpu.verify(td, gd, tokens.cuda(), torch.from_numpy(table).cuda(), 0.1, un.cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(res.cpu().numpy(), res_o)
+
+
+def test_filtered_and_unusable_rows(oracle_mod, lantern_gpu):
+    """-inf logits (top-k / top-p filtering upstream) work; NaN, +inf, all -inf rows,
+    tokens and table entries out of range give the -1 sentinels."""
+    rng = np.random.default_rng(4)
+    N, V, k = 16, 4096, 64
+    t = (rng.standard_normal((N, V)) * 2).astype(np.float32)
+    g = (t + rng.standard_normal((N, V))).astype(np.float32)
+    tokens = rng.integers(0, V - 8, N).astype(np.int32)
+    table = random_table(V, k, seed=10)
+    keep = np.argsort(-t[0])[:50]                  # row 0: only 50 target tokens survive filtering
+    mask = np.ones(V, bool); mask[keep] = False
+    t[0, mask] = -np.inf
+    tokens[0] = keep[3]
+    g[1, : V // 2] = -np.inf                        # row 1: half of the draft row filtered
+    tokens[1] = V // 2 + 5
+    t[2, 100] = np.nan
+    g[3, 7] = np.inf
+    t[4, :] = -np.inf
+    tokens[5] = V
+    tokens[6] = -3
+    table[tokens[7], 5] = V + 1                     # bad table entry in the row that row 7 reads
+    t[8, tokens[8]] = -np.inf                       # draft token the target gives zero mass
+    g[9, tokens[9]] = -np.inf                       # draft token the drafter gives zero mass
+    un = torch.from_numpy(philox.uniforms(11, N))
+    acc, res, diag, gg = compare_verify(oracle_mod, lantern_gpu, torch.from_numpy(t), torch.from_numpy(g),
+                                        torch.from_numpy(tokens), table, 0.2, un, label="unusable")
+    assert list(acc[2:8]) == [-1] * 6 and list(res[2:8]) == [-1] * 6
+    assert acc[0] in (0, 1) and acc[1] in (0, 1)
+    assert acc[9] == 1
+
+
+def test_empty_batch_and_determinism(oracle_mod, lantern_gpu):
+    V, k = 512, 8
+    table = torch.from_numpy(random_table(V, k, seed=1)).cuda()
+    empty = torch.empty((0, V), device="cuda")
+    acc, res = lantern_gpu.verify(empty, empty, torch.empty(0, dtype=torch.int32, device="cuda"), table, 0.1,
+                                  torch.empty((0, 2), device="cuda"))
+    assert acc.numel() == 0 and res.numel() == 0
+    cfg = workloads.CONFIGS["tiny"]
+    st = workloads.make_step(cfg, step=9, variant="peaked")
+    tb = torch.from_numpy(random_table(cfg.V, cfg.k, seed=2)).cuda()
+    args = (st.target_logits.cuda(), st.draft_logits.cuda(), st.draft_tokens.cuda(), tb, cfg.delta,
+            st.uniforms.cuda())
+    a1 = lantern_gpu.verify_ex(*args)
+    a2 = lantern_gpu.verify_ex(*args)
+    torch.cuda.synchronize()
+    for name in a1:
+        assert torch.equal(a1[name], a2[name]) or name in ("accept_prob", "mass", "g_tok") and \
+            torch.equal(torch.nan_to_num(a1[name]), torch.nan_to_num(a2[name]))
+
+
+def test_side_stream(oracle_mod, lantern_gpu):
+    """Work is enqueued on the stream that is passed in."""
+    cfg = workloads.CONFIGS["tiny"]
+    st = workloads.make_step(cfg, step=1)
+    table = random_table(cfg.V, cfg.k, seed=3)
+    acc_o, res_o, _ = oracle_mod.verify(st.target_logits, st.draft_logits, st.draft_tokens, table, cfg.k,
+                                        cfg.delta, st.uniforms)
+    s = torch.cuda.Stream()
+    args = [x.cuda() for x in (st.target_logits, st.draft_logits, st.draft_tokens)]
+    tb, un = torch.from_numpy(table).cuda(), st.uniforms.cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        acc, res = lantern_gpu.verify(args[0], args[1], args[2], tb, cfg.delta, un, stream=s)
+    s.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(res.cpu().numpy(), res_o)
