@@ -96,6 +96,7 @@ struct FastShared {
     int w_np[NW];         // first slot that does not definitely pass
     int w_df[NW];         // first slot that definitely fails
     int w_bad[NW];        // table entry outside [0,V)
+    int settled;          // row settled by the fp32 path
 };
 
 template <typename LT>
@@ -318,10 +319,10 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             if (a.out_asize) a.out_asize[row] = a_size;
             if (a.out_path) a.out_path[row] = 0;
         }
-        sh.w_bad[0] = settled ? 1 : 0;
+        sh.settled = settled ? 1 : 0;
     }
     __syncthreads();
-    if (sh.w_bad[0]) return;
+    if (sh.settled) return;
     // not settled in fp32: this workgroup evaluates the row in fp64 (LDS is reused)
     exact_row<LT>(a, row, smem);
 }
