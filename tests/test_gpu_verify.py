@@ -1,6 +1,4 @@
 """GPU parity of lantern_verify / lantern_verify_ex against the CPU oracle, through the C ABI."""
-import dataclasses
-
 import numpy as np
 import pytest
 import torch
@@ -53,7 +51,8 @@ def test_llamagen_step(oracle_mod, lantern_gpu, variant):
     """V=16384, k=1000, bf16 logits, one 60-candidate draft tree."""
     cfg = workloads.CONFIGS["llamagen_step"]
     st, table = _step_and_table(oracle_mod, cfg, cfg.rows, variant)
-    delta = 0.0 if variant == "reject" else cfg.delta
+    # peaked rows put ~1000/16384 of the mass into a random neighbourhood: a small bound cuts it
+    delta = {"plain": cfg.delta, "reject": 0.0, "peaked": 0.01}[variant]
     acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
                                        st.draft_tokens, table, delta, st.uniforms,
                                        label=f"llamagen {variant}")
@@ -77,10 +76,10 @@ def test_image_batch_rows(oracle_mod, lantern_gpu):
 def test_wide_latent_rows(oracle_mod, lantern_gpu):
     """V=8192, k=100, delta=0.3, fp32 logits (table rows from a d=256 bf16 codebook)."""
     cfg = workloads.CONFIGS["wide_latent"]
-    for variant in ("plain", "peaked"):
+    for variant, delta in (("plain", cfg.delta), ("peaked", 0.01)):
         st, table = _step_and_table(oracle_mod, cfg, 256, variant)
         compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
-                       table, cfg.delta, st.uniforms, label=f"wide_latent {variant}")
+                       table, delta, st.uniforms, label=f"wide_latent {variant}")
 
 
 def test_stress_full_step(oracle_mod, lantern_gpu):
