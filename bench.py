@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy, so that a counter run has a kernel of "
+                         "known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters, if known")
     args = ap.parse_args()
@@ -89,6 +92,12 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # events bracket every launch on the stream the kernel runs on
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
