@@ -55,8 +55,8 @@ typedef enum {
     LANTERN_METRIC_COSINE = 1 /* cosine similarity (ablation, Section 5.3.1)           */
 } lantern_metric;
 
-/* Largest vocabulary lantern_verify accepts (bitmask of one row must fit in LDS). */
-#define LANTERN_MAX_VOCAB (1 << 20)
+/* Largest vocabulary lantern_verify accepts (a bitmask of one row and its partial sums must fit in LDS). */
+#define LANTERN_MAX_VOCAB (1 << 19)
 
 /*
  * Bytes of device workspace lantern_build_knn needs for this problem, or 0 if

@@ -15,7 +15,7 @@ from .build import LIB_PATH
 
 F32, BF16 = 0, 1
 METRIC_L2, METRIC_COSINE = 0, 1
-MAX_VOCAB = 1 << 20
+MAX_VOCAB = 1 << 19
 
 OK = 0
 E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -7

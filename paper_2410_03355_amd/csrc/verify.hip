@@ -23,6 +23,7 @@
 #include <stdint.h>
 
 #include "device_utils.h"
+#include "exp64.h"
 #include "verify_args.h"
 
 namespace lantern {
@@ -48,7 +49,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // 16-byte load of data that is read once: non-temporal, so the streamed rows
 // do not evict the neighbour table from the caches.
 __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+#ifdef LANTERN_PLAIN_LOADS
+    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+#else
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#endif
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -99,11 +104,24 @@ struct FastShared {
     int settled;          // row settled by the fp32 path
 };
 
-template <typename LT>
-__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem);
+template <typename LT, bool VEC>
+__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
+                          bool have_max, float max_t, float max_g);
+
+#ifndef LANTERN_FAST_WAVES
+#define LANTERN_FAST_WAVES 0
+#endif
+#if LANTERN_FAST_WAVES > 0
+#define LANTERN_FAST_ATTR __attribute__((amdgpu_waves_per_eu(LANTERN_FAST_WAVES, LANTERN_FAST_WAVES)))
+#else
+#define LANTERN_FAST_ATTR
+#endif
+#ifndef LANTERN_EXTRA_LDS
+#define LANTERN_EXTRA_LDS 0
+#endif
 
 template <typename LT, int NV>
-__global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
+__global__ __launch_bounds__(NT) LANTERN_FAST_ATTR void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -323,12 +341,15 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     }
     __syncthreads();
     if (sh.settled) return;
-    // not settled in fp32: this workgroup evaluates the row in fp64 (LDS is reused)
-    exact_row<LT>(a, row, smem);
+    // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
+    // finite positive normalisers prove there is no NaN / +inf and a finite maximum in both rows
+    const bool rows_finite = (Zt > 0.f) && (Zt < __builtin_huge_valf()) && (Zg > 0.f) && (Zg < __builtin_huge_valf());
+    exact_row<LT, true>(a, row, smem + ((row_bytes + (int)sizeof(FastShared) + 15) & ~15), s_row, rows_finite,
+                        Mt, Mg);
 }
 
 // ---------------------------------------------------------------------------
-// fp64 evaluation of unsettled rows
+// fp64 evaluation of rows the fp32 path did not settle
 // ---------------------------------------------------------------------------
 
 struct ExactShared {
@@ -400,40 +421,120 @@ __device__ __forceinline__ double block_scan_incl(double v, double* red, int tid
     return off + incl;
 }
 
-// Evaluates one row in fp64 with the whole workgroup.  smem: dynamic LDS of at
-// least exact_lds_bytes(V); its previous contents are dead.
-template <typename LT>
-__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
+// EPV consecutive logits of a row as floats; vector vi covers tokens
+// [vi*EPV, vi*EPV+EPV).  Tokens at or beyond V read as -inf.  With VEC the row
+// is 16-byte aligned and V a multiple of EPV; lds, when not null, holds the
+// same row in LDS.
+template <typename LT, bool VEC>
+struct VecLoad {
+    static constexpr int EPV = Lane<LT>::EPV;
+    __device__ static __forceinline__ void load(const LT* row, const unsigned char* lds, int vi, int V,
+                                                float (&out)[EPV]) {
+        if (VEC) {
+            if ((vi + 1) * EPV <= V) {
+                const uint4 v = lds ? reinterpret_cast<const uint4*>(lds)[vi]
+                                    : reinterpret_cast<const uint4*>(row)[vi];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) out[e] = Lane<LT>::get(v, e);
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) out[e] = neg_inf_f();
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                const int x = vi * EPV + e;
+                out[e] = x < V ? Lane<LT>::glob(row, x) : neg_inf_f();
+            }
+        }
+    }
+};
+
+// LDS the exact path needs beyond whatever precedes it: reductions, a bitmask
+// of A over the vocabulary, one fp64 partial sum per (vector chunk, wavefront).
+__host__ __device__ inline size_t exact_lds_bytes(int V, int epv) {
+    const size_t nvec = ((size_t)V + epv - 1) / epv;
+    const size_t nchunk = (nvec + NT - 1) / NT;
+    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 + nchunk * NW * sizeof(double);
+}
+
+// One residual term: max(0, t_A(x) - g(x)) (or t_A(x) when the residual has no mass).
+__device__ __forceinline__ double resid_term(int x, int xt, int V, float lt, float lg, const uint32_t* mask,
+                                             double mt, double mg, double inv_zt, double inv_zg,
+                                             double mass, int zero_resid) {
+    // branch-free: both exponentials are always evaluated, then selected
+    const int xm = x < V ? x : V - 1;
+    const bool in_a = (x < V) && ((mask[xm >> 5] >> (xm & 31)) & 1u);
+    double ta = exp_nonpos((double)lt - mt) * inv_zt;
+    ta = in_a ? 0.0 : ta;
+    ta = (x == xt) ? mass : ta;
+    const double gv = exp_nonpos((double)lg - mg) * inv_zg;
+    const double r = zero_resid ? ta : ta - gv;
+    return r > 0.0 ? r : 0.0;
+}
+
+// Evaluates one row in fp64 with the whole workgroup.  ex: LDS region of
+// exact_lds_bytes().  lds_row: the raw target row in LDS, or null.  have_max:
+// the caller has the row maxima and knows both rows are free of NaN and +inf.
+// Token order of the vector layout: vector vi = chunk*NT + tid, so (chunk,
+// wavefront, lane, element) is ascending token order.  Every pass over the row
+// loads the next chunk's vectors before it works on the current one.
+template <typename LT, bool VEC>
+__device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
+                          bool have_max, float max_t, float max_g) {
     using L = Lane<LT>;
-    ExactShared& sh = *reinterpret_cast<ExactShared*>(smem);
-    uint32_t* mask = reinterpret_cast<uint32_t*>(smem + ((sizeof(ExactShared) + 15) & ~size_t(15)));
+    constexpr int EPV = L::EPV;
+    ExactShared& sh = *reinterpret_cast<ExactShared*>(ex);
+    uint32_t* mask = reinterpret_cast<uint32_t*>(ex + ((sizeof(ExactShared) + 15) & ~size_t(15)));
 
     const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
     const int V = a.V;
     const int k = a.k;
-    const void* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
-    const void* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
+    const int nwords = (V + 31) >> 5;
+    double* wtot = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(mask) + (((size_t)nwords * 4 + 7) & ~size_t(7)));
+    const int nvec = (V + EPV - 1) / EPV;
+    const int nchunk = (nvec + NT - 1) / NT;
+    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
+    const LT* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
     const int xt = a.tokens[row];
     const double delta = (double)a.delta;
     const double u_acc = (double)a.uniforms[2 * (int64_t)row];
     const double u_res = (double)a.uniforms[2 * (int64_t)row + 1];
 
-    // ---- usability: token and table entries in range, logits free of NaN / +inf ----
+    // ---- usability and maxima: token and table entries in range, no NaN / +inf ----
     int bad = ((unsigned)xt < (unsigned)V) ? 0 : 1;
     const int32_t* nrow = a.knn + (int64_t)(bad ? 0 : xt) * k;
     if (!bad)
         for (int j = tid; j < k; j += NT)
             if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
-    double mt = -INFINITY, mg = -INFINITY;
-    for (int x = tid; x < V; x += NT) {
-        const double lt = (double)L::glob(trow, x);
-        const double lg = (double)L::glob(grow, x);
-        if (isnan(lt) || isnan(lg) || lt == INFINITY || lg == INFINITY) bad = 1;
-        mt = fmax(mt, lt);
-        mg = fmax(mg, lg);
+    float mtf = neg_inf_f(), mgf = neg_inf_f();
+    if (have_max) {
+        mtf = max_t;
+        mgf = max_g;
+    } else {
+        float tn[EPV], gn[EPV];
+        VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
+        VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+        for (int c = 0; c < nchunk; ++c) {
+            float tf[EPV], gf[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
+            if (c + 1 < nchunk) {
+                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * NT + tid, V, tn);
+                VecLoad<LT, VEC>::load(grow, nullptr, (c + 1) * NT + tid, V, gn);
+            }
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                if (isnan(tf[e]) || isnan(gf[e]) || tf[e] == INFINITY || gf[e] == INFINITY) bad = 1;
+                mtf = fmaxf(mtf, tf[e]);
+                mgf = fmaxf(mgf, gf[e]);
+            }
+        }
     }
-    mt = block_max(mt, sh.red, tid);
-    mg = block_max(mg, sh.red2, tid);
+    const double mt = block_max((double)mtf, sh.red, tid);
+    const double mg = block_max((double)mgf, sh.red2, tid);
     if (mt == -INFINITY || mg == -INFINITY) bad = 1;
     bad = block_or_i(bad, sh.ired, tid);
     if (bad) {
@@ -451,9 +552,27 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
 
     // ---- softmax normalisers ----
     double zt = 0.0, zg = 0.0;
-    for (int x = tid; x < V; x += NT) {
-        zt += exp((double)L::glob(trow, x) - mt);
-        zg += exp((double)L::glob(grow, x) - mg);
+    {
+        float tn[EPV], gn[EPV];
+        VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
+        VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+        for (int c = 0; c < nchunk; ++c) {
+            float tf[EPV], gf[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
+            if (c + 1 < nchunk) {
+                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * NT + tid, V, tn);
+                VecLoad<LT, VEC>::load(grow, nullptr, (c + 1) * NT + tid, V, gn);
+            }
+            double st = 0.0, sg = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                st += exp_nonpos((double)tf[e] - mt);
+                sg += exp_nonpos((double)gf[e] - mg);
+            }
+            zt += st;
+            zg += sg;
+        }
     }
     zt = block_sum(zt, sh.red, tid);
     zg = block_sum(zg, sh.red2, tid);
@@ -468,7 +587,8 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
         const bool valid = j < k;
         const int n = valid ? nrow[j] : xt;
         const bool self = (n == xt);
-        const double tj = self ? 0.0 : exp((double)L::glob(trow, n) - mt) / zt;
+        const float ln = lds_row ? L::lds(lds_row, n) : L::glob(trow, n);
+        const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
         double ctot;
         const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
         const int fail_j = (valid && !self && !(incl < delta)) ? j : INT_MAX;
@@ -490,8 +610,8 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
         }
     }
 
-    const double t_tok = exp((double)L::glob(trow, xt) - mt) / zt;
-    const double g_tok = exp((double)L::glob(grow, xt) - mg) / zg;
+    const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
+    const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;
     const double mass = t_tok + S;
     const bool accepted = (u_acc * g_tok < mass);
     if (tid == 0) {
@@ -513,7 +633,6 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
     }
 
     // ---- rejected: distorted target t_A, residual max(0, t_A - g), inverse CDF ----
-    const int nwords = (V + 31) >> 5;
     for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
     __syncthreads();
     for (int j = tid; j < a_size; j += NT) {
@@ -522,57 +641,85 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
     }
     __syncthreads();
 
-    // thread tid owns tokens [lo, hi): contiguous, so thread order is token order
-    const int per = (V + NT - 1) / NT;
-    const int lo = min(V, tid * per);
-    const int hi = min(V, lo + per);
+    const double inv_zt = 1.0 / zt, inv_zg = 1.0 / zg;
     int zero_resid = 0;
-    int result = -1;
     for (int attempt = 0; attempt < 2; ++attempt) {
-        double local = 0.0;
-        for (int x = lo; x < hi; ++x) {
-            double ta;
-            if (x == xt) ta = mass;
-            else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
-            else ta = exp((double)L::glob(trow, x) - mt) / zt;
-            double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
-            if (!(r > 0.0)) r = 0.0;
-            local += r;
+        // per (chunk, wavefront) partial sums of the residual, in token order
+        {
+            float tn[EPV], gn[EPV];
+            VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
+            VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+            for (int c = 0; c < nchunk; ++c) {
+                const int vi = c * NT + tid;
+                float tf[EPV], gf[EPV];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
+                if (c + 1 < nchunk) {
+                    VecLoad<LT, VEC>::load(trow, lds_row, vi + NT, V, tn);
+                    VecLoad<LT, VEC>::load(grow, nullptr, vi + NT, V, gn);
+                }
+                double s = 0.0;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e)
+                    s += resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass,
+                                    zero_resid);
+                s = wave_sum(s);
+                if (lane == 0) wtot[c * NW + wave] = s;
+            }
         }
-        double Z;
-        const double incl = block_scan_incl(local, sh.red, tid, &Z);
+        __syncthreads();
+        const int nent = nchunk * NW;
+        double Z = 0.0;
+        for (int e = 0; e < nent; ++e) Z += wtot[e];
         if (!(Z > 0.0) && !zero_resid) {  // residual without mass: sample t_A itself
             zero_resid = 1;
+            __syncthreads();
             continue;
         }
-        const double c = u_res * Z;
-        const int owner = block_min_i((incl > c) ? tid : INT_MAX, sh.ired, tid);
-        if (tid == owner) {
-            double cum = incl - local;
-            int found = -1;
-            for (int x = lo; x < hi; ++x) {
-                double ta;
-                if (x == xt) ta = mass;
-                else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
-                else ta = exp((double)L::glob(trow, x) - mt) / zt;
-                double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
-                if (!(r > 0.0)) r = 0.0;
-                cum += r;
-                if (cum > c) { found = x; break; }
+        const double cthr = u_res * Z;
+        // first (chunk, wavefront) whose running sum exceeds the threshold
+        double P = 0.0;
+        int ent = nent - 1;
+        for (int e = 0; e < nent; ++e) {
+            const double nx = P + wtot[e];
+            if (nx > cthr) { ent = e; break; }
+            P = nx;
+        }
+        if (wave == (ent % NW)) {
+            const int c = ent / NW;
+            const int vi = c * NT + tid;
+            float tf[EPV], gf[EPV];
+            VecLoad<LT, VEC>::load(trow, lds_row, vi, V, tf);
+            VecLoad<LT, VEC>::load(grow, nullptr, vi, V, gf);
+            double r[EPV];
+            double s = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                r[e] = resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass, zero_resid);
+                s += r[e];
             }
-            if (found < 0) {  // rounding between the two summation orders: last token with mass
-                for (int x = hi - 1; x >= lo && found < 0; --x) {
-                    double ta;
-                    if (x == xt) ta = mass;
-                    else if ((mask[x >> 5] >> (x & 31)) & 1u) ta = 0.0;
-                    else ta = exp((double)L::glob(trow, x) - mt) / zt;
-                    double r = zero_resid ? ta : ta - exp((double)L::glob(grow, x) - mg) / zg;
-                    if (r > 0.0) found = x;
+            const double incl = wave_scan_incl(s);
+            double excl = __shfl_up(incl, 1, WAVE);
+            if (lane == 0) excl = 0.0;
+            const unsigned long long cross = __ballot(P + incl > cthr);
+            const unsigned long long haspos = __ballot(s > 0.0);
+            // rounding between the butterfly sum and the scan can leave no crossing lane:
+            // then the last lane that holds mass takes the draw
+            const int owner = cross ? (__ffsll((long long)cross) - 1)
+                                    : (haspos ? 63 - __clzll((long long)haspos) : 0);
+            if (lane == owner) {
+                double cum = P + excl;
+                int found = -1, lastpos = -1;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    cum += r[e];
+                    if (r[e] > 0.0) lastpos = vi * EPV + e;
+                    if (found < 0 && cum > cthr && r[e] > 0.0) found = vi * EPV + e;
                 }
+                if (found < 0) found = lastpos;
+                a.out_accept[row] = 0;
+                a.out_resample[row] = found;
             }
-            result = found;
-            a.out_accept[row] = 0;
-            a.out_resample[row] = result;
         }
         break;
     }
@@ -582,16 +729,12 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* smem) {
 template <typename LT>
 __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    exact_row<LT>(a, blockIdx.x, smem);
+    exact_row<LT, false>(a, blockIdx.x, smem, nullptr, false, 0.f, 0.f);
 }
 
 // ---------------------------------------------------------------------------
 // host-side launch
 // ---------------------------------------------------------------------------
-
-static size_t exact_lds_bytes(int V) {
-    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (size_t)((V + 31) / 32) * 4;
-}
 
 template <typename K>
 static hipError_t allow_lds(K kernel, size_t lds) {
@@ -600,11 +743,15 @@ static hipError_t allow_lds(K kernel, size_t lds) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
+template <typename LT>
+static size_t fast_exact_offset(int V) {
+    const size_t row_bytes = ((size_t)V * sizeof(LT) + 15) & ~size_t(15);
+    return (row_bytes + sizeof(FastShared) + 15) & ~size_t(15);
+}
+
 template <typename LT, int NV>
 static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
-    const size_t row_bytes = ((size_t)a.V * sizeof(LT) + 15) & ~size_t(15);
-    size_t lds = row_bytes + sizeof(FastShared);
-    if (lds < exact_lds_bytes(a.V)) lds = exact_lds_bytes(a.V);
+    const size_t lds = fast_exact_offset<LT>(a.V) + exact_lds_bytes(a.V, Lane<LT>::EPV) + LANTERN_EXTRA_LDS;
     const hipError_t e = allow_lds(&verify_fast<LT, NV>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((verify_fast<LT, NV>), dim3(a.N), dim3(NT), lds, stream, a);
@@ -625,7 +772,7 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
         if (nv <= 8) return launch_fast_nv<LT, 8>(a, stream);
         if (nv <= 16) return launch_fast_nv<LT, 16>(a, stream);
     }
-    const size_t lds = exact_lds_bytes(a.V);
+    const size_t lds = exact_lds_bytes(a.V, EPV);
     const hipError_t e = allow_lds(&verify_exact<LT>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((verify_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
