@@ -125,6 +125,174 @@ __global__ __launch_bounds__(NT) void knn_dist_direct(const CT* cb, int V, int d
     dist[(int64_t)row * V + j] = key;
 }
 
+
+// ---- stage 1 (aligned shapes): approximate keys from a matrix-core contraction ----
+// G = C C^T on MFMA 32x32 tiles with fp32 accumulation; squared l2 key
+// n_i + n_j - 2 G_ij, cosine key -G_ij / sqrt(n_i n_j).  One wavefront owns a
+// 64x64 block of the key matrix (2x2 MFMA tiles); a workgroup of 4 wavefronts
+// owns 128x128.  Operand fragments are read straight from the codebook, which
+// stays cache-resident (at most a few MB).
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_norms(const CT* cb, int V, int d, float* norms) {
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i >= V) return;
+    const CT* ci = cb + (int64_t)i * d;
+    float n = 0.f;
+    for (int t = 0; t < d; ++t) {
+        const float x = cb_f32<CT>(ci, t);
+        n = fmaf(x, x, n);
+    }
+    norms[i] = n;
+}
+
+__global__ __launch_bounds__(NT) void knn_norm_max(const float* norms, int V, float* nmax) {
+    __shared__ float red[NW];
+    float m = 0.f;
+    for (int i = threadIdx.x; i < V; i += NT) m = fmaxf(m, norms[i]);
+    m = wave_max(m);
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = red[0];
+        for (int w = 1; w < NW; ++w) r = fmaxf(r, red[w]);
+        *nmax = r;
+    }
+}
+
+// Accumulator element r of lane l of a 32x32 MFMA tile is row 8*(r/4) + 4*(l/32) + r%4,
+// column l%32 (rows come from the A operand, columns from the B operand).
+__device__ __forceinline__ void store_tile(const f32x16& acc, int i0, int j0, int lane, int r0, int rows,
+                                           int V, int metric, const float* norms, float* dist) {
+    const int j = j0 + (lane & 31);
+    if (j >= V) return;
+    const float nj = norms[j];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = i0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (i < r0 + rows) {
+            const float ni = norms[i];
+            const float g = acc[r];
+            const float key = metric == 0 ? (ni + nj) - 2.f * g : -g * rsqrtf(ni * nj);
+            dist[(int64_t)(i - r0) * V + j] = key;
+        }
+    }
+}
+
+// bf16 codebook, d a multiple of 8: v_mfma_f32_32x32x16_bf16, 16 coordinates per step
+// (lanes 0-31 carry coordinates k0..k0+7 of their row, lanes 32-63 k0+8..k0+15).
+__global__ __launch_bounds__(NT) void knn_dist_mfma_bf16(const uint16_t* cb, const float* norms, int V, int d,
+                                                         int r0, int rows, int metric, float* dist) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    const int i_base = r0 + blockIdx.y * 128 + (wave >> 1) * 64;
+    const int j_base = blockIdx.x * 128 + (wave & 1) * 64;
+    if (i_base >= r0 + rows || j_base >= V) return;
+    const uint16_t* arow[2];
+    const uint16_t* brow[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
+        brow[t] = cb + (int64_t)min(j_base + t * 32 + (lane & 31), V - 1) * d;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    const int kh = 8 * (lane >> 5);
+    for (int k0 = 0; k0 < d; k0 += 16) {
+        const int kk = k0 + kh;
+        uint4 fa[2], fb[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (kk < d) {
+                fa[t] = *reinterpret_cast<const uint4*>(arow[t] + kk);
+                fb[t] = *reinterpret_cast<const uint4*>(brow[t] + kk);
+            } else {
+                fa[t] = make_uint4(0, 0, 0, 0);
+                fb[t] = fa[t];
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]), acc[a][b], 0, 0, 0);
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            store_tile(acc[a][b], i_base + a * 32, j_base + b * 32, lane, r0, rows, V, metric, norms, dist);
+}
+
+// fp32 codebook, d a multiple of 4: v_mfma_f32_32x32x2_f32, 2 coordinates per step
+// (lanes 0-31 carry coordinate k, lanes 32-63 coordinate k+1); rows are read 8 floats at a time.
+__global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const float* norms, int V, int d,
+                                                        int r0, int rows, int metric, float* dist) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    const int i_base = r0 + blockIdx.y * 128 + (wave >> 1) * 64;
+    const int j_base = blockIdx.x * 128 + (wave & 1) * 64;
+    if (i_base >= r0 + rows || j_base >= V) return;
+    const float* arow[2];
+    const float* brow[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
+        brow[t] = cb + (int64_t)min(j_base + t * 32 + (lane & 31), V - 1) * d;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    const bool hi = (lane >> 5) != 0;
+    for (int k0 = 0; k0 < d; k0 += 8) {
+        float4 fa[2][2], fb[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (k0 + 4 * h < d) {
+                    fa[t][h] = *reinterpret_cast<const float4*>(arow[t] + k0 + 4 * h);
+                    fb[t][h] = *reinterpret_cast<const float4*>(brow[t] + k0 + 4 * h);
+                } else {
+                    fa[t][h] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    fb[t][h] = fa[t][h];
+                }
+            }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {  // coordinates k0+2s, k0+2s+1
+            float va[2], vb[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const float4 qa = fa[t][s >> 1], qb = fb[t][s >> 1];
+                va[t] = (s & 1) ? (hi ? qa.w : qa.z) : (hi ? qa.y : qa.x);
+                vb[t] = (s & 1) ? (hi ? qb.w : qb.z) : (hi ? qb.y : qb.x);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[a], vb[b], acc[a][b], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            store_tile(acc[a][b], i_base + a * 32, j_base + b * 32, lane, r0, rows, V, metric, norms, dist);
+}
+
 // ---- stage 2: select, re-rank exactly, emit ----
 struct SelectShared {
     double key[CAND_CAP];
@@ -135,10 +303,13 @@ struct SelectShared {
     int count;
 };
 
-// err_rel, err_abs: |approximate key - exact key| <= err_rel * |exact key| + err_abs
+// Error model of the approximate keys:
+//   |approximate - exact| <= err_rel * |exact| + err_abs + err_norm * (norm_i + max norm)
+// (the last term applies when norms is not null: keys formed as n_i + n_j - 2 G_ij).
 template <typename CT>
 __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
                                                  const float* dist, float err_rel, float err_abs,
+                                                 float err_norm, const float* norms, const float* nmax,
                                                  int32_t* out, int* flags) {
     __shared__ SelectShared sh;
     const int row = blockIdx.x;
@@ -242,7 +413,9 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     bool ok = true;
     if (count < V - 1) {
         const double last = sh.key[need - 1];
-        const double num = (double)thr - (double)err_abs;
+        double eabs = (double)err_abs;
+        if (norms) eabs += (double)err_norm * ((double)norms[i] + (double)*nmax);
+        const double num = (double)thr - eabs;
         const double floor_discarded = num - 1.01 * (double)err_rel * fabs(num);
         ok = last <= floor_discarded;
     }
@@ -291,17 +464,46 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
     int* flags = reinterpret_cast<int*>(ws + L.flags);
     double* slow = reinterpret_cast<double*>(ws + L.slow);
     const CT* cb = static_cast<const CT*>(a.codebook);
-    // direct fp32 evaluation: (d + 4) roundings of at most 2^-23 each, relative to the key for
-    // squared l2 (a sum of squares); absolute, against |cos| <= 1, for the cosine key
+    float* norms = reinterpret_cast<float*>(ws + L.norms);
+    float* nmax = reinterpret_cast<float*>(ws + L.nmax);
+    // matrix-core path: rows 16-byte aligned and coordinates in whole vectors
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.codebook) & 15) == 0;
+    const bool mfma = aligned && (sizeof(CT) == 2 ? (a.d % 8) == 0 : (a.d % 4) == 0) && a.V >= 32;
+    // one rounding is at most 2^-23 relative here (twice the fp32 unit, to cover a
+    // contraction that truncates); a d-term sum takes d + 8 of them
     const float gamma = (float)(a.d + 8) * 1.1920929e-7f;
-    const float err_rel = a.metric == 0 ? gamma : 0.f;
-    const float err_abs = a.metric == 0 ? 0.f : 2.f * gamma;
+    float err_rel, err_abs, err_norm;
+    if (mfma) {
+        hipLaunchKernelGGL((knn_norms<CT>), dim3((a.V + NT - 1) / NT), dim3(NT), 0, stream, cb, a.V, a.d, norms);
+        hipLaunchKernelGGL(knn_norm_max, dim3(1), dim3(NT), 0, stream, norms, a.V, nmax);
+        // n_i + n_j - 2 G: errors of the two norms and of G are each below gamma (n_i + n_j) / 2 ... gamma (n_i + n_j)
+        err_rel = 0.f;
+        err_abs = a.metric == 0 ? 0.f : 4.f * gamma;
+        err_norm = a.metric == 0 ? 2.f * gamma : 0.f;
+    } else {
+        // direct evaluation: relative to the key for squared l2 (a sum of squares);
+        // absolute, against |cos| <= 1, for the cosine key
+        err_rel = a.metric == 0 ? gamma : 0.f;
+        err_abs = a.metric == 0 ? 0.f : 2.f * gamma;
+        err_norm = 0.f;
+    }
     for (int r0 = 0; r0 < a.V; r0 += L.row_block) {
         const int rows = (a.V - r0) < L.row_block ? (a.V - r0) : L.row_block;
-        hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
-                           cb, a.V, a.d, r0, a.metric, dist);
+        if (mfma) {
+            const dim3 grid((a.V + 127) / 128, (rows + 127) / 128);
+            if (sizeof(CT) == 2)
+                hipLaunchKernelGGL(knn_dist_mfma_bf16, grid, dim3(NT), 0, stream,
+                                   reinterpret_cast<const uint16_t*>(cb), norms, a.V, a.d, r0, rows, a.metric, dist);
+            else
+                hipLaunchKernelGGL(knn_dist_mfma_f32, grid, dim3(NT), 0, stream,
+                                   reinterpret_cast<const float*>(cb), norms, a.V, a.d, r0, rows, a.metric, dist);
+        } else {
+            hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
+                               cb, a.V, a.d, r0, a.metric, dist);
+        }
         hipLaunchKernelGGL((knn_select<CT>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k, a.metric,
-                           r0, dist, err_rel, err_abs, a.out, flags);
+                           r0, dist, err_rel, err_abs, err_norm, mfma && a.metric == 0 ? norms : nullptr, nmax,
+                           a.out, flags);
         const int wgs = rows < SLOW_WGS ? rows : SLOW_WGS;
         hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
                            a.metric, r0, rows, flags, slow, a.out);

@@ -268,8 +268,7 @@ __global__ __launch_bounds__(NT) LANTERN_FAST_ATTR void verify_fast(VerifyArgs a
             p[q] = run;
         }
         const float incl = wave_scan_incl(run);
-        float excl = __shfl_up(incl, 1, WAVE);
-        if (lane == 0) excl = 0.f;
+        const float excl = wave_prev(incl, 0.f);
         if (lane == WAVE - 1) sh.wtot[wave] = incl;
         __syncthreads();
         float woff = 0.f, ctot = 0.f;
