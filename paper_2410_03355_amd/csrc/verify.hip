@@ -19,6 +19,7 @@
 // (the paper's p), xt = draft token.
 #include <hip/hip_runtime.h>
 #include <limits.h>
+#include <stddef.h>
 #include <math.h>
 #include <stdint.h>
 
@@ -31,18 +32,21 @@ namespace lantern {
 constexpr float LOG2E_F = 1.44269504088896340736f;
 
 // ---- rounding margins of the fp32 pass -------------------------------------
-// One unnormalised term e = 2^((l - M) * log2e): the subtraction, the product
-// with the rounded constant and v_exp_f32 give a relative error below
-// (2.3 |l - M| + 2) * 2^-24.  Terms with l - M < -32 are below e^-32 each, so
-// bounding |l - M| by 32 costs at most V * 1.3e-14 relative to the sum (>= 1).
-// Sums are trees of depth <= 32 (per thread, wave butterfly, across waves,
-// rescale), adding 32 * 2^-24.  TAU_CUT and TAU_ACC cover one sum against
-// another with both bounds, with about 30 % headroom.
+// One unnormalised term e = 2^(l*log2e - c): the fused multiply-add rounds once,
+// the constant log2e is off by 0.24 * 2^-24 relative, and v_exp_f32 is good to
+// one ulp, so a term with |l - ref| <= 32 has a relative error below
+// (1.24 * 32 + 2) * 2^-24 = 2.5e-6.  Terms more than 32 below the reference are
+// below e^-32 each (V * 1.3e-14 relative to the sum, which is >= 1); terms more
+// than 32 above it are excluded by requiring the sum to stay below 2^46.
+// Sums are trees of depth <= 32 (per thread, wavefront scan, across waves),
+// adding 32 * 2^-24 = 1.9e-6.  A comparison of one sum against another carries
+// both bounds on both sides: at most 1.8e-5, covered by TAU_CUT and TAU_ACC.
 constexpr float TAU_CUT = 2.0e-5f;
 constexpr float TAU_ACC = 3.0e-5f;
 // v_exp_f32 flushes results below 2^-126; absolute slack for products of such
 // terms with sums bounded by V.
 constexpr float ABS_SLACK = 1.0e-30f;
+constexpr float Z_MAX = 7.0e13f;  // just below 2^46 = e^31.9
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -95,256 +99,347 @@ struct Lane<uint16_t> {  // bfloat16 storage
 
 // LDS layout of verify_fast after the raw row
 struct FastShared {
-    float wmax_t[NW], wsum_t[NW], wmax_g[NW], wsum_g[NW];
-    float wtot[NW];       // per-wave totals of the neighbour scan
-    float w_s[NW];        // exclusive sum at the wave's first not-passing slot
-    int w_np[NW];         // first slot that does not definitely pass
-    int w_df[NW];         // first slot that definitely fails
-    int w_bad[NW];        // table entry outside [0,V)
-    int settled;          // row settled by the fp32 path
+    float wmax_t[NW], wmax_g[NW];   // per-wave maxima over the sampled part of the row
+    float wsum_t[NW], wsum_g[NW];   // per-wave sums of exponentials
+    float wtot[NW];                 // per-wave totals of the neighbour terms (first 1024 slots)
+    int wbad[NW];                   // a table entry outside [0,V)
+    int settled;                    // row settled by the fp32 path
+    int pad[3];
+    // from here on the memory is reused by the exact path once the fp32 decision is taken
+    float gs[NT * 4];               // inclusive sums of the neighbour terms within their wavefront
+    unsigned gskip[NT];             // bit q: slot 4*tid+q is the token itself or beyond k
 };
+constexpr size_t FAST_SHARED_HEAD = offsetof(FastShared, gs);
+constexpr size_t FAST_SHARED_TAIL = sizeof(FastShared) - FAST_SHARED_HEAD;
+static_assert(FAST_SHARED_HEAD % 16 == 0, "the exact path's LDS region must be 16-byte aligned");
 
 template <typename LT, bool VEC>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g);
 
-#ifndef LANTERN_FAST_WAVES
-#define LANTERN_FAST_WAVES 0
-#endif
-#if LANTERN_FAST_WAVES > 0
-#define LANTERN_FAST_ATTR __attribute__((amdgpu_waves_per_eu(LANTERN_FAST_WAVES, LANTERN_FAST_WAVES)))
-#else
-#define LANTERN_FAST_ATTR
-#endif
 #ifndef LANTERN_EXTRA_LDS
 #define LANTERN_EXTRA_LDS 0
 #endif
+#ifndef LANTERN_PERSISTENT
+#define LANTERN_PERSISTENT 0
+#endif
+#ifndef LANTERN_WGS_PER_CU
+#define LANTERN_WGS_PER_CU 2
+#endif
 
-template <typename LT, int NV>
-__global__ __launch_bounds__(NT) LANTERN_FAST_ATTR void verify_fast(VerifyArgs a) {
+constexpr int SPL = 16;              // table slots per lane when one wavefront walks 1024 slots
+constexpr int FAST_MAX_K = 8192;     // keeps the scan's summation depth inside the margin
+
+// Per-row scalars that are fetched one row ahead.
+struct RowMeta {
+    int xt;        // draft token
+    float u_acc;   // acceptance draw
+    float lg_tok;  // draft logit of the token
+    int nb[4];     // table slots 4*tid .. 4*tid+3
+};
+
+// fp32 path, persistent: workgroup b handles rows b, b + gridDim.x, ... and keeps the
+// loads of its next row in flight while it works on the current one.
+// FULL: the row fills all NV vector slots of every thread (no bounds checks).
+//
+// Exponentials are taken as 2^(l*log2e - c) with one reference c per row, common to all
+// terms of that row, so its own rounding cancels in every comparison.  The reference is
+// the maximum over the first vector slot of every thread (an eighth of the row at NV = 8)
+// rather than the row maximum: any element of the row works, because the sum then holds
+// a term equal to one (Z >= 1) and every term is at most Z; rows whose sum exceeds 2^46
+// (an element more than 32 above the reference) are left to the exact path.
+template <typename LT, int NV, bool FULL, bool PERSIST>
+__global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* s_row = smem;
     const int row_bytes = (a.V * (int)sizeof(LT) + 15) & ~15;
     FastShared& sh = *reinterpret_cast<FastShared*>(smem + row_bytes);
+    unsigned char* ex_lds = reinterpret_cast<unsigned char*>(sh.gs);
 
-    const int row = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = tid >> 6;
     const int V = a.V;
     const int k = a.k;
-
-    const int xt = a.tokens[row];
-    const bool tok_ok = (unsigned)xt < (unsigned)V;
-    const int xs = tok_ok ? xt : 0;
-
-    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
-    const LT* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
-    const uint4* tv = reinterpret_cast<const uint4*>(trow);
-    const uint4* gv = reinterpret_cast<const uint4*>(grow);
+    const int N = a.N;
     const int nvec = V / EPV;
-
-    // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
-    uint4 T[NV], G[NV];
-#pragma unroll
-    for (int c = 0; c < NV; ++c) {
-        const int vi = c * NT + tid;
-        if (vi < nvec) {
-            T[c] = load_stream16(tv + vi);
-            G[c] = load_stream16(gv + vi);
-        } else {
-            T[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
-            G[c] = T[c];
-        }
-    }
-
-    // first chunk of the table row: 4 consecutive slots per thread
-    const int32_t* nrow = a.knn + (int64_t)xs * k;
+    const int stride_rows = gridDim.x;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
-    int nb[4];
-    {
+
+    uint4 Tn[NV], Gn[NV];
+    RowMeta mn;
+    int xt_after = 0;  // token of the row after the next one
+
+    auto issue_row = [&](int r, uint4 (&Tn)[NV], uint4 (&Gn)[NV]) {
+        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)r * a.stride);
+        const uint4* gv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride);
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            const int vi = c * NT + tid;
+            if (FULL || vi < nvec) {
+                Tn[c] = load_stream16(tv + vi);
+                Gn[c] = load_stream16(gv + vi);
+            } else {
+                Tn[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+                Gn[c] = Tn[c];
+            }
+        }
+    };
+    auto issue_meta = [&](int r, int xt, RowMeta& mn) {
+        mn.xt = xt;
+        const int xs = ((unsigned)xt < (unsigned)V) ? xt : 0;
+        const int32_t* nrow = a.knn + (int64_t)xs * k;
         const int j0 = tid * 4;
         if (nvec_ok && j0 + 3 < k) {
             const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
-            nb[0] = q.x; nb[1] = q.y; nb[2] = q.z; nb[3] = q.w;
+            mn.nb[0] = q.x; mn.nb[1] = q.y; mn.nb[2] = q.z; mn.nb[3] = q.w;
         } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
+            for (int q = 0; q < 4; ++q) mn.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
         }
-    }
-    const float u_acc = a.uniforms[2 * (int64_t)row];
-    const float lg_tok = L::glob(grow, xs);
+        mn.u_acc = a.uniforms[2 * (int64_t)r];
+        mn.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, xs);
+    };
 
-    // ---- raw target row to LDS, wave-local maxima ----
-    float mt = neg_inf_f(), mg = neg_inf_f();
-#pragma unroll
-    for (int c = 0; c < NV; ++c) {
-        const int vi = c * NT + tid;
-        if (vi < nvec) reinterpret_cast<uint4*>(s_row)[vi] = T[c];
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) {
-            mt = fmaxf(mt, L::get(T[c], e));
-            mg = fmaxf(mg, L::get(G[c], e));
-        }
-    }
-    mt = wave_max(mt);
-    mg = wave_max(mg);
-    // a slice that is all -inf contributes nothing; subtracting 0 keeps 2^-inf = 0
-    const float mt_s = (mt == neg_inf_f()) ? 0.f : mt;
-    const float mg_s = (mg == neg_inf_f()) ? 0.f : mg;
-
-    // ---- unnormalised exponentials relative to the wave maximum, summed ----
-    float st = 0.f, sg = 0.f;
-#pragma unroll
-    for (int c = 0; c < NV; ++c) {
-        float et[EPV], eg[EPV];
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) {
-            et[e] = hw_exp2((L::get(T[c], e) - mt_s) * LOG2E_F);
-            eg[e] = hw_exp2((L::get(G[c], e) - mg_s) * LOG2E_F);
-        }
-#pragma unroll
-        for (int s = EPV / 2; s > 0; s >>= 1)
-#pragma unroll
-            for (int e = 0; e < s; ++e) {
-                et[e] += et[e + s];
-                eg[e] += eg[e + s];
-            }
-        st += et[0];
-        sg += eg[0];
-    }
-    st = wave_sum(st);
-    sg = wave_sum(sg);
-    if (lane == 0) {
-        sh.wmax_t[wave] = mt; sh.wsum_t[wave] = st;
-        sh.wmax_g[wave] = mg; sh.wsum_g[wave] = sg;
-    }
-    __syncthreads();
-
-    float Mt = neg_inf_f(), Mg = neg_inf_f();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        Mt = fmaxf(Mt, sh.wmax_t[w]);
-        Mg = fmaxf(Mg, sh.wmax_g[w]);
-    }
-    float Zt = 0.f, Zg = 0.f;  // sums of 2^((l - M) log2e) over the row; NaN if the row is unusable
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        Zt += sh.wsum_t[w] * hw_exp2((sh.wmax_t[w] - Mt) * LOG2E_F);
-        Zg += sh.wsum_g[w] * hw_exp2((sh.wmax_g[w] - Mg) * LOG2E_F);
+    int row = blockIdx.x;
+    if (row >= N) return;
+    uint4 T[NV], G[NV];
+    RowMeta m;
+    if (PERSIST) {
+        issue_row(row, Tn, Gn);
+        issue_meta(row, a.tokens[row], mn);
+        if (row + stride_rows < N) xt_after = a.tokens[row + stride_rows];
+    } else {
+        issue_row(row, T, G);
+        issue_meta(row, a.tokens[row], m);
     }
 
-    // ---- neighbourhood walk as a prefix scan over the k table slots ----
-    const float R = a.delta * Zt;               // cut: inclusive sum < delta * Zt
-    const float cut_lo = R * (1.f - TAU_CUT) - ABS_SLACK;
-    const float cut_hi = R * (1.f + TAU_CUT) + ABS_SLACK;
-    float carry = 0.f;
-    int first_np = INT_MAX, first_df = INT_MAX;
-    float s_cut = 0.f;
-    int bad = tok_ok ? 0 : 1;
-
-    for (int base = 0; base < k; base += NT * 4) {
-        const int j0 = base + tid * 4;
-        if (base > 0) {
+    while (true) {
+        const int next = row + stride_rows;
+        if (PERSIST) {
+            // the prefetched row becomes the current one; start fetching the next
 #pragma unroll
-            for (int q = 0; q < 4; ++q) nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
-        }
-        float p[4];
-        float run = 0.f;
-        int my_np = INT_MAX, my_df = INT_MAX;
-        bool is_self[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bool valid = j0 + q < k;
-            const int n = nb[q];
-            const bool inr = (unsigned)n < (unsigned)V;
-            if (valid && !inr) bad = 1;
-            float e = 0.f;
-            is_self[q] = (n == xt) || !valid;
-            if (valid && inr && n != xt) e = hw_exp2((L::lds(s_row, n) - Mt) * LOG2E_F);
-            run += e;
-            p[q] = run;
-        }
-        const float incl = wave_scan_incl(run);
-        const float excl = wave_prev(incl, 0.f);
-        if (lane == WAVE - 1) sh.wtot[wave] = incl;
-        __syncthreads();
-        float woff = 0.f, ctot = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float v = sh.wtot[w];
-            if (w < wave) woff += v;
-            ctot += v;
-        }
-        const float off = carry + woff + excl;
-        float my_s = 0.f;
-#pragma unroll
-        for (int q = 3; q >= 0; --q) {
-            if (!is_self[q]) {
-                const float I = off + p[q];
-                if (!(I < cut_lo)) { my_np = j0 + q; my_s = off + (q ? p[q - 1] : 0.f); }
-                if (I > cut_hi) my_df = j0 + q;
+            for (int c = 0; c < NV; ++c) { T[c] = Tn[c]; G[c] = Gn[c]; }
+            m = mn;
+            if (next < N) {
+                issue_row(next, Tn, Gn);
+                issue_meta(next, xt_after, mn);
+                if (next + stride_rows < N) xt_after = a.tokens[next + stride_rows];
             }
         }
-        // wave-level first not-pass / first definite-fail
-        const int w_np = wave_min(my_np);
-        const int w_df = wave_min(my_df);
-        const unsigned long long owner = __ballot(my_np == w_np && my_np != INT_MAX);
-        float w_s = 0.f;
-        if (owner) w_s = __shfl(my_s, __ffsll((long long)owner) - 1, WAVE);
-        if (lane == 0) { sh.w_np[wave] = w_np; sh.w_df[wave] = w_df; sh.w_s[wave] = w_s; }
-        __syncthreads();
-        if (first_np == INT_MAX) {
+        const int xt = m.xt;
+        const bool tok_ok = (unsigned)xt < (unsigned)V;
+        const int xs = tok_ok ? xt : 0;
+
+        // ---- raw target row to LDS; reference = maximum over vector slot 0 of every thread ----
 #pragma unroll
-            for (int w = NW - 1; w >= 0; --w) {
-                if (sh.w_np[w] != INT_MAX) { first_np = sh.w_np[w]; s_cut = sh.w_s[w]; }
-                if (sh.w_df[w] != INT_MAX) first_df = sh.w_df[w];
+        for (int c = 0; c < NV; ++c) {
+            const int vi = c * NT + tid;
+            if (FULL || vi < nvec) reinterpret_cast<uint4*>(s_row)[vi] = T[c];
+        }
+        float rt = neg_inf_f(), rg = neg_inf_f();
+#pragma unroll
+        for (int e = 0; e < EPV; e += 2) {
+            rt = fmaxf(rt, fmaxf(L::get(T[0], e), L::get(T[0], e + 1)));
+            rg = fmaxf(rg, fmaxf(L::get(G[0], e), L::get(G[0], e + 1)));
+        }
+        rt = wave_max(rt);
+        rg = wave_max(rg);
+        if (lane == 0) { sh.wmax_t[wave] = rt; sh.wmax_g[wave] = rg; }
+        __syncthreads();  // the row is in LDS and the wave maxima are published
+        rt = sh.wmax_t[0];
+        rg = sh.wmax_g[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            rt = fmaxf(rt, sh.wmax_t[w]);
+            rg = fmaxf(rg, sh.wmax_g[w]);
+        }
+        // a sampled part without a finite logit: reference 0 (large rows then overflow and fall through)
+        if (rt == neg_inf_f()) rt = 0.f;
+        if (rg == neg_inf_f()) rg = 0.f;
+        const float ct = rt * LOG2E_F;   // rounded once; common to every term of the row
+        const float cg = rg * LOG2E_F;
+
+        // ---- exponentials 2^(l*log2e - c), summed ----
+        float st = 0.f, sg = 0.f;
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+            float et[EPV], eg[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                et[e] = hw_exp2(__builtin_fmaf(L::get(T[c], e), LOG2E_F, -ct));
+                eg[e] = hw_exp2(__builtin_fmaf(L::get(G[c], e), LOG2E_F, -cg));
+            }
+#pragma unroll
+            for (int s = EPV / 2; s > 0; s >>= 1)
+#pragma unroll
+                for (int e = 0; e < s; ++e) {
+                    et[e] += et[e + s];
+                    eg[e] += eg[e + s];
+                }
+            st += et[0];
+            sg += eg[0];
+        }
+        st = wave_sum(st);
+        sg = wave_sum(sg);
+
+        // ---- neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront ----
+        {
+            float run = 0.f;
+            float p[4];
+            unsigned skip = 0;
+            int bad = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool valid = tid * 4 + q < k;
+                const int n = m.nb[q];
+                const bool inr = (unsigned)n < (unsigned)V;
+                if (valid && !inr) bad = 1;
+                float e = 0.f;
+                if (n == xt || !valid) skip |= 1u << q;
+                else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
+                run += e;
+                p[q] = run;
+            }
+            const float incl = wave_scan_incl(run);
+            const float excl = wave_prev(incl, 0.f);
+            reinterpret_cast<float4*>(sh.gs)[tid] = make_float4(excl + p[0], excl + p[1], excl + p[2], excl + p[3]);
+            sh.gskip[tid] = skip;
+            bad = wave_or(bad);
+            if (lane == WAVE - 1) sh.wtot[wave] = incl;
+            if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; sh.wbad[wave] = bad; }
+        }
+        __syncthreads();  // sums and neighbour partial sums are published
+
+        // ---- wavefront 0: cut, mass, acceptance ----
+        if (wave == 0) {
+            float Zt = 0.f, Zg = 0.f;
+            int bad = tok_ok ? 0 : 1;
+            float woff[NW];
+            float run_off = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                Zt += sh.wsum_t[w];
+                Zg += sh.wsum_g[w];
+                bad |= sh.wbad[w];
+                woff[w] = run_off;
+                run_off += sh.wtot[w];
+            }
+            const float R = a.delta * Zt;               // cut: inclusive sum < delta * Zt
+            const float cut_lo = R * (1.f - TAU_CUT) - ABS_SLACK;
+            const float cut_hi = R * (1.f + TAU_CUT) + ABS_SLACK;
+            // lane l takes slots 16 l .. 16 l + 15: threads 4 l .. 4 l + 3, all in wavefront l / 16
+            const float off = woff[lane >> 4];
+            int my_np = INT_MAX, my_df = INT_MAX;  // first slot not definitely passing / definitely failing
+            float my_s = 0.f;
+            float before = off + ((lane & 15) ? sh.gs[lane * SPL - 1] : 0.f);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float4 v = reinterpret_cast<const float4*>(sh.gs)[lane * 4 + t];
+                const unsigned skip = sh.gskip[lane * 4 + t];
+                const float I[4] = {off + v.x, off + v.y, off + v.z, off + v.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (!((skip >> q) & 1u)) {
+                        if (my_np == INT_MAX && !(I[q] < cut_lo)) { my_np = lane * SPL + t * 4 + q; my_s = before; }
+                        if (my_df == INT_MAX && I[q] > cut_hi) my_df = lane * SPL + t * 4 + q;
+                    }
+                    before = I[q];
+                }
+            }
+            int first_np = wave_min(my_np);
+            int first_df = wave_min(my_df);
+            float s_cut = 0.f;
+            float carry = run_off;
+            if (first_np != INT_MAX) {
+                const unsigned long long owner = __ballot(my_np == first_np);
+                s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s), __ffsll((long long)owner) - 1));
+            } else if (k > NT * 4) {
+                // slots beyond the first 1024: this wavefront walks them 1024 at a time
+                const int32_t* nrow = a.knn + (int64_t)xs * k;
+                for (int base = NT * 4; base < k; base += WAVE * SPL) {
+                    const int j0 = base + lane * SPL;
+                    float ev[SPL];
+                    float run = 0.f;
+                    unsigned skip = 0;
+#pragma unroll
+                    for (int q = 0; q < SPL; ++q) {
+                        const bool valid = j0 + q < k;
+                        const int n = valid ? nrow[j0 + q] : 0;
+                        const bool inr = (unsigned)n < (unsigned)V;
+                        if (valid && !inr) bad = 1;
+                        float e = 0.f;
+                        if (n == xt || !valid) skip |= 1u << q;
+                        else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
+                        ev[q] = e;
+                        run += e;
+                    }
+                    const float incl = wave_scan_incl(run);
+                    const float ctot = lane63_f(incl);
+                    float I = carry + wave_prev(incl, 0.f);
+                    my_np = INT_MAX; my_df = INT_MAX; my_s = 0.f;
+#pragma unroll
+                    for (int q = 0; q < SPL; ++q) {
+                        const float bef = I;
+                        I += ev[q];
+                        if (!((skip >> q) & 1u)) {
+                            if (my_np == INT_MAX && !(I < cut_lo)) { my_np = j0 + q; my_s = bef; }
+                            if (my_df == INT_MAX && I > cut_hi) my_df = j0 + q;
+                        }
+                    }
+                    const int w_np = wave_min(my_np);
+                    if (w_np != INT_MAX) {
+                        const unsigned long long owner = __ballot(my_np == w_np);
+                        first_np = w_np;
+                        first_df = wave_min(my_df);
+                        s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s),
+                                                                         __ffsll((long long)owner) - 1));
+                        break;
+                    }
+                    carry += ctot;
+                }
+                bad = wave_or(bad);
+            }
+
+            const bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
+            const int a_size = (first_np == INT_MAX) ? k : first_np;
+            const float S = (first_np == INT_MAX) ? carry : s_cut;
+            const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
+            const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
+            const float MA = e_tx + S;                // mass * Zt
+            const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
+            const float rhs = MA * Zg;                // mass  * Zt * Zg
+            const bool accept = (lhs + ABS_SLACK) < rhs * (1.f - TAU_ACC);
+            // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
+            const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
+            const bool settled = !bad && sums_ok && cut_definite && accept;
+            if (lane == 0) {
+                if (settled) {
+                    a.out_accept[row] = 1;
+                    a.out_resample[row] = -1;
+                    const float mass = MA / Zt;
+                    const float gx = e_gx / Zg;
+                    if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
+                    if (a.out_mass) a.out_mass[row] = mass;
+                    if (a.out_gtok) a.out_gtok[row] = gx;
+                    if (a.out_asize) a.out_asize[row] = a_size;
+                    if (a.out_path) a.out_path[row] = 0;
+                }
+                sh.settled = settled ? 1 : 0;
             }
         }
-        carry += ctot;
-        if (first_np != INT_MAX) break;  // uniform across the workgroup
-        __syncthreads();                 // wtot / w_np are rewritten by the next chunk
-    }
-    bad = wave_or(bad);
-    if (lane == 0) sh.w_bad[wave] = bad;
-    __syncthreads();
-    bad = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) bad |= sh.w_bad[w];
-
-    if (tid == 0) {
-        const bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
-        const int a_size = (first_np == INT_MAX) ? k : first_np;
-        const float S = (first_np == INT_MAX) ? carry : s_cut;
-        const float e_tx = hw_exp2((L::lds(s_row, xs) - Mt) * LOG2E_F);
-        const float e_gx = hw_exp2((lg_tok - Mg) * LOG2E_F);
-        const float MA = e_tx + S;              // mass * Zt
-        const float lhs = u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
-        const float rhs = MA * Zg;              // mass  * Zt * Zg
-        const bool accept = (lhs + ABS_SLACK) < rhs * (1.f - TAU_ACC);
-        const bool settled = !bad && cut_definite && accept;
-        if (settled) {
-            a.out_accept[row] = 1;
-            a.out_resample[row] = -1;
-            const float mass = MA / Zt;
-            const float gx = e_gx / Zg;
-            if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
-            if (a.out_mass) a.out_mass[row] = mass;
-            if (a.out_gtok) a.out_gtok[row] = gx;
-            if (a.out_asize) a.out_asize[row] = a_size;
-            if (a.out_path) a.out_path[row] = 0;
+        __syncthreads();  // the decision is published; wavefront 0 is done with the LDS row
+        if (!sh.settled) {
+            // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
+            exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
+            __syncthreads();
         }
-        sh.settled = settled ? 1 : 0;
+        if (!PERSIST) break;
+        row = next;
+        if (row >= N) break;
     }
-    __syncthreads();
-    if (sh.settled) return;
-    // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
-    // finite positive normalisers prove there is no NaN / +inf and a finite maximum in both rows
-    const bool rows_finite = (Zt > 0.f) && (Zt < __builtin_huge_valf()) && (Zg > 0.f) && (Zg < __builtin_huge_valf());
-    exact_row<LT, true>(a, row, smem + ((row_bytes + (int)sizeof(FastShared) + 15) & ~15), s_row, rows_finite,
-                        Mt, Mg);
 }
 
 // ---------------------------------------------------------------------------
@@ -420,30 +515,59 @@ __device__ __forceinline__ double block_scan_incl(double v, double* red, int tid
     return off + incl;
 }
 
-// EPV consecutive logits of a row as floats; vector vi covers tokens
-// [vi*EPV, vi*EPV+EPV).  Tokens at or beyond V read as -inf.  With VEC the row
-// is 16-byte aligned and V a multiple of EPV; lds, when not null, holds the
-// same row in LDS.
+// The exact path walks a row four logits per lane at a time (8-byte loads for
+// bf16, 16-byte loads for fp32): vector vi covers tokens [4 vi, 4 vi + 4).
+// Tokens at or beyond V read as -inf.  With VEC the row is 16-byte aligned and
+// V a multiple of four; lds, when not null, holds the same row in LDS.
+constexpr int EXV = 4;
+
 template <typename LT, bool VEC>
-struct VecLoad {
-    static constexpr int EPV = Lane<LT>::EPV;
-    __device__ static __forceinline__ void load(const LT* row, const unsigned char* lds, int vi, int V,
-                                                float (&out)[EPV]) {
+struct VecLoad;
+
+template <bool VEC>
+struct VecLoad<float, VEC> {
+    __device__ static __forceinline__ void load(const float* row, const unsigned char* lds, int vi, int V,
+                                                float (&out)[EXV]) {
         if (VEC) {
-            if ((vi + 1) * EPV <= V) {
-                const uint4 v = lds ? reinterpret_cast<const uint4*>(lds)[vi]
-                                    : reinterpret_cast<const uint4*>(row)[vi];
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) out[e] = Lane<LT>::get(v, e);
-            } else {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) out[e] = neg_inf_f();
+            if ((vi + 1) * EXV <= V) {
+                const float4 v = lds ? reinterpret_cast<const float4*>(lds)[vi]
+                                     : reinterpret_cast<const float4*>(row)[vi];
+                out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+                return;
             }
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
         } else {
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                const int x = vi * EPV + e;
-                out[e] = x < V ? Lane<LT>::glob(row, x) : neg_inf_f();
+            for (int e = 0; e < EXV; ++e) {
+                const int x = vi * EXV + e;
+                out[e] = x < V ? row[x] : neg_inf_f();
+            }
+        }
+    }
+};
+
+template <bool VEC>
+struct VecLoad<uint16_t, VEC> {
+    __device__ static __forceinline__ void load(const uint16_t* row, const unsigned char* lds, int vi, int V,
+                                                float (&out)[EXV]) {
+        if (VEC) {
+            if ((vi + 1) * EXV <= V) {
+                const uint2 v = lds ? reinterpret_cast<const uint2*>(lds)[vi]
+                                    : reinterpret_cast<const uint2*>(row)[vi];
+                out[0] = __uint_as_float(v.x << 16);
+                out[1] = __uint_as_float(v.x & 0xFFFF0000u);
+                out[2] = __uint_as_float(v.y << 16);
+                out[3] = __uint_as_float(v.y & 0xFFFF0000u);
+                return;
+            }
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
+        } else {
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) {
+                const int x = vi * EXV + e;
+                out[e] = x < V ? Lane<uint16_t>::glob(row, x) : neg_inf_f();
             }
         }
     }
@@ -451,8 +575,8 @@ struct VecLoad {
 
 // LDS the exact path needs beyond whatever precedes it: reductions, a bitmask
 // of A over the vocabulary, one fp64 partial sum per (vector chunk, wavefront).
-__host__ __device__ inline size_t exact_lds_bytes(int V, int epv) {
-    const size_t nvec = ((size_t)V + epv - 1) / epv;
+__host__ __device__ inline size_t exact_lds_bytes(int V) {
+    const size_t nvec = ((size_t)V + EXV - 1) / EXV;
     const size_t nchunk = (nvec + NT - 1) / NT;
     return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 + nchunk * NW * sizeof(double);
 }
@@ -482,7 +606,7 @@ template <typename LT, bool VEC>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g) {
     using L = Lane<LT>;
-    constexpr int EPV = L::EPV;
+    constexpr int EPV = EXV;
     ExactShared& sh = *reinterpret_cast<ExactShared*>(ex);
     uint32_t* mask = reinterpret_cast<uint32_t*>(ex + ((sizeof(ExactShared) + 15) & ~size_t(15)));
 
@@ -742,18 +866,47 @@ static hipError_t allow_lds(K kernel, size_t lds) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
+// Dynamic LDS of verify_fast: raw row, the head of FastShared, then a region that holds either
+// the neighbour partial sums or the exact path's data.
 template <typename LT>
-static size_t fast_exact_offset(int V) {
+static size_t fast_lds_bytes(int V) {
     const size_t row_bytes = ((size_t)V * sizeof(LT) + 15) & ~size_t(15);
-    return (row_bytes + sizeof(FastShared) + 15) & ~size_t(15);
+    const size_t tail = exact_lds_bytes(V) > FAST_SHARED_TAIL ? exact_lds_bytes(V) : FAST_SHARED_TAIL;
+    return row_bytes + FAST_SHARED_HEAD + tail;
+}
+
+// Workgroups of the persistent fast kernel: LANTERN_WGS_PER_CU per compute unit of the current device.
+[[maybe_unused]] static int fast_grid_size() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256 * LANTERN_WGS_PER_CU;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev] = cus * LANTERN_WGS_PER_CU;
+    }
+    return cached[dev];
 }
 
 template <typename LT, int NV>
 static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
-    const size_t lds = fast_exact_offset<LT>(a.V) + exact_lds_bytes(a.V, Lane<LT>::EPV) + LANTERN_EXTRA_LDS;
-    const hipError_t e = allow_lds(&verify_fast<LT, NV>, lds);
+    const size_t lds = fast_lds_bytes<LT>(a.V) + LANTERN_EXTRA_LDS;
+    const bool full = a.V == NV * NT * Lane<LT>::EPV;
+#if LANTERN_PERSISTENT
+    // persistent workgroups: a fixed number per compute unit, each walking rows with a stride
+    int grid = fast_grid_size();
+    if (grid > a.N) grid = a.N;
+    constexpr bool P = true;
+#else
+    const int grid = a.N;   // one workgroup per row
+    constexpr bool P = false;
+#endif
+    hipError_t e = full ? allow_lds(&verify_fast<LT, NV, true, P>, lds) : allow_lds(&verify_fast<LT, NV, false, P>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_fast<LT, NV>), dim3(a.N), dim3(NT), lds, stream, a);
+    if (full)
+        hipLaunchKernelGGL((verify_fast<LT, NV, true, P>), dim3(grid), dim3(NT), lds, stream, a);
+    else
+        hipLaunchKernelGGL((verify_fast<LT, NV, false, P>), dim3(grid), dim3(NT), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -762,7 +915,7 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
     constexpr int EPV = Lane<LT>::EPV;
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
                             (uintptr_t)(a.stride * (int64_t)sizeof(LT));
-    if ((align & 15) == 0 && (a.V % EPV) == 0) {
+    if ((align & 15) == 0 && (a.V % EPV) == 0 && a.k <= FAST_MAX_K) {
         const int nvec = a.V / EPV;
         const int nv = (nvec + NT - 1) / NT;
         if (nv <= 1) return launch_fast_nv<LT, 1>(a, stream);
@@ -771,7 +924,7 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
         if (nv <= 8) return launch_fast_nv<LT, 8>(a, stream);
         if (nv <= 16) return launch_fast_nv<LT, 16>(a, stream);
     }
-    const size_t lds = exact_lds_bytes(a.V, EPV);
+    const size_t lds = exact_lds_bytes(a.V);
     const hipError_t e = allow_lds(&verify_exact<LT>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((verify_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
