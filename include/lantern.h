@@ -77,7 +77,11 @@ size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, i
  *              (c_i[t]-c_j[t])^2 with every operation rounded separately;
  *              equal distances are ordered by the lower token index.
  *   workspace  device memory of at least lantern_build_knn_workspace_bytes,
- *              256-byte aligned
+ *              256-byte aligned.  Scratch, except that when the work has
+ *              finished its first int32 holds the number of rows whose
+ *              pre-selection could not be proven complete and that were
+ *              therefore ranked from all V exact distances (slow; zero for
+ *              codebooks without massive exact ties).
  *
  * An approximate distance from a matrix-core contraction only pre-selects
  * candidates; the order written is always the fp64 one, so the result does

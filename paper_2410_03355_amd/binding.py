@@ -91,8 +91,9 @@ def knn_workspace_bytes(cb_dtype: int, V: int, d: int, k: int) -> int:
     return int(load().lantern_build_knn_workspace_bytes(cb_dtype, V, d, k))
 
 
-def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None) -> torch.Tensor:
-    """lantern_build_knn on a [V, d] device tensor; returns int32 [V, k] on the device."""
+def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None, return_stats: bool = False):
+    """lantern_build_knn on a [V, d] device tensor; returns int32 [V, k] on the device.
+    With return_stats also a device int32 scalar tensor: rows ranked by the exact all-pairs pass."""
     lib = load()
     _need_cuda(codebook)
     if codebook.dim() != 2 or not codebook.is_contiguous():
@@ -110,6 +111,8 @@ def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None) -
     if rc != OK:
         raise LanternError(rc, "lantern_build_knn")
     ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    if return_stats:
+        return out, ws[:4].view(torch.int32)[0]
     return out
 
 

@@ -28,7 +28,7 @@ constexpr int SLOW_WGS = 128;     // workgroups (and fp64 row buffers) of the ex
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct KnnLayout {
-    size_t norms, nmax, dist, flags, slow, total;
+    size_t stats, norms, nmax, dist, flags, slow, total;
     int row_block;
 };
 
@@ -36,6 +36,7 @@ static KnnLayout knn_layout(int V) {
     KnnLayout L;
     L.row_block = V < ROW_BLOCK ? V : ROW_BLOCK;
     size_t off = 0;
+    L.stats = off; off = align_up(off + 256, 256);   // int32[0]: rows that took the exact all-pairs pass
     L.norms = off; off = align_up(off + sizeof(float) * (size_t)V, 256);
     L.nmax = off;  off = align_up(off + 256, 256);
     L.dist = off;  off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
@@ -294,27 +295,53 @@ __global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const f
 }
 
 // ---- stage 2: select, re-rank exactly, emit ----
+constexpr int HBINS = 2048;          // histogram bins per refinement level (11 bits of the key)
+constexpr int HB_PER_THREAD = HBINS / NT;
+
+template <int CAP>
 struct SelectShared {
-    double key[CAND_CAP];
-    int idx[CAND_CAP];
-    unsigned hist[256];
-    int digit;
-    int remaining;
+    double key[CAP];      // the histogram lives in the first bytes until the candidates are known
+    int idx[CAP];
+    unsigned red_u[2 * NW];
     int count;
+    unsigned thr_max;
+    int sel_bin;
+    int sel_below;
 };
 
 // Error model of the approximate keys:
 //   |approximate - exact| <= err_rel * |exact| + err_abs + err_norm * (norm_i + max norm)
 // (the last term applies when norms is not null: keys formed as n_i + n_j - 2 G_ij).
-template <typename CT>
+//
+// NK > 0: the row's V <= NK * 256 approximate keys are held in registers as order-preserving
+// unsigned integers; NK == 0: they are re-read from the workspace in every pass.
+// The (k-1+pad)-th smallest key is located with histograms of 2048 bins over the keys'
+// integer range, refined inside the threshold bin until the candidate set fits the LDS
+// (at most three levels cover 32 bits).
+// Runs body(e) for every key slot of a thread: fully unrolled when the keys sit in registers.
+template <int NK, typename F>
+__device__ __forceinline__ void for_keys(int npt, F body) {
+    if (NK > 0) {
+#pragma unroll
+        for (int e = 0; e < NK; ++e) body(e);
+    } else {
+        for (int e = 0; e < npt; ++e) body(e);
+    }
+}
+
+template <typename CT, int NK, int CAP>
 __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
                                                  const float* dist, float err_rel, float err_abs,
                                                  float err_norm, const float* norms, const float* nmax,
                                                  int32_t* out, int* flags) {
-    __shared__ SelectShared sh;
+    static_assert(CAP * sizeof(double) >= HBINS * sizeof(unsigned), "histogram must fit in the key array");
+    __shared__ SelectShared<CAP> sh;
+    unsigned* hist = reinterpret_cast<unsigned*>(sh.key);
     const int row = blockIdx.x;
     const int i = r0 + row;
     const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
     const float* drow = dist + (int64_t)row * V;
     int32_t* orow = out + (int64_t)i * k;
     const int need = k - 1;
@@ -323,61 +350,119 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         flags[row] = 0;
     }
     if (need == 0) return;
-    const int pad = 32 + need / 32;
+    const int pad = 16 + need / 64;
     const int want = min(V - 1, need + pad);
-    if (want > CAND_CAP) {
+    if (want > CAP) {
         if (tid == 0) flags[row] = 1;
         return;
     }
 
-    // radix select: key of the want-th smallest approximate key among j != i
-    uint32_t prefix = 0;
-    int remaining = want;
-    for (int pass = 3; pass >= 0; --pass) {
-        const int shift = pass * 8;
-        const uint32_t himask = pass == 3 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        sh.hist[tid] = 0;
-        __syncthreads();
-        for (int j = tid; j < V; j += NT) {
-            if (j == i) continue;
-            const uint32_t key = ord_key(drow[j]);
-            if ((key & himask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+    constexpr int NKR = NK > 0 ? NK : 1;
+    uint32_t keys[NKR];
+    const int npt = NK > 0 ? NK : (V + NT - 1) / NT;   // keys per thread
+    // key of element e of this thread (token e * NT + tid); 0xFFFFFFFF for the row's own token and padding
+    auto key_at = [&](int e) -> uint32_t {
+        if (NK > 0) return keys[e];
+        const int j = e * NT + tid;
+        return (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+    };
+    if (NK > 0) {
+#pragma unroll
+        for (int e = 0; e < NKR; ++e) {
+            const int j = e * NT + tid;
+            keys[e] = (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
         }
-        __syncthreads();
-        if (tid == 0) {
-            int cum = 0, b = 0;
-            for (; b < 255; ++b) {
-                const int h = (int)sh.hist[b];
-                if (cum + h >= remaining) break;
-                cum += h;
-            }
-            sh.digit = b;
-            sh.remaining = remaining - cum;
-        }
-        __syncthreads();
-        prefix |= (uint32_t)sh.digit << shift;
-        remaining = sh.remaining;
-        __syncthreads();
     }
-    const uint32_t thr_key = prefix;
-    const float thr = ord_inv(thr_key);
 
-    // compaction of every j != i with approximate key <= threshold
-    if (tid == 0) sh.count = 0;
+    // range of the keys
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+    for_keys<NK>(npt, [&](int e) {
+        const uint32_t key = key_at(e);
+        if (key != 0xFFFFFFFFu) { kmin = min(kmin, key); kmax = max(kmax, key); }
+    });
+    // unsigned order through signed scans: flip the top bit
+    kmin = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMin>((int)(kmin ^ 0x80000000u), INT_MAX), 63) ^ 0x80000000u;
+    kmax = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMax>((int)(kmax ^ 0x80000000u), INT_MIN), 63) ^ 0x80000000u;
+    if (lane == 0) { sh.red_u[wave] = kmin; sh.red_u[NW + wave] = kmax; }
     __syncthreads();
-    for (int j = tid; j < V; j += NT) {
-        if (j == i) continue;
-        if (ord_key(drow[j]) <= thr_key) {
-            const int slot = atomicAdd(&sh.count, 1);
-            if (slot < CAND_CAP) sh.idx[slot] = j;
+    kmin = sh.red_u[0]; kmax = sh.red_u[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { kmin = min(kmin, sh.red_u[w]); kmax = max(kmax, sh.red_u[NW + w]); }
+
+    // histogram refinement: keys in [lo, lo + (HBINS << shift)) are binned by (key - lo) >> shift
+    uint32_t lo = kmin;
+    int shift = 0;
+    while (((uint64_t)(kmax - kmin) >> shift) >= (uint64_t)HBINS) ++shift;
+    int below = 0;               // keys strictly below lo: all of them are candidates
+    uint32_t thr_key = kmax;     // every key <= thr_key is a candidate
+    for (int level = 0; level < 4; ++level) {
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < HB_PER_THREAD; ++b) hist[b * NT + tid] = 0;
+        __syncthreads();
+        const uint64_t span = (uint64_t)HBINS << shift;
+        for_keys<NK>(npt, [&](int e) {
+            const uint32_t key = key_at(e);
+            if (key != 0xFFFFFFFFu && key >= lo && (uint64_t)(key - lo) < span)
+                atomicAdd(&hist[(key - lo) >> shift], 1u);
+        });
+        __syncthreads();
+        // bin whose cumulative count first reaches the number still wanted: thread tid owns bins 8 tid .. 8 tid + 7
+        const int still = want - below;
+        unsigned local[HB_PER_THREAD];
+        unsigned tsum = 0;
+#pragma unroll
+        for (int b = 0; b < HB_PER_THREAD; ++b) { local[b] = hist[tid * HB_PER_THREAD + b]; tsum += local[b]; }
+        const int incl = wave_scan_i<OpSum>((int)tsum, 0);
+        if (lane == WAVE - 1) sh.red_u[wave] = (unsigned)incl;
+        __syncthreads();
+        int woff = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) if (w < wave) woff += (int)sh.red_u[w];
+        int cum = woff + incl - (int)tsum;   // keys in bins before this thread's
+        if (cum < still && cum + (int)tsum >= still) {
+#pragma unroll
+            for (int b = 0; b < HB_PER_THREAD; ++b) {
+                if (cum < still && cum + (int)local[b] >= still) { sh.sel_bin = tid * HB_PER_THREAD + b; sh.sel_below = cum; }
+                cum += (int)local[b];
+            }
         }
+        __syncthreads();
+        const int bin = sh.sel_bin;
+        const int cnt_below_bin = sh.sel_below;
+        const int in_bin = (int)hist[bin];
+        const uint32_t bin_lo = lo + ((uint32_t)bin << shift);
+        const uint32_t bin_hi = (uint32_t)min((uint64_t)bin_lo + (((uint64_t)1 << shift) - 1), (uint64_t)0xFFFFFFFEu);
+        if (below + cnt_below_bin + in_bin <= CAP || shift == 0) {
+            thr_key = bin_hi;   // take the whole bin
+            break;
+        }
+        // too many keys share the bin: keep what lies below it and split the bin itself
+        below += cnt_below_bin;
+        lo = bin_lo;
+        shift = shift > 11 ? shift - 11 : 0;
     }
+
+    // compaction of every j != i with approximate key <= threshold; the largest such key
+    if (tid == 0) { sh.count = 0; sh.thr_max = 0u; }
+    __syncthreads();
+    uint32_t my_max = 0u;
+    for_keys<NK>(npt, [&](int e) {
+        const uint32_t key = key_at(e);
+        if (key <= thr_key) {   // the row's own token and padding carry 0xFFFFFFFF > thr_key
+            const int slot = atomicAdd(&sh.count, 1);
+            if (slot < CAP) sh.idx[slot] = e * NT + tid;
+            my_max = max(my_max, key);
+        }
+    });
+    atomicMax(&sh.thr_max, my_max);
     __syncthreads();
     const int count = sh.count;
-    if (count > CAND_CAP) {  // too many ties at the threshold
+    if (count > CAP) {  // more equal keys at the threshold than the LDS holds
         if (tid == 0) flags[row] = 1;
         return;
     }
+    const float thr = ord_inv(sh.thr_max);   // every discarded token has an approximate key above this
     int P = 1;
     while (P < count) P <<= 1;
     for (int c = tid; c < P; c += NT) {
@@ -417,7 +502,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         if (norms) eabs += (double)err_norm * ((double)norms[i] + (double)*nmax);
         const double num = (double)thr - eabs;
         const double floor_discarded = num - 1.01 * (double)err_rel * fabs(num);
-        ok = last <= floor_discarded;
+        ok = count >= need && last <= floor_discarded;
     }
     if (!ok) {
         if (tid == 0) flags[row] = 1;
@@ -430,12 +515,13 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
 template <typename CT>
 __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d, int k, int metric, int r0,
                                                      int rows, const int* flags, double* bufs,
-                                                     int32_t* out) {
+                                                     int32_t* out, int* stats) {
     const int tid = threadIdx.x;
     double* buf = bufs + (int64_t)blockIdx.x * V;
     const int need = k - 1;
     for (int row = blockIdx.x; row < rows; row += gridDim.x) {
         if (!flags[row]) continue;  // uniform
+        if (tid == 0) atomicAdd(stats, 1);
         const int i = r0 + row;
         __syncthreads();
         for (int j = tid; j < V; j += NT)
@@ -456,6 +542,8 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
     }
 }
 
+__global__ void knn_clear_stats(int* stats) { stats[threadIdx.x] = 0; }
+
 template <typename CT>
 static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
     const KnnLayout L = knn_layout(a.V);
@@ -464,6 +552,8 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
     int* flags = reinterpret_cast<int*>(ws + L.flags);
     double* slow = reinterpret_cast<double*>(ws + L.slow);
     const CT* cb = static_cast<const CT*>(a.codebook);
+    int* stats = reinterpret_cast<int*>(ws + L.stats);
+    hipLaunchKernelGGL(knn_clear_stats, dim3(1), dim3(64), 0, stream, stats);
     float* norms = reinterpret_cast<float*>(ws + L.norms);
     float* nmax = reinterpret_cast<float*>(ws + L.nmax);
     // matrix-core path: rows 16-byte aligned and coordinates in whole vectors
@@ -501,12 +591,23 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
             hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
                                cb, a.V, a.d, r0, a.metric, dist);
         }
-        hipLaunchKernelGGL((knn_select<CT>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k, a.metric,
-                           r0, dist, err_rel, err_abs, err_norm, mfma && a.metric == 0 ? norms : nullptr, nmax,
-                           a.out, flags);
+        const float* nsel = mfma && a.metric == 0 ? norms : nullptr;
+        // candidate capacity: 2048 slots (24 KB of LDS) when k allows, else 4096
+        const bool small_cap = (a.k - 1) + 16 + (a.k - 1) / 64 + 512 <= 2048;
+#define LANTERN_LAUNCH_SELECT(NKV, CAPV)                                                                    \
+        hipLaunchKernelGGL((knn_select<CT, NKV, CAPV>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k,  \
+                           a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
+#define LANTERN_LAUNCH_SELECT_NK(NKV)                                                                       \
+        do { if (small_cap) LANTERN_LAUNCH_SELECT(NKV, 2048); else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP); } while (0)
+        if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8);
+        else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32);
+        else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64);
+        else LANTERN_LAUNCH_SELECT_NK(0);
+#undef LANTERN_LAUNCH_SELECT_NK
+#undef LANTERN_LAUNCH_SELECT
         const int wgs = rows < SLOW_WGS ? rows : SLOW_WGS;
         hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
-                           a.metric, r0, rows, flags, slow, a.out);
+                           a.metric, r0, rows, flags, slow, a.out, stats);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

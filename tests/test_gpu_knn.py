@@ -8,9 +8,11 @@ from synth import workloads
 pytestmark = pytest.mark.gpu
 
 
-def _gpu_table(lantern, cb, k, metric="l2"):
-    out = lantern.build_knn(cb.cuda(), k, metric=metric)
+def _gpu_table(lantern, cb, k, metric="l2", max_exact_rows=None):
+    out, exact_rows = lantern.build_knn(cb.cuda(), k, metric=metric, return_stats=True)
     torch.cuda.synchronize()
+    if max_exact_rows is not None:  # the matrix-core pre-selection must settle (nearly) every row itself
+        assert int(exact_rows.item()) <= max_exact_rows, f"{int(exact_rows.item())} rows took the all-pairs pass"
     return out.cpu().numpy()
 
 
@@ -30,7 +32,7 @@ def _check_structure(table, V, k):
 def test_tiny_full_table(oracle_mod, lantern_gpu):
     cfg = workloads.CONFIGS["tiny"]
     cb = workloads.make_codebook(cfg)
-    got = _gpu_table(lantern_gpu, cb, cfg.k)
+    got = _gpu_table(lantern_gpu, cb, cfg.k, max_exact_rows=0)
     want = oracle_mod.build_knn(cb.numpy(), cfg.k, threads=8)
     np.testing.assert_array_equal(got, want)
 
@@ -40,7 +42,7 @@ def test_full_size_tables(oracle_mod, lantern_gpu, name):
     """Full-size build on the GPU; the oracle recomputes a sample of rows one by one."""
     cfg = workloads.CONFIGS[name]
     cb = workloads.make_codebook(cfg)
-    got = _gpu_table(lantern_gpu, cb, cfg.k)
+    got = _gpu_table(lantern_gpu, cb, cfg.k, max_exact_rows=0)
     _check_structure(got, cfg.V, cfg.k)
     rng = np.random.default_rng(cfg.index)
     rows = np.concatenate([[0, 1, cfg.V - 1, 2047, 2048], rng.integers(0, cfg.V, 40)])
@@ -72,6 +74,13 @@ def test_exact_ties_and_duplicates(oracle_mod, lantern_gpu):
         got = _gpu_table(lantern_gpu, torch.from_numpy(lattice), k)
         want = oracle_mod.build_knn(lattice, k, threads=8)
         np.testing.assert_array_equal(got, want)
+    # more equal keys than the candidate buffer holds: the rows must go to the all-pairs pass
+    # (and be counted), not be guessed
+    same = torch.ones(3000, 4)
+    got, exact_rows = lantern_gpu.build_knn(same.cuda(), 5, return_stats=True)
+    torch.cuda.synchronize()
+    assert int(exact_rows.item()) == 3000
+    np.testing.assert_array_equal(got.cpu().numpy(), oracle_mod.build_knn(same.numpy(), 5, threads=8))
     rng = np.random.default_rng(5)
     base = rng.standard_normal((40, 8)).astype(np.float32)
     dup = base[rng.integers(0, 40, 600)]           # 600 codes, only 40 distinct
