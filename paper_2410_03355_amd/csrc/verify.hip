@@ -53,11 +53,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // 16-byte load of data that is read once: non-temporal, so the streamed rows
 // do not evict the neighbour table from the caches.
 __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
-#ifdef LANTERN_PLAIN_LOADS
-    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
-#else
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-#endif
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -117,20 +113,10 @@ template <typename LT, bool VEC>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g);
 
-#ifndef LANTERN_EXTRA_LDS
-#define LANTERN_EXTRA_LDS 0
-#endif
-#ifndef LANTERN_PERSISTENT
-#define LANTERN_PERSISTENT 0
-#endif
-#ifndef LANTERN_WGS_PER_CU
-#define LANTERN_WGS_PER_CU 2
-#endif
-
 constexpr int SPL = 16;              // table slots per lane when one wavefront walks 1024 slots
 constexpr int FAST_MAX_K = 8192;     // keeps the scan's summation depth inside the margin
 
-// Per-row scalars that are fetched one row ahead.
+// Per-row scalars and table slots, fetched together with the row.
 struct RowMeta {
     int xt;        // draft token
     float u_acc;   // acceptance draw
@@ -138,8 +124,7 @@ struct RowMeta {
     int nb[4];     // table slots 4*tid .. 4*tid+3
 };
 
-// fp32 path, persistent: workgroup b handles rows b, b + gridDim.x, ... and keeps the
-// loads of its next row in flight while it works on the current one.
+// fp32 path, one workgroup per row.
 // FULL: the row fills all NV vector slots of every thread (no bounds checks).
 //
 // Exponentials are taken as 2^(l*log2e - c) with one reference c per row, common to all
@@ -148,7 +133,7 @@ struct RowMeta {
 // rather than the row maximum: any element of the row works, because the sum then holds
 // a term equal to one (Z >= 1) and every term is at most Z; rows whose sum exceeds 2^46
 // (an element more than 32 above the reference) are left to the exact path.
-template <typename LT, int NV, bool FULL, bool PERSIST>
+template <typename LT, int NV, bool FULL>
 __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
@@ -163,72 +148,46 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     const int wave = tid >> 6;
     const int V = a.V;
     const int k = a.k;
-    const int N = a.N;
     const int nvec = V / EPV;
-    const int stride_rows = gridDim.x;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
+    const int row = blockIdx.x;
 
-    uint4 Tn[NV], Gn[NV];
-    RowMeta mn;
-    int xt_after = 0;  // token of the row after the next one
-
-    auto issue_row = [&](int r, uint4 (&Tn)[NV], uint4 (&Gn)[NV]) {
-        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)r * a.stride);
-        const uint4* gv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride);
+    // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
+    uint4 T[NV], G[NV];
+    {
+        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride);
+        const uint4* gv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride);
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
             const int vi = c * NT + tid;
             if (FULL || vi < nvec) {
-                Tn[c] = load_stream16(tv + vi);
-                Gn[c] = load_stream16(gv + vi);
+                T[c] = load_stream16(tv + vi);
+                G[c] = load_stream16(gv + vi);
             } else {
-                Tn[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
-                Gn[c] = Tn[c];
+                T[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+                G[c] = T[c];
             }
         }
-    };
-    auto issue_meta = [&](int r, int xt, RowMeta& mn) {
-        mn.xt = xt;
-        const int xs = ((unsigned)xt < (unsigned)V) ? xt : 0;
-        const int32_t* nrow = a.knn + (int64_t)xs * k;
+    }
+    // token, its table slots 4*tid .. 4*tid+3, acceptance draw, draft logit of the token
+    RowMeta m;
+    {
+        m.xt = a.tokens[row];
+        const int xs0 = ((unsigned)m.xt < (unsigned)V) ? m.xt : 0;
+        const int32_t* nrow = a.knn + (int64_t)xs0 * k;
         const int j0 = tid * 4;
         if (nvec_ok && j0 + 3 < k) {
             const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
-            mn.nb[0] = q.x; mn.nb[1] = q.y; mn.nb[2] = q.z; mn.nb[3] = q.w;
+            m.nb[0] = q.x; m.nb[1] = q.y; m.nb[2] = q.z; m.nb[3] = q.w;
         } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mn.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
+            for (int q = 0; q < 4; ++q) m.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
         }
-        mn.u_acc = a.uniforms[2 * (int64_t)r];
-        mn.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, xs);
-    };
-
-    int row = blockIdx.x;
-    if (row >= N) return;
-    uint4 T[NV], G[NV];
-    RowMeta m;
-    if (PERSIST) {
-        issue_row(row, Tn, Gn);
-        issue_meta(row, a.tokens[row], mn);
-        if (row + stride_rows < N) xt_after = a.tokens[row + stride_rows];
-    } else {
-        issue_row(row, T, G);
-        issue_meta(row, a.tokens[row], m);
+        m.u_acc = a.uniforms[2 * (int64_t)row];
+        m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride, xs0);
     }
 
-    while (true) {
-        const int next = row + stride_rows;
-        if (PERSIST) {
-            // the prefetched row becomes the current one; start fetching the next
-#pragma unroll
-            for (int c = 0; c < NV; ++c) { T[c] = Tn[c]; G[c] = Gn[c]; }
-            m = mn;
-            if (next < N) {
-                issue_row(next, Tn, Gn);
-                issue_meta(next, xt_after, mn);
-                if (next + stride_rows < N) xt_after = a.tokens[next + stride_rows];
-            }
-        }
+    {
         const int xt = m.xt;
         const bool tok_ok = (unsigned)xt < (unsigned)V;
         const int xs = tok_ok ? xt : 0;
@@ -434,11 +393,7 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
         if (!sh.settled) {
             // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
             exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
-            __syncthreads();
         }
-        if (!PERSIST) break;
-        row = next;
-        if (row >= N) break;
     }
 }
 
@@ -875,38 +830,16 @@ static size_t fast_lds_bytes(int V) {
     return row_bytes + FAST_SHARED_HEAD + tail;
 }
 
-// Workgroups of the persistent fast kernel: LANTERN_WGS_PER_CU per compute unit of the current device.
-[[maybe_unused]] static int fast_grid_size() {
-    static int cached[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256 * LANTERN_WGS_PER_CU;
-    if (cached[dev] == 0) {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-        cached[dev] = cus * LANTERN_WGS_PER_CU;
-    }
-    return cached[dev];
-}
-
 template <typename LT, int NV>
 static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
-    const size_t lds = fast_lds_bytes<LT>(a.V) + LANTERN_EXTRA_LDS;
+    const size_t lds = fast_lds_bytes<LT>(a.V);
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-#if LANTERN_PERSISTENT
-    // persistent workgroups: a fixed number per compute unit, each walking rows with a stride
-    int grid = fast_grid_size();
-    if (grid > a.N) grid = a.N;
-    constexpr bool P = true;
-#else
-    const int grid = a.N;   // one workgroup per row
-    constexpr bool P = false;
-#endif
-    hipError_t e = full ? allow_lds(&verify_fast<LT, NV, true, P>, lds) : allow_lds(&verify_fast<LT, NV, false, P>, lds);
+    const hipError_t e = full ? allow_lds(&verify_fast<LT, NV, true>, lds) : allow_lds(&verify_fast<LT, NV, false>, lds);
     if (e != hipSuccess) return e;
     if (full)
-        hipLaunchKernelGGL((verify_fast<LT, NV, true, P>), dim3(grid), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((verify_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
     else
-        hipLaunchKernelGGL((verify_fast<LT, NV, false, P>), dim3(grid), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((verify_fast<LT, NV, false>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
 }
 
