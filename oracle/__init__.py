@@ -57,6 +57,9 @@ def _load():
                                       i32p, i32p, ctypes.c_int, ctypes.c_double, f32p, i32p, i32p,
                                       f64p, ctypes.c_int]
         lib.oracle_verify.restype = ctypes.c_int
+        lib.oracle_verify_greedy.argtypes = [f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int64, i32p, i32p,
+                                             ctypes.c_int, ctypes.c_double, i32p, i32p, f64p, ctypes.c_int]
+        lib.oracle_verify_greedy.restype = ctypes.c_int
         lib.oracle_diag_count.restype = ctypes.c_int
         lib.oracle_max_threads.restype = ctypes.c_int
         assert lib.oracle_diag_count() == len(DIAG_NAMES)
@@ -164,3 +167,26 @@ def verify(target_logits, draft_logits, draft_tokens, knn, k: int, delta: float,
         raise ValueError("oracle_verify: bad arguments")
     d = {n: diag[:, i] for i, n in enumerate(DIAG_NAMES)} if want_diag else None
     return acc, res, d
+
+
+def verify_greedy(target_logits, draft_tokens, knn, k: int, delta: float, threads: int = 1):
+    """Greedy-decoding variant.  Returns (accept int32[N], token int32[N], diag dict) where
+    diag has mass, other (largest distorted-target value outside the draft token) and a_size."""
+    lib = _load()
+    tl = _as_f32(target_logits)
+    if tl.ndim != 2:
+        raise ValueError("logits must be [N, V]")
+    N, V = tl.shape
+    tok = _as_i32(draft_tokens).reshape(-1)
+    tab = _as_i32(knn)
+    if tok.shape[0] != N or tab.size != V * k:
+        raise ValueError("shape mismatch")
+    acc = np.empty(N, dtype=np.int32)
+    out = np.empty(N, dtype=np.int32)
+    diag = np.empty((N, 3), dtype=np.float64)
+    rc = lib.oracle_verify_greedy(_p(tl, ctypes.c_float), N, V, V, _p(tok, ctypes.c_int32),
+                                  _p(tab, ctypes.c_int32), int(k), float(delta), _p(acc, ctypes.c_int32),
+                                  _p(out, ctypes.c_int32), _p(diag, ctypes.c_double), int(threads))
+    if rc != 0:
+        raise ValueError("oracle_verify_greedy: bad arguments")
+    return acc, out, {"mass": diag[:, 0], "other": diag[:, 1], "a_size": diag[:, 2]}

@@ -390,6 +390,86 @@ int oracle_verify(const float* target_logits, const float* draft_logits, int N, 
     return failed ? -1 : 0;
 }
 
+
+/* ------------------------------------------------------------------------- */
+/* Greedy decoding variant (Section 4.3, last sentence)                       */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Accept xt iff xt = argmax_x t_A(x), where t_A is the distorted target
+ * induced by A_{k,delta}(xt): the mass of A at xt, zero on the rest of A, t
+ * elsewhere.  The arg-max takes the lowest token index among equal values.
+ * out_token[i] is -1 when accepted and that arg-max otherwise (the token
+ * greedy decoding of the distorted target emits).  No drafter probabilities
+ * and no random draws are involved.
+ * diag (optional, [N,3]): mass, the largest t_A outside xt, a_size.
+ * Unusable rows get -1 in both outputs, as in oracle_verify.
+ */
+int oracle_verify_greedy(const float* target_logits, int N, int V, int64_t row_stride,
+                         const int32_t* draft_tokens, const int32_t* knn, int k, double delta,
+                         int32_t* out_accept, int32_t* out_token, double* diag, int threads) {
+    if (N < 0 || V < 1 || k < 1 || k > V || row_stride < V || !(delta >= 0.0)) return -1;
+    if (N == 0) return 0;
+    if (!target_logits || !draft_tokens || !knn || !out_accept || !out_token) return -1;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads > 0 ? threads : 1)
+#endif
+    {
+        double* buf = (double*)malloc(sizeof(double) * 2 * (size_t)V);
+        if (!buf) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+            double* t = buf;
+            double* ta = buf + V;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (int i = 0; i < N; ++i) {
+                double* dg = diag ? diag + (size_t)i * 3 : NULL;
+                if (dg) dg[0] = dg[1] = dg[2] = NAN;
+                int xt = draft_tokens[i];
+                int ok = (xt >= 0 && xt < V) && row_args_ok(V, xt, knn + (size_t)xt * k, k);
+                if (ok) ok = softmax_row(target_logits + (size_t)i * row_stride, V, t) == 0;
+                if (!ok) {
+                    out_accept[i] = -1;
+                    out_token[i] = -1;
+                    continue;
+                }
+                const int32_t* nbrs = knn + (size_t)xt * k;
+                /* the same nearest-first walk as in verify_probs */
+                double d_tv = 0.0;
+                int a = 0;
+                for (int j = 0; j < k; ++j) {
+                    int x = nbrs[j];
+                    if (x == xt) { a = j + 1; continue; }
+                    double cand = d_tv + t[x];
+                    if (cand < delta) { d_tv = cand; a = j + 1; } else break;
+                }
+                double mass = t[xt] + d_tv;
+                memcpy(ta, t, sizeof(double) * (size_t)V);
+                for (int j = 0; j < a; ++j)
+                    if (nbrs[j] != xt) ta[nbrs[j]] = 0.0;
+                ta[xt] = mass;
+                int best = 0;
+                for (int x = 1; x < V; ++x)
+                    if (ta[x] > ta[best]) best = x;   /* strict: the lowest index wins ties */
+                double other = -1.0;
+                for (int x = 0; x < V; ++x)
+                    if (x != xt && ta[x] > other) other = ta[x];
+                out_accept[i] = (best == xt) ? 1 : 0;
+                out_token[i] = (best == xt) ? -1 : best;
+                if (dg) { dg[0] = mass; dg[1] = other; dg[2] = (double)a; }
+            }
+        }
+        free(buf);
+    }
+    return failed ? -1 : 0;
+}
+
 int oracle_max_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
