@@ -152,6 +152,27 @@ int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                       float* out_accept_prob, float* out_mass, float* out_g_tok,
                       int32_t* out_a_size, int32_t* out_path, void* hip_stream);
 
+/*
+ * Greedy-decoding variant (Section 4.3, last sentence): accept the draft token
+ * xt iff xt = argmax_x t_A(x), where t_A is the target distribution distorted
+ * by A_{k,delta}(xt) (the mass of A at xt, zero on the rest of A, t elsewhere).
+ * Equal values go to the lower token index.  No drafter logits and no random
+ * draws are involved.
+ *
+ *   target_logits, draft_tokens, knn, k, delta   as in lantern_verify
+ *   out_accept [N] int32: 1 accepted, 0 rejected
+ *   out_token  [N] int32: -1 when accepted, else argmax_x t_A(x), the token
+ *              greedy decoding of the distorted target emits
+ *   out_path   [N] int32 or NULL: 0 settled by the fp32 pass, 1 evaluated in fp64
+ * Unusable rows (see lantern_verify) get -1 in both outputs.  Decisions are
+ * exact with respect to fp64 evaluation, as for lantern_verify.
+ * Errors: E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_DEVICE.
+ */
+int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype, int N, int V,
+                          int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
+                          float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
+                          void* hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* lantern_status_string(int status);
 

@@ -22,7 +22,8 @@ E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -
 
 EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
-    "lantern_verify", "lantern_verify_ex", "lantern_status_string", "lantern_version",
+    "lantern_verify", "lantern_verify_ex", "lantern_verify_greedy", "lantern_status_string",
+    "lantern_version",
 )
 
 _lib = None
@@ -56,6 +57,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_ex.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp,
                                       vp, vp, vp, vp, vp, vp]
     lib.lantern_verify_ex.restype = i32
+    lib.lantern_verify_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp, vp]
+    lib.lantern_verify_greedy.restype = i32
     lib.lantern_status_string.argtypes = [i32]
     lib.lantern_status_string.restype = ctypes.c_char_p
     lib.lantern_version.argtypes = []
@@ -177,3 +180,31 @@ def verify_ex(target_logits, draft_logits, draft_tokens, knn, delta: float, unif
     if rc != OK:
         raise LanternError(rc, "lantern_verify_ex")
     return out
+
+
+def verify_greedy(target_logits, draft_tokens, knn, delta: float, stream=None, want_path: bool = False):
+    """lantern_verify_greedy; returns (accept int32[N], token int32[N]) device tensors
+    (and the per-row path tensor when want_path)."""
+    lib = load()
+    _need_cuda(target_logits, draft_tokens, knn)
+    if target_logits.dim() != 2 or target_logits.stride(1) != 1:
+        raise ValueError("logits must be a [N, V] tensor with dense rows")
+    N, V = target_logits.shape
+    if draft_tokens.dtype != torch.int32 or knn.dtype != torch.int32:
+        raise TypeError("draft_tokens and knn must be int32")
+    if draft_tokens.numel() != N or knn.dim() != 2 or knn.shape[0] != V:
+        raise ValueError("shape mismatch between logits, tokens and the table")
+    if not (draft_tokens.is_contiguous() and knn.is_contiguous()):
+        raise ValueError("draft_tokens and knn must be contiguous")
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev)
+    tok = torch.empty(N, dtype=torch.int32, device=dev)
+    path = torch.empty(N, dtype=torch.int32, device=dev) if want_path else None
+    rc = lib.lantern_verify_greedy(target_logits.data_ptr(), _dtype_code(target_logits), N, V,
+                                   target_logits.stride(0) if N > 1 else V, draft_tokens.data_ptr(),
+                                   knn.data_ptr(), int(knn.shape[1]), float(delta), acc.data_ptr(),
+                                   tok.data_ptr(), path.data_ptr() if want_path else None,
+                                   _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_greedy")
+    return (acc, tok, path) if want_path else (acc, tok)

@@ -70,6 +70,32 @@ int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                        out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
 }
 
+int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype, int N, int V,
+                          int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
+                          float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
+                          void* hip_stream) {
+    if (!dtype_ok((int)logits_dtype)) return LANTERN_E_DTYPE;
+    if (N < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
+        return LANTERN_E_SHAPE;
+    if (!(delta >= 0.0f)) return LANTERN_E_DELTA;
+    if (N == 0) return LANTERN_OK;
+    if (!target_logits || !draft_tokens || !knn || !out_accept || !out_token) return LANTERN_E_NULL;
+    lantern::GreedyArgs a;
+    a.target = target_logits;
+    a.N = N;
+    a.V = V;
+    a.stride = row_stride_elems;
+    a.tokens = draft_tokens;
+    a.knn = knn;
+    a.k = k;
+    a.delta = delta;
+    a.out_accept = out_accept;
+    a.out_token = out_token;
+    a.out_path = out_path;
+    const hipError_t e = lantern::launch_verify_greedy(a, (int)logits_dtype, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k) {
     if (!dtype_ok((int)cb_dtype) || V < 1 || d < 1 || k < 1 || k > V) return 0;
     return lantern::knn_workspace_bytes(V, d, k);

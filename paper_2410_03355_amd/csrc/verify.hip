@@ -23,75 +23,11 @@
 #include <math.h>
 #include <stdint.h>
 
-#include "device_utils.h"
-#include "exp64.h"
+#include "fast_cut.h"
 #include "verify_args.h"
+#include "verify_common.h"
 
 namespace lantern {
-
-constexpr float LOG2E_F = 1.44269504088896340736f;
-
-// ---- rounding margins of the fp32 pass -------------------------------------
-// One unnormalised term e = 2^(l*log2e - c): the fused multiply-add rounds once,
-// the constant log2e is off by 0.24 * 2^-24 relative, and v_exp_f32 is good to
-// one ulp, so a term with |l - ref| <= 32 has a relative error below
-// (1.24 * 32 + 2) * 2^-24 = 2.5e-6.  Terms more than 32 below the reference are
-// below e^-32 each (V * 1.3e-14 relative to the sum, which is >= 1); terms more
-// than 32 above it are excluded by requiring the sum to stay below 2^46.
-// Sums are trees of depth <= 32 (per thread, wavefront scan, across waves),
-// adding 32 * 2^-24 = 1.9e-6.  A comparison of one sum against another carries
-// both bounds on both sides: at most 1.8e-5, covered by TAU_CUT and TAU_ACC.
-constexpr float TAU_CUT = 2.0e-5f;
-constexpr float TAU_ACC = 3.0e-5f;
-// v_exp_f32 flushes results below 2^-126; absolute slack for products of such
-// terms with sums bounded by V.
-constexpr float ABS_SLACK = 1.0e-30f;
-constexpr float Z_MAX = 7.0e13f;  // just below 2^46 = e^31.9
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// 16-byte load of data that is read once: non-temporal, so the streamed rows
-// do not evict the neighbour table from the caches.
-__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-template <typename LT>
-struct Lane;
-
-template <>
-struct Lane<float> {
-    static constexpr int EPV = 4;  // elements per 16-byte vector
-    static constexpr uint32_t NEG_INF_WORD = 0xFF800000u;
-    __device__ static __forceinline__ float get(const uint4& v, int e) {
-        const uint32_t w = e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
-        return __uint_as_float(w);
-    }
-    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
-        return reinterpret_cast<const float*>(row)[x];
-    }
-    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
-        return reinterpret_cast<const float*>(row)[x];
-    }
-};
-
-template <>
-struct Lane<uint16_t> {  // bfloat16 storage
-    static constexpr int EPV = 8;
-    static constexpr uint32_t NEG_INF_WORD = 0xFF80FF80u;
-    __device__ static __forceinline__ float get(const uint4& v, int e) {
-        const int wi = e >> 1;
-        const uint32_t w = wi == 0 ? v.x : wi == 1 ? v.y : wi == 2 ? v.z : v.w;
-        return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
-    }
-    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
-        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
-    }
-    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
-        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
-    }
-};
 
 // LDS layout of verify_fast after the raw row
 struct FastShared {
@@ -112,9 +48,6 @@ static_assert(FAST_SHARED_HEAD % 16 == 0, "the exact path's LDS region must be 1
 template <typename LT, bool VEC>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g);
-
-constexpr int SPL = 16;              // table slots per lane when one wavefront walks 1024 slots
-constexpr int FAST_MAX_K = 8192;     // keeps the scan's summation depth inside the margin
 
 // Per-row scalars and table slots, fetched together with the row.
 struct RowMeta {
@@ -245,126 +178,24 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
         sg = wave_sum(sg);
 
         // ---- neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront ----
-        {
-            float run = 0.f;
-            float p[4];
-            unsigned skip = 0;
-            int bad = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const bool valid = tid * 4 + q < k;
-                const int n = m.nb[q];
-                const bool inr = (unsigned)n < (unsigned)V;
-                if (valid && !inr) bad = 1;
-                float e = 0.f;
-                if (n == xt || !valid) skip |= 1u << q;
-                else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
-                run += e;
-                p[q] = run;
-            }
-            const float incl = wave_scan_incl(run);
-            const float excl = wave_prev(incl, 0.f);
-            reinterpret_cast<float4*>(sh.gs)[tid] = make_float4(excl + p[0], excl + p[1], excl + p[2], excl + p[3]);
-            sh.gskip[tid] = skip;
-            bad = wave_or(bad);
-            if (lane == WAVE - 1) sh.wtot[wave] = incl;
-            if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; sh.wbad[wave] = bad; }
-        }
+        const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
+        scan_publish<LT>(m.nb, xt, k, V, s_row, ct, scan);
+        if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; }
         __syncthreads();  // sums and neighbour partial sums are published
 
         // ---- wavefront 0: cut, mass, acceptance ----
         if (wave == 0) {
             float Zt = 0.f, Zg = 0.f;
-            int bad = tok_ok ? 0 : 1;
-            float woff[NW];
-            float run_off = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 Zt += sh.wsum_t[w];
                 Zg += sh.wsum_g[w];
-                bad |= sh.wbad[w];
-                woff[w] = run_off;
-                run_off += sh.wtot[w];
             }
-            const float R = a.delta * Zt;               // cut: inclusive sum < delta * Zt
-            const float cut_lo = R * (1.f - TAU_CUT) - ABS_SLACK;
-            const float cut_hi = R * (1.f + TAU_CUT) + ABS_SLACK;
-            // lane l takes slots 16 l .. 16 l + 15: threads 4 l .. 4 l + 3, all in wavefront l / 16
-            const float off = woff[lane >> 4];
-            int my_np = INT_MAX, my_df = INT_MAX;  // first slot not definitely passing / definitely failing
-            float my_s = 0.f;
-            float before = off + ((lane & 15) ? sh.gs[lane * SPL - 1] : 0.f);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float4 v = reinterpret_cast<const float4*>(sh.gs)[lane * 4 + t];
-                const unsigned skip = sh.gskip[lane * 4 + t];
-                const float I[4] = {off + v.x, off + v.y, off + v.z, off + v.w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (!((skip >> q) & 1u)) {
-                        if (my_np == INT_MAX && !(I[q] < cut_lo)) { my_np = lane * SPL + t * 4 + q; my_s = before; }
-                        if (my_df == INT_MAX && I[q] > cut_hi) my_df = lane * SPL + t * 4 + q;
-                    }
-                    before = I[q];
-                }
-            }
-            int first_np = wave_min(my_np);
-            int first_df = wave_min(my_df);
-            float s_cut = 0.f;
-            float carry = run_off;
-            if (first_np != INT_MAX) {
-                const unsigned long long owner = __ballot(my_np == first_np);
-                s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s), __ffsll((long long)owner) - 1));
-            } else if (k > NT * 4) {
-                // slots beyond the first 1024: this wavefront walks them 1024 at a time
-                const int32_t* nrow = a.knn + (int64_t)xs * k;
-                for (int base = NT * 4; base < k; base += WAVE * SPL) {
-                    const int j0 = base + lane * SPL;
-                    float ev[SPL];
-                    float run = 0.f;
-                    unsigned skip = 0;
-#pragma unroll
-                    for (int q = 0; q < SPL; ++q) {
-                        const bool valid = j0 + q < k;
-                        const int n = valid ? nrow[j0 + q] : 0;
-                        const bool inr = (unsigned)n < (unsigned)V;
-                        if (valid && !inr) bad = 1;
-                        float e = 0.f;
-                        if (n == xt || !valid) skip |= 1u << q;
-                        else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
-                        ev[q] = e;
-                        run += e;
-                    }
-                    const float incl = wave_scan_incl(run);
-                    const float ctot = lane63_f(incl);
-                    float I = carry + wave_prev(incl, 0.f);
-                    my_np = INT_MAX; my_df = INT_MAX; my_s = 0.f;
-#pragma unroll
-                    for (int q = 0; q < SPL; ++q) {
-                        const float bef = I;
-                        I += ev[q];
-                        if (!((skip >> q) & 1u)) {
-                            if (my_np == INT_MAX && !(I < cut_lo)) { my_np = j0 + q; my_s = bef; }
-                            if (my_df == INT_MAX && I > cut_hi) my_df = j0 + q;
-                        }
-                    }
-                    const int w_np = wave_min(my_np);
-                    if (w_np != INT_MAX) {
-                        const unsigned long long owner = __ballot(my_np == w_np);
-                        first_np = w_np;
-                        first_df = wave_min(my_df);
-                        s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s),
-                                                                         __ffsll((long long)owner) - 1));
-                        break;
-                    }
-                    carry += ctot;
-                }
-                bad = wave_or(bad);
-            }
-
-            const bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
-            const int a_size = (first_np == INT_MAX) ? k : first_np;
-            const float S = (first_np == INT_MAX) ? carry : s_cut;
+            const CutResult cut = scan_cut<LT>(Zt, a.delta, xt, xs, k, V, a.knn, s_row, ct, scan);
+            const int bad = cut.bad | (tok_ok ? 0 : 1);
+            const bool cut_definite = cut.definite;
+            const int a_size = cut.a_size;
+            const float S = cut.S;
             const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
             const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
             const float MA = e_tx + S;                // mass * Zt
@@ -400,133 +231,6 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
 // ---------------------------------------------------------------------------
 // fp64 evaluation of rows the fp32 path did not settle
 // ---------------------------------------------------------------------------
-
-struct ExactShared {
-    double red[NW];
-    double red2[NW];
-    double bcast[4];
-    int ired[NW];
-    int ibcast[2];
-};
-
-__device__ __forceinline__ double block_sum(double v, double* red, int tid) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
-    __syncthreads();
-    double s = 0.0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
-    return s;
-}
-
-__device__ __forceinline__ double block_max(double v, double* red, int tid) {
-    v = wave_max(v);
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
-    __syncthreads();
-    double s = red[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) s = fmax(s, red[w]);
-    return s;
-}
-
-__device__ __forceinline__ int block_min_i(int v, int* red, int tid) {
-    v = wave_min(v);
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
-    __syncthreads();
-    int s = red[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) s = min(s, red[w]);
-    return s;
-}
-
-__device__ __forceinline__ int block_or_i(int v, int* red, int tid) {
-    v = wave_or(v);
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
-    __syncthreads();
-    int s = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s |= red[w];
-    return s;
-}
-
-// Inclusive prefix sum over the workgroup in thread order; *total gets the sum.
-__device__ __forceinline__ double block_scan_incl(double v, double* red, int tid, double* total) {
-    const double incl = wave_scan_incl(v);
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == WAVE - 1) red[tid >> 6] = incl;
-    __syncthreads();
-    double off = 0.0, tot = 0.0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        const double x = red[w];
-        if (w < (tid >> 6)) off += x;
-        tot += x;
-    }
-    *total = tot;
-    return off + incl;
-}
-
-// The exact path walks a row four logits per lane at a time (8-byte loads for
-// bf16, 16-byte loads for fp32): vector vi covers tokens [4 vi, 4 vi + 4).
-// Tokens at or beyond V read as -inf.  With VEC the row is 16-byte aligned and
-// V a multiple of four; lds, when not null, holds the same row in LDS.
-constexpr int EXV = 4;
-
-template <typename LT, bool VEC>
-struct VecLoad;
-
-template <bool VEC>
-struct VecLoad<float, VEC> {
-    __device__ static __forceinline__ void load(const float* row, const unsigned char* lds, int vi, int V,
-                                                float (&out)[EXV]) {
-        if (VEC) {
-            if ((vi + 1) * EXV <= V) {
-                const float4 v = lds ? reinterpret_cast<const float4*>(lds)[vi]
-                                     : reinterpret_cast<const float4*>(row)[vi];
-                out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-                return;
-            }
-#pragma unroll
-            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
-        } else {
-#pragma unroll
-            for (int e = 0; e < EXV; ++e) {
-                const int x = vi * EXV + e;
-                out[e] = x < V ? row[x] : neg_inf_f();
-            }
-        }
-    }
-};
-
-template <bool VEC>
-struct VecLoad<uint16_t, VEC> {
-    __device__ static __forceinline__ void load(const uint16_t* row, const unsigned char* lds, int vi, int V,
-                                                float (&out)[EXV]) {
-        if (VEC) {
-            if ((vi + 1) * EXV <= V) {
-                const uint2 v = lds ? reinterpret_cast<const uint2*>(lds)[vi]
-                                    : reinterpret_cast<const uint2*>(row)[vi];
-                out[0] = __uint_as_float(v.x << 16);
-                out[1] = __uint_as_float(v.x & 0xFFFF0000u);
-                out[2] = __uint_as_float(v.y << 16);
-                out[3] = __uint_as_float(v.y & 0xFFFF0000u);
-                return;
-            }
-#pragma unroll
-            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
-        } else {
-#pragma unroll
-            for (int e = 0; e < EXV; ++e) {
-                const int x = vi * EXV + e;
-                out[e] = x < V ? Lane<uint16_t>::glob(row, x) : neg_inf_f();
-            }
-        }
-    }
-};
 
 // LDS the exact path needs beyond whatever precedes it: reductions, a bitmask
 // of A over the vocabulary, one fp64 partial sum per (vector chunk, wavefront).
@@ -655,38 +359,10 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     zt = block_sum(zt, sh.red, tid);
     zg = block_sum(zg, sh.red2, tid);
 
-    // ---- nearest-first walk: inclusive sums of t over the table slots ----
-    double carry = 0.0;
-    int a_size = k;
-    double S = 0.0;
-    bool cut_found = false;
-    for (int base = 0; base < k && !cut_found; base += NT) {
-        const int j = base + tid;
-        const bool valid = j < k;
-        const int n = valid ? nrow[j] : xt;
-        const bool self = (n == xt);
-        const float ln = lds_row ? L::lds(lds_row, n) : L::glob(trow, n);
-        const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
-        double ctot;
-        const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
-        const int fail_j = (valid && !self && !(incl < delta)) ? j : INT_MAX;
-        const int first = block_min_i(fail_j, sh.ired, tid);
-        if (first != INT_MAX) {
-            cut_found = true;
-            a_size = first;
-            // sum before the failing slot = inclusive sum of the slot before it
-            if (first == base) {
-                S = carry;
-            } else {
-                if (j == first - 1) sh.bcast[0] = incl;
-                __syncthreads();
-                S = sh.bcast[0];
-            }
-        } else {
-            carry += ctot;
-            S = carry;
-        }
-    }
+    // ---- nearest-first walk over the table row ----
+    int a_size;
+    double S;
+    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, delta, sh, tid, &a_size, &S);
 
     const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
     const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;

@@ -30,3 +30,24 @@ struct VerifyArgs {
 hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream);
 
 }  // namespace lantern
+
+namespace lantern {
+
+// Greedy-decoding variant: target logits only, no random draws.
+struct GreedyArgs {
+    const void* target;       // [N, stride] logits of the target model
+    int N;
+    int V;
+    int64_t stride;
+    const int32_t* tokens;    // [N] draft tokens
+    const int32_t* knn;       // [V, k] neighbour table
+    int k;
+    float delta;
+    int32_t* out_accept;      // [N]
+    int32_t* out_token;       // [N]
+    int32_t* out_path;        // optional, may be null
+};
+
+hipError_t launch_verify_greedy(const GreedyArgs& a, int logits_dtype, hipStream_t stream);
+
+}  // namespace lantern

@@ -1,0 +1,259 @@
+// Pieces shared by the verification kernels (sampling and greedy variants):
+// rounding margins of the fp32 paths, logit unpacking, workgroup reductions in
+// fp64 and the four-logit vector loads of the exact paths.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "device_utils.h"
+#include "exp64.h"
+
+namespace lantern {
+
+constexpr float LOG2E_F = 1.44269504088896340736f;
+
+// ---- rounding margins of the fp32 pass -------------------------------------
+// One unnormalised term e = 2^(l*log2e - c): the fused multiply-add rounds once,
+// the constant log2e is off by 0.24 * 2^-24 relative, and v_exp_f32 is good to
+// one ulp, so a term with |l - ref| <= 32 has a relative error below
+// (1.24 * 32 + 2) * 2^-24 = 2.5e-6.  Terms more than 32 below the reference are
+// below e^-32 each (V * 1.3e-14 relative to the sum, which is >= 1); terms more
+// than 32 above it are excluded by requiring the sum to stay below 2^46.
+// Sums are trees of depth <= 32 (per thread, wavefront scan, across waves),
+// adding 32 * 2^-24 = 1.9e-6.  A comparison of one sum against another carries
+// both bounds on both sides: at most 1.8e-5, covered by TAU_CUT and TAU_ACC.
+constexpr float TAU_CUT = 2.0e-5f;
+constexpr float TAU_ACC = 3.0e-5f;
+// v_exp_f32 flushes results below 2^-126; absolute slack for products of such
+// terms with sums bounded by V.
+constexpr float ABS_SLACK = 1.0e-30f;
+constexpr float Z_MAX = 7.0e13f;  // just below 2^46 = e^31.9
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read once: non-temporal, so the streamed rows
+// do not evict the neighbour table from the caches.
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <typename LT>
+struct Lane;
+
+template <>
+struct Lane<float> {
+    static constexpr int EPV = 4;  // elements per 16-byte vector
+    static constexpr uint32_t NEG_INF_WORD = 0xFF800000u;
+    __device__ static __forceinline__ float get(const uint4& v, int e) {
+        const uint32_t w = e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+        return __uint_as_float(w);
+    }
+    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
+        return reinterpret_cast<const float*>(row)[x];
+    }
+    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
+        return reinterpret_cast<const float*>(row)[x];
+    }
+    __device__ static __forceinline__ void lds_set_neg_inf(unsigned char* row, int x) {
+        reinterpret_cast<uint32_t*>(row)[x] = 0xFF800000u;
+    }
+};
+
+template <>
+struct Lane<uint16_t> {  // bfloat16 storage
+    static constexpr int EPV = 8;
+    static constexpr uint32_t NEG_INF_WORD = 0xFF80FF80u;
+    __device__ static __forceinline__ float get(const uint4& v, int e) {
+        const int wi = e >> 1;
+        const uint32_t w = wi == 0 ? v.x : wi == 1 ? v.y : wi == 2 ? v.z : v.w;
+        return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+    __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
+    }
+    __device__ static __forceinline__ float glob(const void* row, int64_t x) {
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
+    }
+    __device__ static __forceinline__ void lds_set_neg_inf(unsigned char* row, int x) {
+        reinterpret_cast<uint16_t*>(row)[x] = 0xFF80u;
+    }
+};
+
+// ---- fp64 workgroup helpers of the exact paths ----
+
+struct ExactShared {
+    double red[NW];
+    double red2[NW];
+    double bcast[4];
+    int ired[NW];
+    int ibcast[2];
+};
+
+__device__ __forceinline__ double block_sum(double v, double* red, int tid) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    return s;
+}
+
+__device__ __forceinline__ double block_max(double v, double* red, int tid) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    double s = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) s = fmax(s, red[w]);
+    return s;
+}
+
+__device__ __forceinline__ int block_min_i(int v, int* red, int tid) {
+    v = wave_min(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    int s = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) s = min(s, red[w]);
+    return s;
+}
+
+__device__ __forceinline__ int block_or_i(int v, int* red, int tid) {
+    v = wave_or(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    int s = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s |= red[w];
+    return s;
+}
+
+// Inclusive prefix sum over the workgroup in thread order; *total gets the sum.
+__device__ __forceinline__ double block_scan_incl(double v, double* red, int tid, double* total) {
+    const double incl = wave_scan_incl(v);
+    __syncthreads();
+    if ((tid & (WAVE - 1)) == WAVE - 1) red[tid >> 6] = incl;
+    __syncthreads();
+    double off = 0.0, tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const double x = red[w];
+        if (w < (tid >> 6)) off += x;
+        tot += x;
+    }
+    *total = tot;
+    return off + incl;
+}
+
+// The exact path walks a row four logits per lane at a time (8-byte loads for
+// bf16, 16-byte loads for fp32): vector vi covers tokens [4 vi, 4 vi + 4).
+// Tokens at or beyond V read as -inf.  With VEC the row is 16-byte aligned and
+// V a multiple of four; lds, when not null, holds the same row in LDS.
+constexpr int EXV = 4;
+
+template <typename LT, bool VEC>
+struct VecLoad;
+
+template <bool VEC>
+struct VecLoad<float, VEC> {
+    __device__ static __forceinline__ void load(const float* row, const unsigned char* lds, int vi, int V,
+                                                float (&out)[EXV]) {
+        if (VEC) {
+            if ((vi + 1) * EXV <= V) {
+                const float4 v = lds ? reinterpret_cast<const float4*>(lds)[vi]
+                                     : reinterpret_cast<const float4*>(row)[vi];
+                out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+                return;
+            }
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
+        } else {
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) {
+                const int x = vi * EXV + e;
+                out[e] = x < V ? row[x] : neg_inf_f();
+            }
+        }
+    }
+};
+
+template <bool VEC>
+struct VecLoad<uint16_t, VEC> {
+    __device__ static __forceinline__ void load(const uint16_t* row, const unsigned char* lds, int vi, int V,
+                                                float (&out)[EXV]) {
+        if (VEC) {
+            if ((vi + 1) * EXV <= V) {
+                const uint2 v = lds ? reinterpret_cast<const uint2*>(lds)[vi]
+                                    : reinterpret_cast<const uint2*>(row)[vi];
+                out[0] = __uint_as_float(v.x << 16);
+                out[1] = __uint_as_float(v.x & 0xFFFF0000u);
+                out[2] = __uint_as_float(v.y << 16);
+                out[3] = __uint_as_float(v.y & 0xFFFF0000u);
+                return;
+            }
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) out[e] = neg_inf_f();
+        } else {
+#pragma unroll
+            for (int e = 0; e < EXV; ++e) {
+                const int x = vi * EXV + e;
+                out[e] = x < V ? Lane<uint16_t>::glob(row, x) : neg_inf_f();
+            }
+        }
+    }
+};
+
+// Nearest-first walk of the neighbourhood in fp64 (Algorithm 2, inference part), by the
+// whole workgroup: inclusive sums of t over the table slots, 256 slots at a time; the walk
+// ends at the first slot, other than the token itself, whose inclusive sum is not below
+// delta.  *a_size: slots taken; *S: sum of t over the taken slots other than the token.
+// trow: the target row in global memory; lds_row: the same raw row in LDS, or null.
+template <typename LT>
+__device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* lds_row, const int32_t* nrow,
+                                           int k, int xt, double mt, double zt, double delta, ExactShared& sh,
+                                           int tid, int* a_size, double* S) {
+    using L = Lane<LT>;
+    double carry = 0.0;
+    *a_size = k;
+    *S = 0.0;
+    bool cut_found = false;
+    for (int base = 0; base < k && !cut_found; base += NT) {
+        const int j = base + tid;
+        const bool valid = j < k;
+        const int n = valid ? nrow[j] : xt;
+        const bool self = (n == xt);
+        const float ln = lds_row ? L::lds(lds_row, n) : L::glob(trow, n);
+        const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
+        double ctot;
+        const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
+        const int fail_j = (valid && !self && !(incl < delta)) ? j : INT_MAX;
+        const int first = block_min_i(fail_j, sh.ired, tid);
+        if (first != INT_MAX) {
+            cut_found = true;
+            *a_size = first;
+            // sum before the failing slot = inclusive sum of the slot before it
+            if (first == base) {
+                *S = carry;
+            } else {
+                if (j == first - 1) sh.bcast[0] = incl;
+                __syncthreads();
+                *S = sh.bcast[0];
+            }
+        } else {
+            carry += ctot;
+            *S = carry;
+        }
+    }
+}
+
+}  // namespace lantern
