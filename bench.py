@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent"])
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
+    ap.add_argument("--mode", default="sample", choices=["sample", "greedy"],
+                    help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -88,10 +90,21 @@ def main() -> int:
     out_res = [torch.empty(cfg.rows, dtype=torch.int32, device=dev) for _ in range(nbuf)]
     torch.cuda.synchronize()
 
+    greedy = args.mode == "greedy"
+    lib = lantern.load()
+    dcode = lantern.BF16 if cfg.logit_dtype == "bf16" else lantern.F32
+
     def step(i: int):
         b = bufs[i % nbuf]
-        lantern.verify(b.target_logits, b.draft_logits, b.draft_tokens, knn, delta, b.uniforms,
-                       out_accept=out_acc[i % nbuf], out_resample=out_res[i % nbuf], stream=stream)
+        if greedy:
+            rc = lib.lantern_verify_greedy(b.target_logits.data_ptr(), dcode, cfg.rows, cfg.V, cfg.V,
+                                           b.draft_tokens.data_ptr(), knn.data_ptr(), cfg.k, float(delta),
+                                           out_acc[i % nbuf].data_ptr(), out_res[i % nbuf].data_ptr(), None,
+                                           stream.cuda_stream)
+            assert rc == 0, rc
+        else:
+            lantern.verify(b.target_logits, b.draft_logits, b.draft_tokens, knn, delta, b.uniforms,
+                           out_accept=out_acc[i % nbuf], out_resample=out_res[i % nbuf], stream=stream)
 
     for i in range(args.warmup):
         step(i)
@@ -120,6 +133,8 @@ def main() -> int:
     rows = cfg.rows
     logit_bytes = 2 if cfg.logit_dtype == "bf16" else 4
     bytes_per_launch = algorithmic_bytes_per_verification(cfg.V, cfg.k, logit_bytes) * rows
+    if greedy:  # one logit row, the table row, token, two outputs
+        bytes_per_launch = (cfg.V * logit_bytes + 4 * cfg.k + 12) * rows
     achieved_gbs = bytes_per_launch / (kernel_ms_avg * 1e-3) / 1e9
     value = rows * args.steps / wall
 
@@ -140,7 +155,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{cfg.name}/{args.variant}: V={cfg.V} d={cfg.d} k={cfg.k} delta={delta} "
+            "workload": f"{cfg.name}/{args.variant}/{args.mode}: V={cfg.V} d={cfg.d} k={cfg.k} delta={delta} "
                         f"rows_per_step={rows} logits={cfg.logit_dtype}",
             "rows_per_step": rows,
             "distinct_step_buffers": nbuf,
@@ -148,20 +163,20 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "verify_fast",
+            "kernel": "greedy_fast" if greedy else "verify_fast",
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": args.traffic_bytes if args.traffic_bytes is not None
-            else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant)),
+            else (None if greedy else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "kernel_ms_avg": kernel_ms_avg,
         },
         "knn_build_ms": knn_build_ms,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not greedy:
         import numpy as np
         import oracle  # CPU baseline leg only
         threads = min(os.cpu_count() or 1, 16, oracle.max_threads())

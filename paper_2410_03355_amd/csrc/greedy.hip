@@ -18,14 +18,18 @@ namespace lantern {
 struct GreedyShared {
     float wmax[NW];       // per-wave maxima over the sampled part of the row
     float wsum[NW];       // per-wave sums of exponentials
+    float wemax[NW];      // per-wave largest exponential
     float wtot[NW];       // scan: wavefront totals
     int wbad[NW];
     float best_val[NW];   // arg-max outside A: per-wave value and lowest index
     int best_idx[NW];
     int a_size;           // published cut
     int cut_ok;           // cut definite, inputs usable
+    int early_accept;     // the mass of A beats the largest term of the whole row
+    int pad0;
     float mass_z;         // (mass of A) * Z
     float z;              // Z
+    int pad1[2];
     // from here on the memory is reused by the exact path once the fp32 path gives up
     float gs[NT * 4];
     unsigned gskip[NT];
@@ -229,12 +233,14 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     const float ct = rt * LOG2E_F;
 
     // ---- exponentials 2^(l*log2e - c), summed; neighbour terms scanned ----
-    float st = 0.f;
+    float st = 0.f, emax = 0.f;
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
         float et[EPV];
 #pragma unroll
         for (int e = 0; e < EPV; ++e) et[e] = hw_exp2(__builtin_fmaf(L::get(T[c], e), LOG2E_F, -ct));
+#pragma unroll
+        for (int e = 0; e < EPV; e += 2) emax = fmaxf(emax, fmaxf(et[e], et[e + 1]));
 #pragma unroll
         for (int s = EPV / 2; s > 0; s >>= 1)
 #pragma unroll
@@ -242,23 +248,34 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
         st += et[0];
     }
     st = wave_sum(st);
+    emax = wave_max(emax);
     const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
     scan_publish<LT>(nb, xt, k, V, s_row, ct, scan);
-    if (lane == 0) sh.wsum[wave] = st;
+    if (lane == 0) { sh.wsum[wave] = st; sh.wemax[wave] = emax; }
     __syncthreads();
 
     // ---- wavefront 0: the cut ----
     if (wave == 0) {
-        float Zt = 0.f;
+        float Zt = 0.f, Emax = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) Zt += sh.wsum[w];
+        for (int w = 0; w < NW; ++w) { Zt += sh.wsum[w]; Emax = fmaxf(Emax, sh.wemax[w]); }
         const CutResult cut = scan_cut<LT>(Zt, a.delta, xt, xs, k, V, a.knn, s_row, ct, scan);
         const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX);
+        const bool cut_ok = cut.definite && !cut.bad && tok_ok && sums_ok;
+        const float mass_z = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct)) + cut.S;
+        // no term of the row, inside or outside A, reaches the mass of A: accepted without looking at A
+        const bool early = cut_ok && (mass_z * (1.f - TAU_ACC) > Emax * (1.f + TAU_ACC) + ABS_SLACK);
         if (lane == 0) {
             sh.a_size = cut.a_size;
-            sh.cut_ok = (cut.definite && !cut.bad && tok_ok && sums_ok) ? 1 : 0;
-            sh.mass_z = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct)) + cut.S;
+            sh.cut_ok = cut_ok ? 1 : 0;
+            sh.early_accept = early ? 1 : 0;
+            sh.mass_z = mass_z;
             sh.z = Zt;
+            if (early) {
+                a.out_accept[row] = 1;
+                a.out_token[row] = -1;
+                if (a.out_path) a.out_path[row] = 0;
+            }
         }
     }
     __syncthreads();
@@ -266,6 +283,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
         greedy_exact_row<LT, true>(a, row, ex_lds, s_row);
         return;
     }
+    if (sh.early_accept) return;
     const int a_size = sh.a_size;
     const float mass_z = sh.mass_z;
 
