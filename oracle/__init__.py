@@ -190,3 +190,23 @@ def verify_greedy(target_logits, draft_tokens, knn, k: int, delta: float, thread
     if rc != 0:
         raise ValueError("oracle_verify_greedy: bad arguments")
     return acc, out, {"mass": diag[:, 0], "other": diag[:, 1], "a_size": diag[:, 2]}
+
+
+def accept_chains(accept, resample, L: int):
+    """Walk of B drafted chains of L candidates; returns (kept int32[B], next_token int32[B])."""
+    lib = _load()
+    lib.oracle_accept_chains.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                                         ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32),
+                                         ctypes.POINTER(ctypes.c_int32)]
+    lib.oracle_accept_chains.restype = ctypes.c_int
+    acc = _as_i32(accept).reshape(-1)
+    res = _as_i32(resample).reshape(-1)
+    if acc.shape != res.shape or acc.shape[0] % L:
+        raise ValueError("shape mismatch")
+    B = acc.shape[0] // L
+    n = np.empty(B, dtype=np.int32)
+    nxt = np.empty(B, dtype=np.int32)
+    if lib.oracle_accept_chains(_p(acc, ctypes.c_int32), _p(res, ctypes.c_int32), B, L,
+                                _p(n, ctypes.c_int32), _p(nxt, ctypes.c_int32)) != 0:
+        raise ValueError("oracle_accept_chains: bad arguments")
+    return n, nxt

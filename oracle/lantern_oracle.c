@@ -477,3 +477,39 @@ int oracle_max_threads(void) {
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------------- */
+/* Walk of a drafted chain (Algorithm 1, the loop over t = 1..L)              */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * B chains of L candidates each; chain b owns rows b*L .. b*L+L-1 of accept /
+ * resample in drafting order.  The drafts are taken while they are accepted;
+ * at the first candidate that is not accepted the loop exits with that row's
+ * resampled token.  out_len[b]: number of drafts kept.  out_next[b]: the
+ * resampled token that follows them; -1 when all L were accepted (the caller
+ * then samples the extra token from the target's next row); -2 when the first
+ * row that was not accepted is an unusable one (accept = -1).
+ */
+int oracle_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L,
+                         int32_t* out_len, int32_t* out_next) {
+    if (B < 0 || L < 1) return -1;
+    if (B == 0) return 0;
+    if (!accept || !resample || !out_len || !out_next) return -1;
+    for (int b = 0; b < B; ++b) {
+        int n = 0;
+        int next = -1;
+        for (int t = 0; t < L; ++t) {
+            int a = accept[(size_t)b * L + t];
+            if (a == 1) {
+                n = n + 1;
+            } else {
+                next = (a == 0) ? resample[(size_t)b * L + t] : -2;
+                break;
+            }
+        }
+        out_len[b] = n;
+        out_next[b] = next;
+    }
+    return 0;
+}
