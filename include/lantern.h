@@ -173,6 +173,24 @@ int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype,
                           float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
                           void* hip_stream);
 
+/*
+ * Walk of B drafted chains of L candidates each (Algorithm 1, the loop over
+ * the drafts): chain b owns rows b*L .. b*L+L-1 of the outputs of
+ * lantern_verify (or lantern_verify_greedy), in drafting order.  Drafts are
+ * kept while they are accepted; the first candidate that is not accepted ends
+ * the chain with its resampled token.
+ *
+ *   accept, resample  [B*L] int32, as written by lantern_verify
+ *   out_len   [B] int32: number of drafts kept (0..L)
+ *   out_next  [B] int32: the token that follows them: the resampled token of
+ *             the first rejected candidate; -1 when all L were accepted (the
+ *             caller then samples the extra token from the target's next row);
+ *             -2 when the chain was ended by an unusable row (accept = -1)
+ * Errors: E_NULL, E_SHAPE (B < 0, L < 1), E_DEVICE.  B = 0 does nothing.
+ */
+int lantern_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L, int32_t* out_len,
+                          int32_t* out_next, void* hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* lantern_status_string(int status);
 

@@ -4,7 +4,7 @@ Python names mirror the C ABI of include/lantern.h: build_knn, verify,
 verify_ex.  The work is done by hand-written gfx950 kernels in liblantern.so.
 """
 from .binding import (  # noqa: F401
-    BF16, F32, MAX_VOCAB, METRIC_COSINE, METRIC_L2, EXPORTS, LanternError, build_knn,
+    BF16, F32, MAX_VOCAB, METRIC_COSINE, METRIC_L2, EXPORTS, LanternError, accept_chains, build_knn,
     knn_workspace_bytes, load, status_string, verify, verify_ex, verify_greedy,
 )
 from .build import LIB_PATH, build  # noqa: F401

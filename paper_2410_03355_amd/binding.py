@@ -22,7 +22,8 @@ E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -
 
 EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
-    "lantern_verify", "lantern_verify_ex", "lantern_verify_greedy", "lantern_status_string",
+    "lantern_verify", "lantern_verify_ex", "lantern_verify_greedy", "lantern_accept_chains",
+    "lantern_status_string",
     "lantern_version",
 )
 
@@ -59,6 +60,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_ex.restype = i32
     lib.lantern_verify_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp, vp]
     lib.lantern_verify_greedy.restype = i32
+    lib.lantern_accept_chains.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.lantern_accept_chains.restype = i32
     lib.lantern_status_string.argtypes = [i32]
     lib.lantern_status_string.restype = ctypes.c_char_p
     lib.lantern_version.argtypes = []
@@ -208,3 +211,24 @@ def verify_greedy(target_logits, draft_tokens, knn, delta: float, stream=None, w
     if rc != OK:
         raise LanternError(rc, "lantern_verify_greedy")
     return (acc, tok, path) if want_path else (acc, tok)
+
+
+def accept_chains(accept, resample, L: int, stream=None):
+    """lantern_accept_chains; accept / resample are int32 device tensors of B*L rows.
+    Returns (kept int32[B], next_token int32[B])."""
+    lib = load()
+    _need_cuda(accept, resample)
+    if accept.dtype != torch.int32 or resample.dtype != torch.int32:
+        raise TypeError("accept and resample must be int32")
+    if accept.numel() != resample.numel() or L < 1 or accept.numel() % L:
+        raise ValueError("accept and resample must hold B*L rows")
+    if not (accept.is_contiguous() and resample.is_contiguous()):
+        raise ValueError("accept and resample must be contiguous")
+    B = accept.numel() // L
+    kept = torch.empty(B, dtype=torch.int32, device=accept.device)
+    nxt = torch.empty(B, dtype=torch.int32, device=accept.device)
+    rc = lib.lantern_accept_chains(accept.data_ptr(), resample.data_ptr(), B, int(L), kept.data_ptr(),
+                                   nxt.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_accept_chains")
+    return kept, nxt

@@ -96,6 +96,16 @@ int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype,
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
+int lantern_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L, int32_t* out_len,
+                          int32_t* out_next, void* hip_stream) {
+    if (B < 0 || L < 1) return LANTERN_E_SHAPE;
+    if (B == 0) return LANTERN_OK;
+    if (!accept || !resample || !out_len || !out_next) return LANTERN_E_NULL;
+    const hipError_t e = lantern::launch_accept_chains(accept, resample, B, L, out_len, out_next,
+                                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k) {
     if (!dtype_ok((int)cb_dtype) || V < 1 || d < 1 || k < 1 || k > V) return 0;
     return lantern::knn_workspace_bytes(V, d, k);

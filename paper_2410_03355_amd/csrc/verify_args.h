@@ -51,3 +51,10 @@ struct GreedyArgs {
 hipError_t launch_verify_greedy(const GreedyArgs& a, int logits_dtype, hipStream_t stream);
 
 }  // namespace lantern
+
+namespace lantern {
+
+hipError_t launch_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L,
+                                int32_t* out_len, int32_t* out_next, hipStream_t stream);
+
+}  // namespace lantern
