@@ -64,17 +64,45 @@ __device__ __forceinline__ float ord_inv(uint32_t k) {
 }
 
 // ---- exact fp64 key of the pair (i, j): the definition, operation by operation ----
+// Four consecutive coordinates of a code as floats (one 16-byte or 8-byte load); the caller
+// guarantees t + 3 < d and 16-byte aligned rows.
+__device__ __forceinline__ void cb_load4(const float* p, int t, float (&o)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p + t);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+}
+__device__ __forceinline__ void cb_load4(const uint16_t* p, int t, float (&o)[4]) {
+    const uint2 v = *reinterpret_cast<const uint2*>(p + t);
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+}
+
+// vec4: rows are 16-byte aligned and d is a multiple of 4, so coordinates are fetched four at
+// a time; the arithmetic is the same sequence of separately rounded operations either way.
 template <typename CT>
-__device__ double exact_key(const CT* cb, int d, int i, int j, int metric) {
+__device__ double exact_key(const CT* cb, int d, int i, int j, int metric, bool vec4) {
 #pragma clang fp contract(off)
     const CT* ci = cb + (int64_t)i * d;
     const CT* cj = cb + (int64_t)j * d;
     if (metric == 0) {
         double acc = 0.0;
-        for (int t = 0; t < d; ++t) {
-            const double diff = (double)cb_f32<CT>(ci, t) - (double)cb_f32<CT>(cj, t);
-            const double sq = diff * diff;
-            acc = acc + sq;
+        if (vec4) {
+            for (int t = 0; t < d; t += 4) {
+                float x[4], y[4];
+                cb_load4(ci, t, x);
+                cb_load4(cj, t, y);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const double diff = (double)x[e] - (double)y[e];
+                    const double sq = diff * diff;
+                    acc = acc + sq;
+                }
+            }
+        } else {
+            for (int t = 0; t < d; ++t) {
+                const double diff = (double)cb_f32<CT>(ci, t) - (double)cb_f32<CT>(cj, t);
+                const double sq = diff * diff;
+                acc = acc + sq;
+            }
         }
         return acc;
     }
@@ -95,7 +123,6 @@ __device__ double exact_key(const CT* cb, int d, int i, int j, int metric) {
     return -(dot / den);
 }
 
-// ---- stage 1 (generic shapes): approximate keys by direct evaluation in fp32 ----
 template <typename CT>
 __global__ __launch_bounds__(NT) void knn_dist_direct(const CT* cb, int V, int d, int r0, int metric,
                                                       float* dist) {
@@ -345,12 +372,14 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     const float* drow = dist + (int64_t)row * V;
     int32_t* orow = out + (int64_t)i * k;
     const int need = k - 1;
+    // rows of four-coordinate groups, each group one aligned load (16 bytes fp32, 8 bytes bf16)
+    const bool vec4 = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(cb) & 15) == 0);
     if (tid == 0) {
         orow[0] = i;
         flags[row] = 0;
     }
     if (need == 0) return;
-    const int pad = 16 + need / 64;
+    const int pad = 8 + need / 128;
     const int want = min(V - 1, need + pad);
     if (want > CAP) {
         if (tid == 0) flags[row] = 1;
@@ -393,6 +422,10 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     uint32_t lo = kmin;
     int shift = 0;
     while (((uint64_t)(kmax - kmin) >> shift) >= (uint64_t)HBINS) ++shift;
+    // the sort works on a power of two: refine until the candidates fit the smallest one that holds `want`
+    int fit = 1;
+    while (fit < want) fit <<= 1;
+    if (fit > CAP) fit = CAP;
     int below = 0;               // keys strictly below lo: all of them are candidates
     uint32_t thr_key = kmax;     // every key <= thr_key is a candidate
     for (int level = 0; level < 4; ++level) {
@@ -433,7 +466,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         const int in_bin = (int)hist[bin];
         const uint32_t bin_lo = lo + ((uint32_t)bin << shift);
         const uint32_t bin_hi = (uint32_t)min((uint64_t)bin_lo + (((uint64_t)1 << shift) - 1), (uint64_t)0xFFFFFFFEu);
-        if (below + cnt_below_bin + in_bin <= CAP || shift == 0) {
+        if (below + cnt_below_bin + in_bin <= fit || shift == 0) {
             thr_key = bin_hi;   // take the whole bin
             break;
         }
@@ -467,7 +500,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     while (P < count) P <<= 1;
     for (int c = tid; c < P; c += NT) {
         if (c < count) {
-            sh.key[c] = exact_key<CT>(cb, d, i, sh.idx[c], metric);
+            sh.key[c] = exact_key<CT>(cb, d, i, sh.idx[c], metric, vec4);
         } else {
             sh.key[c] = INFINITY;
             sh.idx[c] = INT_MAX;
@@ -525,7 +558,7 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
         const int i = r0 + row;
         __syncthreads();
         for (int j = tid; j < V; j += NT)
-            buf[j] = (j == i) ? INFINITY : exact_key<CT>(cb, d, i, j, metric);
+            buf[j] = (j == i) ? INFINITY : exact_key<CT>(cb, d, i, j, metric, false);
         __threadfence_block();
         __syncthreads();
         int32_t* orow = out + (int64_t)i * k;
@@ -593,7 +626,7 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
         }
         const float* nsel = mfma && a.metric == 0 ? norms : nullptr;
         // candidate capacity: 2048 slots (24 KB of LDS) when k allows, else 4096
-        const bool small_cap = (a.k - 1) + 16 + (a.k - 1) / 64 + 512 <= 2048;
+        const bool small_cap = (a.k - 1) + 8 + (a.k - 1) / 128 <= 2048;
 #define LANTERN_LAUNCH_SELECT(NKV, CAPV)                                                                    \
         hipLaunchKernelGGL((knn_select<CT, NKV, CAPV>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k,  \
                            a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
