@@ -57,6 +57,14 @@ def _load():
                                       i32p, i32p, ctypes.c_int, ctypes.c_double, f32p, i32p, i32p,
                                       f64p, ctypes.c_int]
         lib.oracle_verify.restype = ctypes.c_int
+        lib.oracle_verify_probs_div.argtypes = [f64p, f64p, ctypes.c_int, ctypes.c_int, i32p,
+                                                ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
+                                                ctypes.c_double, i32p, i32p, f64p, f64p, f64p]
+        lib.oracle_verify_probs_div.restype = ctypes.c_int
+        lib.oracle_verify_div.argtypes = [f32p, f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                          i32p, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_double, f32p, i32p,
+                                          i32p, f64p, ctypes.c_int]
+        lib.oracle_verify_div.restype = ctypes.c_int
         lib.oracle_verify_greedy.argtypes = [f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int64, i32p, i32p,
                                              ctypes.c_int, ctypes.c_double, i32p, i32p, f64p, ctypes.c_int]
         lib.oracle_verify_greedy.restype = ctypes.c_int
@@ -112,8 +120,11 @@ def softmax(logits) -> np.ndarray:
     return out
 
 
+DIVERGENCES = {"tvd": 0, "jsd": 1}
+
+
 def verify_probs(t, g, xt: int, nbrs, delta: float, u_acc: float, u_res: float,
-                 want_dists: bool = False) -> dict:
+                 want_dists: bool = False, divergence: str = "tvd") -> dict:
     """One verification on explicit probability vectors."""
     lib = _load()
     t = np.ascontiguousarray(t, dtype=np.float64)
@@ -125,8 +136,9 @@ def verify_probs(t, g, xt: int, nbrs, delta: float, u_acc: float, u_res: float,
     diag = np.empty(len(DIAG_NAMES), dtype=np.float64)
     rho = np.empty(V, dtype=np.float64) if want_dists else None
     ta = np.empty(V, dtype=np.float64) if want_dists else None
-    rc = lib.oracle_verify_probs(_p(t, ctypes.c_double), _p(g, ctypes.c_double), V, int(xt),
-                                 _p(nb, ctypes.c_int32), nb.shape[0], float(delta), float(u_acc),
+    rc = lib.oracle_verify_probs_div(_p(t, ctypes.c_double), _p(g, ctypes.c_double), V, int(xt),
+                                 _p(nb, ctypes.c_int32), nb.shape[0], DIVERGENCES[divergence], float(delta),
+                                 float(u_acc),
                                  float(u_res), _p(acc, ctypes.c_int32), _p(res, ctypes.c_int32),
                                  _p(diag, ctypes.c_double),
                                  _p(rho, ctypes.c_double) if want_dists else None,
@@ -143,7 +155,7 @@ def verify_probs(t, g, xt: int, nbrs, delta: float, u_acc: float, u_res: float,
 
 
 def verify(target_logits, draft_logits, draft_tokens, knn, k: int, delta: float, uniforms,
-           threads: int = 1, want_diag: bool = True):
+           threads: int = 1, want_diag: bool = True, divergence: str = "tvd"):
     """N verifications from logits.  Returns (accept int32[N], resample int32[N], diag dict|None)."""
     lib = _load()
     tl = _as_f32(target_logits)
@@ -159,8 +171,9 @@ def verify(target_logits, draft_logits, draft_tokens, knn, k: int, delta: float,
     acc = np.empty(N, dtype=np.int32)
     res = np.empty(N, dtype=np.int32)
     diag = np.empty((N, len(DIAG_NAMES)), dtype=np.float64) if want_diag else None
-    rc = lib.oracle_verify(_p(tl, ctypes.c_float), _p(dl, ctypes.c_float), N, V, V,
-                           _p(tok, ctypes.c_int32), _p(tab, ctypes.c_int32), int(k), float(delta),
+    rc = lib.oracle_verify_div(_p(tl, ctypes.c_float), _p(dl, ctypes.c_float), N, V, V,
+                           _p(tok, ctypes.c_int32), _p(tab, ctypes.c_int32), int(k), DIVERGENCES[divergence],
+                           float(delta),
                            _p(un, ctypes.c_float), _p(acc, ctypes.c_int32), _p(res, ctypes.c_int32),
                            _p(diag, ctypes.c_double) if want_diag else None, int(threads))
     if rc != 0:

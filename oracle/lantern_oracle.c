@@ -203,8 +203,28 @@ int oracle_diag_count(void) { return DIAG_COUNT; }
  *     A residual with no mass at all falls back to sampling t_A.
  * optional outputs (may be NULL): rho_out[V] normalised residual, ta_out[V].
  */
+/* Jensen-Shannon divergence (natural logarithm) between the distorted target induced by a set A
+ * and the target itself, from the definition 1/2 KL(t_A || m) + 1/2 KL(t || m), m = (t_A + t)/2,
+ * restricted to the entries where the two differ: at xt the pair is (mass, t0); at a member x of
+ * A other than xt it is (0, t(x)), whose term is 1/2 t(x) ln(t(x) / (t(x)/2)); everywhere else
+ * both are equal and the terms vanish.  moved = sum of t over A without xt; 0 ln 0 = 0. */
+static double jsd_of_prefix(double t0, double moved) {
+    double mass = t0 + moved;
+    double mid = 0.5 * (mass + t0);
+    double kl_a = mass > 0.0 ? mass * log(mass / mid) : 0.0;
+    double kl_t = t0 > 0.0 ? t0 * log(t0 / mid) : 0.0;
+    double members = moved * log(2.0);
+    return 0.5 * kl_a + 0.5 * (kl_t + members);
+}
+
+/* divergence 0: total variation distance (Section 4.3); 1: Jensen-Shannon divergence
+ * (ablation of Section 5.3.2).  Returns the divergence of the prefix that moves `moved`. */
+static double prefix_divergence(int divergence, double t0, double moved) {
+    return divergence == 0 ? moved : jsd_of_prefix(t0, moved);
+}
+
 static void verify_probs(const double* t, const double* g, int V, int xt,
-                         const int32_t* nbrs, int k, double delta,
+                         const int32_t* nbrs, int k, int divergence, double delta,
                          double u_acc, double u_res,
                          int32_t* out_accept, int32_t* out_resample,
                          double* diag, double* scratch,
@@ -219,10 +239,11 @@ static void verify_probs(const double* t, const double* g, int V, int xt,
             continue;
         }
         double inc = t[x];
-        double cand = d_tv + inc;
-        double mg = fabs(cand - delta);
+        double cand = d_tv + inc;                       /* mass moved onto xt if x is taken */
+        double div = prefix_divergence(divergence, t[xt], cand);
+        double mg = fabs(div - delta);
         if (mg < margin_cut) margin_cut = mg;
-        if (cand < delta) {
+        if (div < delta) {
             d_tv = cand;
             a = j + 1;
         } else {
@@ -325,7 +346,7 @@ int oracle_verify_probs(const double* t, const double* g, int V, int xt,
     if (!row_args_ok(V, xt, nbrs, k)) return -1;
     double* scratch = (double*)malloc(sizeof(double) * (size_t)V);
     if (!scratch) return -1;
-    verify_probs(t, g, V, xt, nbrs, k, delta, u_acc, u_res, out_accept, out_resample,
+    verify_probs(t, g, V, xt, nbrs, k, 0, delta, u_acc, u_res, out_accept, out_resample,
                  diag, scratch, rho_out, ta_out);
     free(scratch);
     return 0;
@@ -340,10 +361,27 @@ int oracle_verify_probs(const double* t, const double* g, int V, int xt,
  * [0,V), or whose logits hold NaN, +inf or nothing finite, gets -1 in both.
  * diag is NULL or [N, oracle_diag_count()].  Returns 0, or -1 on bad arguments.
  */
+int oracle_verify_div(const float* target_logits, const float* draft_logits, int N, int V,
+                      int64_t row_stride, const int32_t* draft_tokens, const int32_t* knn, int k,
+                      int divergence, double delta, const float* uniforms,
+                      int32_t* out_accept, int32_t* out_resample, double* diag, int threads);
+
 int oracle_verify(const float* target_logits, const float* draft_logits, int N, int V,
                   int64_t row_stride, const int32_t* draft_tokens, const int32_t* knn, int k,
                   double delta, const float* uniforms,
                   int32_t* out_accept, int32_t* out_resample, double* diag, int threads) {
+    return oracle_verify_div(target_logits, draft_logits, N, V, row_stride, draft_tokens, knn, k, 0, delta,
+                             uniforms, out_accept, out_resample, diag, threads);
+}
+
+/* As oracle_verify with a choice of divergence for the bound on A: 0 total variation
+ * distance, 1 Jensen-Shannon divergence (natural logarithm).  With JSD the diagnostic
+ * "tvd_walk" still reports the mass moved onto xt. */
+int oracle_verify_div(const float* target_logits, const float* draft_logits, int N, int V,
+                      int64_t row_stride, const int32_t* draft_tokens, const int32_t* knn, int k,
+                      int divergence, double delta, const float* uniforms,
+                      int32_t* out_accept, int32_t* out_resample, double* diag, int threads) {
+    if (divergence != 0 && divergence != 1) return -1;
     if (N < 0 || V < 1 || k < 1 || k > V || row_stride < V || !(delta >= 0.0)) return -1;
     if (N == 0) return 0;
     if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms || !out_accept ||
@@ -380,7 +418,7 @@ int oracle_verify(const float* target_logits, const float* draft_logits, int N, 
                     out_resample[i] = -1;
                     continue;
                 }
-                verify_probs(t, g, V, xt, knn + (size_t)xt * k, k, delta,
+                verify_probs(t, g, V, xt, knn + (size_t)xt * k, k, divergence, delta,
                              (double)uniforms[2 * (size_t)i], (double)uniforms[2 * (size_t)i + 1],
                              &out_accept[i], &out_resample[i], dg, scratch, NULL, NULL);
             }
@@ -468,6 +506,24 @@ int oracle_verify_greedy(const float* target_logits, int N, int V, int64_t row_s
         free(buf);
     }
     return failed ? -1 : 0;
+}
+
+/* oracle_verify_probs with a choice of divergence (see oracle_verify_div). */
+int oracle_verify_probs_div(const double* t, const double* g, int V, int xt,
+                            const int32_t* nbrs, int k, int divergence, double delta,
+                            double u_acc, double u_res,
+                            int32_t* out_accept, int32_t* out_resample,
+                            double* diag, double* rho_out, double* ta_out) {
+    if (!t || !g || !nbrs || !out_accept || !out_resample) return -1;
+    if (V < 1 || k < 1 || k > V || !(delta >= 0.0)) return -1;
+    if (divergence != 0 && divergence != 1) return -1;
+    if (!row_args_ok(V, xt, nbrs, k)) return -1;
+    double* scratch = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!scratch) return -1;
+    verify_probs(t, g, V, xt, nbrs, k, divergence, delta, u_acc, u_res, out_accept, out_resample,
+                 diag, scratch, rho_out, ta_out);
+    free(scratch);
+    return 0;
 }
 
 int oracle_max_threads(void) {
