@@ -55,6 +55,11 @@ typedef enum {
     LANTERN_METRIC_COSINE = 1 /* cosine similarity (ablation, Section 5.3.1)           */
 } lantern_metric;
 
+typedef enum {
+    LANTERN_DIV_TVD = 0,      /* total variation distance, the paper's choice (Section 4.3) */
+    LANTERN_DIV_JSD = 1       /* Jensen-Shannon divergence, natural logarithm (ablation, Section 5.3.2) */
+} lantern_divergence;
+
 /* Largest vocabulary lantern_verify accepts (a bitmask of one row and its partial sums must fit in LDS). */
 #define LANTERN_MAX_VOCAB (1 << 19)
 
@@ -151,6 +156,24 @@ int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                       const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                       float* out_accept_prob, float* out_mass, float* out_g_tok,
                       int32_t* out_a_size, int32_t* out_path, void* hip_stream);
+
+/*
+ * lantern_verify_ex with a choice of the divergence that bounds the neighbourhood
+ * (Section 5.3.2 compares the two): the walk takes a neighbour while the
+ * divergence between the distorted target and the target, after adding it,
+ * stays strictly below delta.  LANTERN_DIV_TVD is lantern_verify_ex itself.
+ * For LANTERN_DIV_JSD the divergence of a prefix is
+ *   1/2 [ m ln(2m/(m+t0)) + t0 ln(2 t0/(m+t0)) + (m - t0) ln 2 ],
+ * t0 = t(xt), m = mass of the prefix (the entries where the two distributions
+ * differ; it never exceeds ln 2).  All other arguments, outputs and errors as
+ * in lantern_verify_ex; an unknown divergence is E_SHAPE.
+ */
+int lantern_verify_divergence(const void* target_logits, const void* draft_logits,
+                              lantern_dtype logits_dtype, int N, int V, int64_t row_stride_elems,
+                              const int32_t* draft_tokens, const int32_t* knn, int k, int divergence,
+                              float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                              float* out_accept_prob, float* out_mass, float* out_g_tok,
+                              int32_t* out_a_size, int32_t* out_path, void* hip_stream);
 
 /*
  * Greedy-decoding variant (Section 4.3, last sentence): accept the draft token

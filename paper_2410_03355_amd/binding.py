@@ -22,7 +22,8 @@ E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -
 
 EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
-    "lantern_verify", "lantern_verify_ex", "lantern_verify_greedy", "lantern_accept_chains",
+    "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
+    "lantern_accept_chains",
     "lantern_status_string",
     "lantern_version",
 )
@@ -58,6 +59,9 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_ex.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp,
                                       vp, vp, vp, vp, vp, vp]
     lib.lantern_verify_ex.restype = i32
+    lib.lantern_verify_divergence.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, f32, vp, vp, vp,
+                                              vp, vp, vp, vp, vp, vp]
+    lib.lantern_verify_divergence.restype = i32
     lib.lantern_verify_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, f32, vp, vp, vp, vp]
     lib.lantern_verify_greedy.restype = i32
     lib.lantern_accept_chains.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -158,8 +162,13 @@ def verify(target_logits, draft_logits, draft_tokens, knn, delta: float, uniform
     return acc, res
 
 
-def verify_ex(target_logits, draft_logits, draft_tokens, knn, delta: float, uniforms, stream=None):
-    """lantern_verify_ex; returns a dict of device tensors with all diagnostics."""
+DIV_TVD, DIV_JSD = 0, 1
+
+
+def verify_ex(target_logits, draft_logits, draft_tokens, knn, delta: float, uniforms, stream=None,
+              divergence: str = "tvd"):
+    """lantern_verify_ex (divergence "tvd") or lantern_verify_divergence ("jsd"); returns a dict of
+    device tensors with all diagnostics."""
     lib = load()
     N, V, k = _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms)
     dev = target_logits.device
@@ -172,14 +181,15 @@ def verify_ex(target_logits, draft_logits, draft_tokens, knn, delta: float, unif
         "a_size": torch.empty(N, dtype=torch.int32, device=dev),
         "path": torch.empty(N, dtype=torch.int32, device=dev),
     }
-    rc = lib.lantern_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(),
-                               _dtype_code(target_logits), N, V,
-                               target_logits.stride(0) if N > 1 else V, draft_tokens.data_ptr(),
-                               knn.data_ptr(), k, float(delta), uniforms.data_ptr(),
-                               out["accept"].data_ptr(), out["resample"].data_ptr(),
-                               out["accept_prob"].data_ptr(), out["mass"].data_ptr(),
-                               out["g_tok"].data_ptr(), out["a_size"].data_ptr(),
-                               out["path"].data_ptr(), _stream_ptr(stream))
+    common_in = (target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits), N, V,
+                 target_logits.stride(0) if N > 1 else V, draft_tokens.data_ptr(), knn.data_ptr(), k)
+    common_out = (uniforms.data_ptr(), out["accept"].data_ptr(), out["resample"].data_ptr(),
+                  out["accept_prob"].data_ptr(), out["mass"].data_ptr(), out["g_tok"].data_ptr(),
+                  out["a_size"].data_ptr(), out["path"].data_ptr(), _stream_ptr(stream))
+    if divergence == "tvd":
+        rc = lib.lantern_verify_ex(*common_in, float(delta), *common_out)
+    else:
+        rc = lib.lantern_verify_divergence(*common_in, {"jsd": DIV_JSD}[divergence], float(delta), *common_out)
     if rc != OK:
         raise LanternError(rc, "lantern_verify_ex")
     return out

@@ -13,12 +13,13 @@ bool dtype_ok(int dt) { return dt == LANTERN_F32 || dt == LANTERN_BF16; }
 
 int verify_impl(const void* target_logits, const void* draft_logits, int logits_dtype, int N, int V,
                 int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
-                float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                int divergence, float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                 float* out_accept_prob, float* out_mass, float* out_g_tok, int32_t* out_a_size,
                 int32_t* out_path, void* hip_stream) {
     if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
     if (N < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
         return LANTERN_E_SHAPE;
+    if (divergence != LANTERN_DIV_TVD && divergence != LANTERN_DIV_JSD) return LANTERN_E_SHAPE;
     if (!(delta >= 0.0f)) return LANTERN_E_DELTA;  // also rejects NaN
     if (N == 0) return LANTERN_OK;
     if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms || !out_accept ||
@@ -33,6 +34,7 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.tokens = draft_tokens;
     a.knn = knn;
     a.k = k;
+    a.divergence = divergence;
     a.delta = delta;
     a.uniforms = uniforms;
     a.out_accept = out_accept;
@@ -55,7 +57,7 @@ int lantern_verify(const void* target_logits, const void* draft_logits, lantern_
                    const int32_t* knn, int k, float delta, const float* uniforms,
                    int32_t* out_accept, int32_t* out_resample, void* hip_stream) {
     return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
-                       draft_tokens, knn, k, delta, uniforms, out_accept, out_resample, nullptr,
+                       draft_tokens, knn, k, LANTERN_DIV_TVD, delta, uniforms, out_accept, out_resample, nullptr,
                        nullptr, nullptr, nullptr, nullptr, hip_stream);
 }
 
@@ -66,7 +68,18 @@ int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                       float* out_accept_prob, float* out_mass, float* out_g_tok,
                       int32_t* out_a_size, int32_t* out_path, void* hip_stream) {
     return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
-                       draft_tokens, knn, k, delta, uniforms, out_accept, out_resample,
+                       draft_tokens, knn, k, LANTERN_DIV_TVD, delta, uniforms, out_accept, out_resample,
+                       out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
+}
+
+int lantern_verify_divergence(const void* target_logits, const void* draft_logits,
+                              lantern_dtype logits_dtype, int N, int V, int64_t row_stride_elems,
+                              const int32_t* draft_tokens, const int32_t* knn, int k, int divergence,
+                              float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
+                              float* out_accept_prob, float* out_mass, float* out_g_tok,
+                              int32_t* out_a_size, int32_t* out_path, void* hip_stream) {
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+                       draft_tokens, knn, k, divergence, delta, uniforms, out_accept, out_resample,
                        out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
 }
 

@@ -65,11 +65,38 @@ struct CutResult {
     int bad;         // a table entry outside [0, V)
 };
 
-// Wavefront 0, after the barrier.  Zt: sum of the unnormalised target terms.
+// Decides one slot of the walk from its inclusive sum I (unnormalised, like e_tx = the term of
+// the token itself and Zt = the row sum).  Total variation: I against delta * Zt.  Jensen-Shannon:
+// the divergence of the prefix, evaluated in fp32 on unnormalised terms (it is homogeneous of
+// degree one), against delta * Zt; its error is bounded by the derivative (at most ln 2 in either
+// argument) times the error of the arguments plus the rounding of the evaluation itself.
+struct SlotTest {
+    int divergence;
+    float e_tx;
+    float lo, hi;     // delta * Zt shrunk / grown by the margin
+    __device__ __forceinline__ void classify(float I, bool* passes, bool* fails) const {
+        if (divergence == 0) {
+            *passes = I < lo;
+            *fails = I > hi;
+        } else {
+            const float mass = e_tx + I;
+            const float mid = 0.5f * (mass + e_tx);
+            const float kl_a = mass > 0.f ? mass * __logf(mass / mid) : 0.f;
+            const float kl_t = e_tx > 0.f ? e_tx * __logf(e_tx / mid) : 0.f;
+            const float J = 0.5f * kl_a + 0.5f * (kl_t + I * 0.69314718f);
+            const float err = 0.7f * (8.0e-6f * I + 3.0e-6f * e_tx) + 1.0e-6f * (e_tx + I);
+            *passes = J + err < lo;
+            *fails = J - err > hi;
+        }
+    }
+};
+
+// Wavefront 0, after the barrier.  Zt: sum of the unnormalised target terms; e_tx: the
+// unnormalised term of the token itself (used by the Jensen-Shannon bound only).
 template <typename LT>
-__device__ __forceinline__ CutResult scan_cut(float Zt, float delta, int xt, int xs, int k, int V,
-                                              const int32_t* knn, const unsigned char* s_row, float ct,
-                                              const ScanLds& lds) {
+__device__ __forceinline__ CutResult scan_cut(float Zt, int divergence, float delta, float e_tx, int xt, int xs,
+                                              int k, int V, const int32_t* knn, const unsigned char* s_row,
+                                              float ct, const ScanLds& lds) {
     using L = Lane<LT>;
     const int lane = threadIdx.x & (WAVE - 1);
     int bad = 0;
@@ -81,9 +108,12 @@ __device__ __forceinline__ CutResult scan_cut(float Zt, float delta, int xt, int
         woff[w] = run_off;
         run_off += lds.wtot[w];
     }
-    const float R = delta * Zt;                 // cut: inclusive sum < delta * Zt
-    const float cut_lo = R * (1.f - TAU_CUT) - ABS_SLACK;
-    const float cut_hi = R * (1.f + TAU_CUT) + ABS_SLACK;
+    const float R = delta * Zt;                 // cut: divergence of the prefix, times Zt, < delta * Zt
+    SlotTest test;
+    test.divergence = divergence;
+    test.e_tx = e_tx;
+    test.lo = R * (1.f - TAU_CUT) - ABS_SLACK;
+    test.hi = R * (1.f + TAU_CUT) + ABS_SLACK;
     // lane l takes slots 16 l .. 16 l + 15: threads 4 l .. 4 l + 3, all in wavefront l / 16
     const float off = woff[lane >> 4];
     int my_np = INT_MAX, my_df = INT_MAX;  // first slot not definitely passing / definitely failing
@@ -97,8 +127,10 @@ __device__ __forceinline__ CutResult scan_cut(float Zt, float delta, int xt, int
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (!((skip >> q) & 1u)) {
-                if (my_np == INT_MAX && !(I[q] < cut_lo)) { my_np = lane * SPL + t * 4 + q; my_s = before; }
-                if (my_df == INT_MAX && I[q] > cut_hi) my_df = lane * SPL + t * 4 + q;
+                bool passes, fails;
+                test.classify(I[q], &passes, &fails);
+                if (my_np == INT_MAX && !passes) { my_np = lane * SPL + t * 4 + q; my_s = before; }
+                if (my_df == INT_MAX && fails) my_df = lane * SPL + t * 4 + q;
             }
             before = I[q];
         }
@@ -139,8 +171,10 @@ __device__ __forceinline__ CutResult scan_cut(float Zt, float delta, int xt, int
                 const float bef = I;
                 I += ev[q];
                 if (!((skip >> q) & 1u)) {
-                    if (my_np == INT_MAX && !(I < cut_lo)) { my_np = j0 + q; my_s = bef; }
-                    if (my_df == INT_MAX && I > cut_hi) my_df = j0 + q;
+                    bool passes, fails;
+                    test.classify(I, &passes, &fails);
+                    if (my_np == INT_MAX && !passes) { my_np = j0 + q; my_s = bef; }
+                    if (my_df == INT_MAX && fails) my_df = j0 + q;
                 }
             }
             const int w_np = wave_min(my_np);

@@ -125,8 +125,9 @@ __device__ void greedy_exact_row(const GreedyArgs& a, int row, unsigned char* ex
     // walk, mass
     int a_size;
     double S;
-    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, delta, sh, tid, &a_size, &S);
-    const double mass = exp_nonpos((double)L::glob(trow, xt) - mt) / zt + S;
+    const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
+    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, 0, t_tok, delta, sh, tid, &a_size, &S);
+    const double mass = t_tok + S;
 
     // bitmask of A and of xt, then the lowest-index arg-max of the raw logits outside it
     for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
         float Zt = 0.f, Emax = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) { Zt += sh.wsum[w]; Emax = fmaxf(Emax, sh.wemax[w]); }
-        const CutResult cut = scan_cut<LT>(Zt, a.delta, xt, xs, k, V, a.knn, s_row, ct, scan);
+        const CutResult cut = scan_cut<LT>(Zt, 0, a.delta, 0.f, xt, xs, k, V, a.knn, s_row, ct, scan);
         const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX);
         const bool cut_ok = cut.definite && !cut.bad && tok_ok && sums_ok;
         const float mass_z = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct)) + cut.S;

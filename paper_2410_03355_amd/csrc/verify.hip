@@ -191,12 +191,12 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
                 Zt += sh.wsum_t[w];
                 Zg += sh.wsum_g[w];
             }
-            const CutResult cut = scan_cut<LT>(Zt, a.delta, xt, xs, k, V, a.knn, s_row, ct, scan);
+            const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
+            const CutResult cut = scan_cut<LT>(Zt, a.divergence, a.delta, e_tx, xt, xs, k, V, a.knn, s_row, ct, scan);
             const int bad = cut.bad | (tok_ok ? 0 : 1);
             const bool cut_definite = cut.definite;
             const int a_size = cut.a_size;
             const float S = cut.S;
-            const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
             const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
             const float MA = e_tx + S;                // mass * Zt
             const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
@@ -360,11 +360,11 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     zg = block_sum(zg, sh.red2, tid);
 
     // ---- nearest-first walk over the table row ----
+    const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
     int a_size;
     double S;
-    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, delta, sh, tid, &a_size, &S);
+    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, a.divergence, t_tok, delta, sh, tid, &a_size, &S);
 
-    const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
     const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;
     const double mass = t_tok + S;
     const bool accepted = (u_acc * g_tok < mass);

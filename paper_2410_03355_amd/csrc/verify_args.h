@@ -15,6 +15,7 @@ struct VerifyArgs {
     const int32_t* tokens;    // [N] draft tokens
     const int32_t* knn;       // [V, k] neighbour table
     int k;
+    int divergence;           // bound on A: 0 total variation distance, 1 Jensen-Shannon divergence
     float delta;
     const float* uniforms;    // [N, 2]
     int32_t* out_accept;      // [N]

@@ -213,15 +213,30 @@ struct VecLoad<uint16_t, VEC> {
     }
 };
 
+// Divergence between the distorted target of a prefix and the target, as a function of t0 = t(xt)
+// and of the mass moved onto xt.  0: total variation distance, which is the moved mass itself
+// (Section 4.3).  1: Jensen-Shannon divergence, natural logarithm (Section 5.3.2), from the
+// entries where the two distributions differ: (mass, t0) at xt and (0, t(x)) at the other members.
+__device__ __forceinline__ double prefix_divergence64(int divergence, double t0, double moved) {
+    if (divergence == 0) return moved;
+    const double mass = t0 + moved;
+    const double mid = 0.5 * (mass + t0);
+    const double kl_a = mass > 0.0 ? mass * log(mass / mid) : 0.0;
+    const double kl_t = t0 > 0.0 ? t0 * log(t0 / mid) : 0.0;
+    const double members = moved * log(2.0);
+    return 0.5 * kl_a + 0.5 * (kl_t + members);
+}
+
 // Nearest-first walk of the neighbourhood in fp64 (Algorithm 2, inference part), by the
 // whole workgroup: inclusive sums of t over the table slots, 256 slots at a time; the walk
-// ends at the first slot, other than the token itself, whose inclusive sum is not below
-// delta.  *a_size: slots taken; *S: sum of t over the taken slots other than the token.
+// ends at the first slot, other than the token itself, at which the divergence of the prefix
+// (a function of t_tok = t(xt) and of the inclusive sum) is not below delta.
+// *a_size: slots taken; *S: sum of t over the taken slots other than the token.
 // trow: the target row in global memory; lds_row: the same raw row in LDS, or null.
 template <typename LT>
 __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* lds_row, const int32_t* nrow,
-                                           int k, int xt, double mt, double zt, double delta, ExactShared& sh,
-                                           int tid, int* a_size, double* S) {
+                                           int k, int xt, double mt, double zt, int divergence, double t_tok,
+                                           double delta, ExactShared& sh, int tid, int* a_size, double* S) {
     using L = Lane<LT>;
     double carry = 0.0;
     *a_size = k;
@@ -236,7 +251,7 @@ __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* 
         const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
         double ctot;
         const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
-        const int fail_j = (valid && !self && !(incl < delta)) ? j : INT_MAX;
+        const int fail_j = (valid && !self && !(prefix_divergence64(divergence, t_tok, incl) < delta)) ? j : INT_MAX;
         const int first = block_min_i(fail_j, sh.ired, tid);
         if (first != INT_MAX) {
             cut_found = true;

@@ -1,0 +1,67 @@
+"""GPU parity of the Jensen-Shannon-bounded neighbourhood (lantern_verify_divergence) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from synth import philox, workloads
+from parity_utils import compare_verify, random_table
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("delta", [0.0, 0.002, 0.02, 0.1, 0.5, 0.7])
+def test_tiny(oracle_mod, lantern_gpu, delta):
+    cfg = workloads.CONFIGS["tiny"]
+    cb = workloads.make_codebook(cfg)
+    table = oracle_mod.build_knn(cb.numpy(), cfg.k, threads=8)
+    st = workloads.make_step(cfg, step=31)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                                       table, delta, st.uniforms, label=f"tiny jsd {delta}", divergence="jsd")
+    if delta == 0.0:
+        assert np.all(diag["a_size"] == 1)
+    if delta == 0.7:                       # JSD never reaches ln 2
+        assert np.all(diag["a_size"] == cfg.k)
+
+
+@pytest.mark.parametrize("name,variant,delta", [
+    ("llamagen_step", "plain", 0.2),       # the bound the paper uses with JSD
+    ("llamagen_step", "plain", 0.01),
+    ("llamagen_step", "peaked", 0.005),
+    ("llamagen_step", "reject", 0.0),
+    ("wide_latent", "plain", 0.003),
+    ("wide_latent", "peaked", 0.02),
+])
+def test_full_width_rows(oracle_mod, lantern_gpu, name, variant, delta):
+    cfg = workloads.CONFIGS[name]
+    st = workloads.make_step(cfg, step=5, rows=384, variant=variant)
+    table = random_table(cfg.V, cfg.k, seed=21)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                                       table, delta, st.uniforms, threads=16, label=f"{name} {variant} jsd {delta}",
+                                       divergence="jsd")
+    if delta in (0.01, 0.005, 0.003, 0.02):
+        assert (diag["a_size"] < cfg.k).sum() > 0      # the bound cuts some neighbourhoods
+        assert (diag["a_size"] > 1).sum() > 0
+
+
+@pytest.mark.parametrize("V,k,N,dtype", [(7, 7, 5, torch.float32), (1003, 50, 20, torch.bfloat16),
+                                         (4096, 2500, 9, torch.bfloat16), (40000, 100, 5, torch.float32)])
+def test_shapes(oracle_mod, lantern_gpu, V, k, N, dtype):
+    rng = np.random.default_rng(V + k)
+    t = torch.from_numpy((rng.standard_normal((N, V)) * 2.5).astype(np.float32))
+    g = (t + torch.from_numpy(rng.standard_normal((N, V)).astype(np.float32))).to(dtype)
+    t = t.to(dtype)
+    tokens = torch.from_numpy(rng.integers(0, V, N).astype(np.int32))
+    table = random_table(V, k, seed=V)
+    un = torch.from_numpy(philox.uniforms(V, N))
+    for delta in (0.01, 0.15):
+        compare_verify(oracle_mod, lantern_gpu, t, g, tokens, table, delta, un, label=f"V={V} jsd",
+                       divergence="jsd")
+
+
+def test_unknown_divergence_is_rejected(lantern_gpu):
+    import ctypes
+    lib = lantern_gpu.load()
+    p = ctypes.c_void_p(4096)
+    rc = lib.lantern_verify_divergence(p, p, 0, 4, 16, 16, p, p, 4, 7, 0.1, p, p, p, None, None, None, None, None,
+                                       None)
+    assert rc == lantern_gpu.binding.E_SHAPE
