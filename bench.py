@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy"],
                     help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only")
+    ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
+                    help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -102,6 +104,13 @@ def main() -> int:
                                            out_acc[i % nbuf].data_ptr(), out_res[i % nbuf].data_ptr(), None,
                                            stream.cuda_stream)
             assert rc == 0, rc
+        elif args.divergence == "jsd":
+            rc = lib.lantern_verify_divergence(b.target_logits.data_ptr(), b.draft_logits.data_ptr(), dcode,
+                                               cfg.rows, cfg.V, cfg.V, b.draft_tokens.data_ptr(), knn.data_ptr(),
+                                               cfg.k, 1, float(delta), b.uniforms.data_ptr(),
+                                               out_acc[i % nbuf].data_ptr(), out_res[i % nbuf].data_ptr(),
+                                               None, None, None, None, None, stream.cuda_stream)
+            assert rc == 0, rc
         else:
             lantern.verify(b.target_logits, b.draft_logits, b.draft_tokens, knn, delta, b.uniforms,
                            out_accept=out_acc[i % nbuf], out_resample=out_res[i % nbuf], stream=stream)
@@ -155,7 +164,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{cfg.name}/{args.variant}/{args.mode}: V={cfg.V} d={cfg.d} k={cfg.k} delta={delta} "
+            "workload": f"{cfg.name}/{args.variant}/{args.mode}/{args.divergence}: V={cfg.V} d={cfg.d} k={cfg.k} delta={delta} "
                         f"rows_per_step={rows} logits={cfg.logit_dtype}",
             "rows_per_step": rows,
             "distinct_step_buffers": nbuf,
@@ -169,14 +178,14 @@ def main() -> int:
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": args.traffic_bytes if args.traffic_bytes is not None
-            else (None if greedy else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
+            else (None if greedy or args.divergence != "tvd" else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "kernel_ms_avg": kernel_ms_avg,
         },
         "knn_build_ms": knn_build_ms,
     }
 
-    if not args.no_cpu_baseline and not greedy:
+    if not args.no_cpu_baseline and not greedy and args.divergence == "tvd":
         import numpy as np
         import oracle  # CPU baseline leg only
         threads = min(os.cpu_count() or 1, 16, oracle.max_threads())

@@ -78,6 +78,14 @@ struct SlotTest {
         if (divergence == 0) {
             *passes = I < lo;
             *fails = I > hi;
+        } else if (I * 0.69314718f < lo) {
+            // JSD <= ln 2 * TVD: far below the bound, no need to evaluate the divergence
+            *passes = true;
+            *fails = false;
+        } else if (I * 0.34657359f > hi) {
+            // JSD >= 1/2 ln 2 * (moved mass): far above the bound
+            *passes = false;
+            *fails = true;
         } else {
             const float mass = e_tx + I;
             const float mid = 0.5f * (mass + e_tx);
