@@ -1,0 +1,61 @@
+"""The library only enqueues kernels on the caller's stream, so its calls can be captured into a HIP
+graph and replayed; every replay must equal the eager result on the buffers' current contents."""
+import numpy as np
+import pytest
+import torch
+
+from synth import workloads
+from parity_utils import random_table
+
+pytestmark = pytest.mark.gpu
+
+
+def test_capture_and_replay(oracle_mod, lantern_gpu):
+    cfg = workloads.CONFIGS["tiny"]
+    L, B = 4, 64
+    rows = L * B
+    table = random_table(cfg.V, cfg.k, seed=33)
+    tb = torch.from_numpy(table).cuda()
+    steps = [workloads.make_step(cfg, step=s, rows=rows) for s in (40, 41, 42)]
+    # static buffers the captured calls read and write
+    tl = torch.empty_like(steps[0].target_logits, device="cuda")
+    dl = torch.empty_like(steps[0].draft_logits, device="cuda")
+    tok = torch.empty(rows, dtype=torch.int32, device="cuda")
+    un = torch.empty((rows, 2), dtype=torch.float32, device="cuda")
+    acc = torch.empty(rows, dtype=torch.int32, device="cuda")
+    res = torch.empty(rows, dtype=torch.int32, device="cuda")
+
+    def load(st):
+        tl.copy_(st.target_logits); dl.copy_(st.draft_logits); tok.copy_(st.draft_tokens); un.copy_(st.uniforms)
+
+    load(steps[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm up outside the capture
+        lantern_gpu.verify(tl, dl, tok, tb, cfg.delta, un, out_accept=acc, out_resample=res, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s = torch.cuda.current_stream()
+        lantern_gpu.verify(tl, dl, tok, tb, cfg.delta, un, out_accept=acc, out_resample=res, stream=s)
+        kept, nxt = lantern_gpu.accept_chains(acc, res, L, stream=s)
+        gacc, gtok = lantern_gpu.verify_greedy(tl, tok, tb, cfg.delta, stream=s)
+
+    for st in (steps[1], steps[2], steps[0], steps[2]):
+        load(st)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        acc_o, res_o, _ = oracle_mod.verify(st.target_logits, st.draft_logits, st.draft_tokens, table, cfg.k,
+                                            cfg.delta, st.uniforms, threads=8)
+        np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(res.cpu().numpy(), res_o)
+        n_o, next_o = oracle_mod.accept_chains(acc_o, res_o, L)
+        np.testing.assert_array_equal(kept.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+        ga_o, gt_o, _ = oracle_mod.verify_greedy(st.target_logits, st.draft_tokens, table, cfg.k, cfg.delta,
+                                                 threads=8)
+        np.testing.assert_array_equal(gacc.cpu().numpy(), ga_o)
+        np.testing.assert_array_equal(gtok.cpu().numpy(), gt_o)
