@@ -223,3 +223,54 @@ def accept_chains(accept, resample, L: int):
                                 _p(n, ctypes.c_int32), _p(nxt, ctypes.c_int32)) != 0:
         raise ValueError("oracle_accept_chains: bad arguments")
     return n, nxt
+
+
+def accept_trees(accept, resample, parent, M: int):
+    """Walk of B drafted trees of M nodes; returns (len int32[B], path int32[B, M], next int32[B])."""
+    lib = _load()
+    P = ctypes.POINTER(ctypes.c_int32)
+    lib.oracle_accept_trees.argtypes = [P, P, P, ctypes.c_int, ctypes.c_int, P, P, P]
+    lib.oracle_accept_trees.restype = ctypes.c_int
+    acc = _as_i32(accept).reshape(-1)
+    res = _as_i32(resample).reshape(-1)
+    par = _as_i32(parent).reshape(-1)
+    if acc.shape != res.shape or acc.shape != par.shape or acc.shape[0] % M:
+        raise ValueError("shape mismatch")
+    B = acc.shape[0] // M
+    n = np.empty(B, dtype=np.int32)
+    path = np.empty((B, M), dtype=np.int32)
+    nxt = np.empty(B, dtype=np.int32)
+    if lib.oracle_accept_trees(_p(acc, ctypes.c_int32), _p(res, ctypes.c_int32), _p(par, ctypes.c_int32), B, M,
+                               _p(n, ctypes.c_int32), _p(path, ctypes.c_int32), _p(nxt, ctypes.c_int32)) != 0:
+        raise ValueError("oracle_accept_trees: bad arguments")
+    return n, path, nxt
+
+
+def verify_rows(target_logits, draft_logits, row_index, draft_tokens, knn, k: int, delta: float, uniforms,
+                threads: int = 1, divergence: str = "tvd"):
+    """N verifications over R shared logit rows: verification i reads row row_index[i] of both
+    logit matrices (the siblings of a draft tree share the rows computed after their parent's
+    prefix).  An index outside [0, R) makes that verification unusable (-1, -1).
+    Returns (accept int32[N], resample int32[N], diag dict)."""
+    tl = _as_f32(target_logits)
+    dl = _as_f32(draft_logits)
+    idx = np.asarray(row_index, dtype=np.int64).reshape(-1)
+    ok = (idx >= 0) & (idx < tl.shape[0])
+    safe = np.where(ok, idx, 0)
+    acc, res, diag = verify(tl[safe], dl[safe], draft_tokens, knn, k, delta, uniforms, threads=threads,
+                            divergence=divergence)
+    acc[~ok] = -1
+    res[~ok] = -1
+    return acc, res, diag
+
+
+def verify_greedy_rows(target_logits, row_index, draft_tokens, knn, k: int, delta: float, threads: int = 1):
+    """Greedy-decoding variant over shared logit rows, as verify_rows."""
+    tl = _as_f32(target_logits)
+    idx = np.asarray(row_index, dtype=np.int64).reshape(-1)
+    ok = (idx >= 0) & (idx < tl.shape[0])
+    safe = np.where(ok, idx, 0)
+    acc, tok, diag = verify_greedy(tl[safe], draft_tokens, knn, k, delta, threads=threads)
+    acc[~ok] = -1
+    tok[~ok] = -1
+    return acc, tok, diag

@@ -569,3 +569,79 @@ int oracle_accept_chains(const int32_t* accept, const int32_t* resample, int B, 
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Walk of a drafted tree (Algorithm 1 applied along the branches)            */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * B trees of M candidate nodes each (the paper verifies 60 candidates per
+ * step, Appendix on experimental details, and leaves the tree rule to its
+ * drafter); tree b owns rows b*M .. b*M+M-1.  parent[i] is the node, within
+ * the tree, whose token precedes node i, or -1 when node i directly follows
+ * the committed prefix; nodes are listed in drafting order, parent[i] < i.
+ * accept / resample hold, per node, the outcome of verifying that node's token
+ * against the distributions after its parent's prefix.
+ *
+ * The rule stated here (it reduces to the chain of Algorithm 1 when every node
+ * has one child): standing at a node (at first the committed prefix, -1), its
+ * children are tried in index order; the first child whose row says accepted
+ * is taken and the walk continues from it.  A child with an unusable row
+ * (accept < 0) met before any accepted one ends the walk with next = -2.  When
+ * every child was rejected the walk ends with the resampled token of the first
+ * child, the candidate Algorithm 1 tries at that position; when the node has
+ * no child at all every draft on the branch was accepted and next = -1 (the
+ * caller samples the extra token).  A tree with a parent outside [-1, i) is
+ * not walked: len 0, next = -3.
+ *
+ * out_len[b]: number of accepted nodes.  out_path[b*M + j]: the j-th accepted
+ * node for j < len, -1 beyond.  out_next[b] as above.
+ */
+int oracle_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B, int M,
+                        int32_t* out_len, int32_t* out_path, int32_t* out_next) {
+    if (B < 0 || M < 1) return -1;
+    if (B == 0) return 0;
+    if (!accept || !resample || !parent || !out_len || !out_path || !out_next) return -1;
+    for (int b = 0; b < B; ++b) {
+        const int32_t* acc = accept + (size_t)b * M;
+        const int32_t* res = resample + (size_t)b * M;
+        const int32_t* par = parent + (size_t)b * M;
+        int32_t* path = out_path + (size_t)b * M;
+        for (int j = 0; j < M; ++j) path[j] = -1;
+        int well_formed = 1;
+        for (int i = 0; i < M; ++i)
+            if (par[i] < -1 || par[i] >= i) well_formed = 0;
+        if (!well_formed) {
+            out_len[b] = 0;
+            out_next[b] = -3;
+            continue;
+        }
+        int cur = -1;
+        int len = 0;
+        int next = -1;
+        for (;;) {
+            int first_child = -1;
+            int taken = -1;
+            int unusable = 0;
+            for (int i = cur + 1; i < M; ++i) {
+                if (par[i] != cur) continue;
+                if (first_child < 0) first_child = i;
+                if (acc[i] == 1) { taken = i; break; }
+                if (acc[i] < 0) { unusable = 1; break; }
+            }
+            if (taken >= 0) {
+                path[len] = taken;
+                len = len + 1;
+                cur = taken;
+                continue;
+            }
+            if (unusable) next = -2;
+            else if (first_child >= 0) next = res[first_child];
+            else next = -1;
+            break;
+        }
+        out_len[b] = len;
+        out_next[b] = next;
+    }
+    return 0;
+}
