@@ -214,6 +214,58 @@ int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype,
 int lantern_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L, int32_t* out_len,
                           int32_t* out_next, void* hip_stream);
 
+/*
+ * Verification over shared logit rows.  A draft tree holds several candidate
+ * tokens for one position (the paper verifies 60 candidates per step of the
+ * target model, Appendix on experimental details); the siblings are verified
+ * against the same pair of distributions, the ones after their parent's
+ * prefix.  Verification i reads row row_index[i] of both logit matrices; all
+ * else is lantern_verify (divergence as in lantern_verify_divergence) and
+ * lantern_verify_greedy.
+ *
+ *   target_logits, draft_logits  device, [R, V] rows of row_stride_elems
+ *   row_index     device, [N] int32, values in [0, R); a value outside makes
+ *                 that verification unusable (-1 in both outputs)
+ *   draft_tokens, uniforms, outputs  [N], one per verification
+ * Errors: as lantern_verify; E_SHAPE also for R < 1 with N > 0; E_NULL for a
+ * missing row_index.  N = 0 does nothing.
+ */
+int lantern_verify_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                        int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                        const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
+                        const float* uniforms, int32_t* out_accept, int32_t* out_resample, void* hip_stream);
+
+int lantern_verify_greedy_rows(const void* target_logits, lantern_dtype logits_dtype, int R, int V,
+                               int64_t row_stride_elems, const int32_t* row_index, int N,
+                               const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                               int32_t* out_accept, int32_t* out_token, void* hip_stream);
+
+/*
+ * Walk of B drafted trees of M candidate nodes each (Algorithm 1 applied along
+ * the branches).  Tree b owns rows b*M .. b*M+M-1 of accept / resample /
+ * parent, in drafting order.  parent[i] is the node of the same tree whose
+ * token precedes node i, or -1 when node i follows the committed prefix;
+ * parent[i] < i.  The paper leaves the rule for siblings to its drafter; the
+ * rule here: standing at a node (first the prefix), its children are tried in
+ * index order, the first accepted one is taken and the walk goes on from it.
+ * With one child per node this is lantern_accept_chains.
+ *
+ *   accept, resample  [B*M] int32, as written by lantern_verify_rows
+ *   parent    [B*M] int32
+ *   out_len   [B] int32: number of accepted nodes
+ *   out_path  [B*M] int32: the accepted nodes of tree b, in order, then -1
+ *   out_next  [B] int32: the token after them: when every child of the last
+ *             node was rejected, the resampled token of its first child (the
+ *             candidate Algorithm 1 tries at that position); -1 when the last
+ *             node has no child (all drafts of the branch accepted, the caller
+ *             samples the extra token); -2 when an unusable child (accept < 0)
+ *             was met before an accepted one; -3, with len 0, when the tree's
+ *             parent array is malformed
+ * Errors: E_NULL, E_SHAPE (B < 0, M < 1), E_DEVICE.  B = 0 does nothing.
+ */
+int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B, int M,
+                         int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* lantern_status_string(int status);
 

@@ -23,7 +23,7 @@ E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -
 EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
-    "lantern_accept_chains",
+    "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_status_string",
     "lantern_version",
 )
@@ -66,6 +66,12 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_greedy.restype = i32
     lib.lantern_accept_chains.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.lantern_accept_chains.restype = i32
+    lib.lantern_verify_rows.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp, vp, vp]
+    lib.lantern_verify_rows.restype = i32
+    lib.lantern_verify_greedy_rows.argtypes = [vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, f32, vp, vp, vp]
+    lib.lantern_verify_greedy_rows.restype = i32
+    lib.lantern_accept_trees.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.lantern_accept_trees.restype = i32
     lib.lantern_status_string.argtypes = [i32]
     lib.lantern_status_string.restype = ctypes.c_char_p
     lib.lantern_version.argtypes = []
@@ -242,3 +248,89 @@ def accept_chains(accept, resample, L: int, stream=None):
     if rc != OK:
         raise LanternError(rc, "lantern_accept_chains")
     return kept, nxt
+
+
+def _check_row_index(row_index, N):
+    if row_index.dtype != torch.int32 or not row_index.is_contiguous() or row_index.numel() != N:
+        raise ValueError("row_index must be a contiguous int32 tensor with one entry per verification")
+
+
+def verify_rows(target_logits, draft_logits, row_index, draft_tokens, knn, delta: float, uniforms,
+                divergence: str = "tvd", stream=None):
+    """lantern_verify_rows: verification i reads logit row row_index[i].
+    Returns (accept int32[N], resample int32[N]) device tensors."""
+    lib = load()
+    _need_cuda(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
+    if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape or \
+            target_logits.dtype != draft_logits.dtype:
+        raise ValueError("logits must be two [R, V] tensors of equal shape and dtype")
+    if target_logits.stride(1) != 1 or draft_logits.stride(1) != 1 or \
+            target_logits.stride(0) != draft_logits.stride(0):
+        raise ValueError("logit rows must be dense and both tensors must share the row stride")
+    R, V = target_logits.shape
+    N = draft_tokens.numel()
+    _check_row_index(row_index, N)
+    if draft_tokens.dtype != torch.int32 or knn.dtype != torch.int32 or uniforms.dtype != torch.float32:
+        raise TypeError("draft_tokens and knn must be int32, uniforms float32")
+    if uniforms.numel() != 2 * N or knn.dim() != 2 or knn.shape[0] != V:
+        raise ValueError("shape mismatch between tokens, uniforms and the table")
+    if not (draft_tokens.is_contiguous() and knn.is_contiguous() and uniforms.is_contiguous()):
+        raise ValueError("draft_tokens, knn and uniforms must be contiguous")
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev)
+    res = torch.empty(N, dtype=torch.int32, device=dev)
+    rc = lib.lantern_verify_rows(target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits),
+                                 R, V, target_logits.stride(0) if R > 1 else V, row_index.data_ptr(), N,
+                                 draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
+                                 {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta),
+                                 uniforms.data_ptr(), acc.data_ptr(), res.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_rows")
+    return acc, res
+
+
+def verify_greedy_rows(target_logits, row_index, draft_tokens, knn, delta: float, stream=None):
+    """lantern_verify_greedy_rows; returns (accept int32[N], token int32[N]) device tensors."""
+    lib = load()
+    _need_cuda(target_logits, row_index, draft_tokens, knn)
+    if target_logits.dim() != 2 or target_logits.stride(1) != 1:
+        raise ValueError("logits must be a [R, V] tensor with dense rows")
+    R, V = target_logits.shape
+    N = draft_tokens.numel()
+    _check_row_index(row_index, N)
+    if draft_tokens.dtype != torch.int32 or knn.dtype != torch.int32:
+        raise TypeError("draft_tokens and knn must be int32")
+    if knn.dim() != 2 or knn.shape[0] != V or not (draft_tokens.is_contiguous() and knn.is_contiguous()):
+        raise ValueError("the table must be a contiguous [V, k] tensor, the tokens contiguous")
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev)
+    tok = torch.empty(N, dtype=torch.int32, device=dev)
+    rc = lib.lantern_verify_greedy_rows(target_logits.data_ptr(), _dtype_code(target_logits), R, V,
+                                        target_logits.stride(0) if R > 1 else V, row_index.data_ptr(), N,
+                                        draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]), float(delta),
+                                        acc.data_ptr(), tok.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_greedy_rows")
+    return acc, tok
+
+
+def accept_trees(accept, resample, parent, M: int, stream=None):
+    """lantern_accept_trees; accept / resample / parent are int32 device tensors of B*M rows.
+    Returns (len int32[B], path int32[B, M], next_token int32[B])."""
+    lib = load()
+    _need_cuda(accept, resample, parent)
+    for t in (accept, resample, parent):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise TypeError("accept, resample and parent must be contiguous int32 tensors")
+    if accept.numel() != resample.numel() or accept.numel() != parent.numel() or M < 1 or accept.numel() % M:
+        raise ValueError("accept, resample and parent must hold B*M rows")
+    B = accept.numel() // M
+    dev = accept.device
+    n = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, M), dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib.lantern_accept_trees(accept.data_ptr(), resample.data_ptr(), parent.data_ptr(), B, int(M),
+                                  n.data_ptr(), path.data_ptr(), nxt.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_accept_trees")
+    return n, path, nxt

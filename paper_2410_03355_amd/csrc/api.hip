@@ -11,14 +11,18 @@ namespace {
 
 bool dtype_ok(int dt) { return dt == LANTERN_F32 || dt == LANTERN_BF16; }
 
-int verify_impl(const void* target_logits, const void* draft_logits, int logits_dtype, int N, int V,
+// R, row_index: number of logit rows and the row every verification reads; without an index
+// array (row_index null) verification i reads row i and R is N.
+int verify_impl(const void* target_logits, const void* draft_logits, int logits_dtype, int R,
+                const int32_t* row_index, int N, int V,
                 int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
                 int divergence, float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                 float* out_accept_prob, float* out_mass, float* out_g_tok, int32_t* out_a_size,
                 int32_t* out_path, void* hip_stream) {
     if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
-    if (N < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
+    if (N < 0 || R < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
         return LANTERN_E_SHAPE;
+    if (N > 0 && R < 1) return LANTERN_E_SHAPE;
     if (divergence != LANTERN_DIV_TVD && divergence != LANTERN_DIV_JSD) return LANTERN_E_SHAPE;
     if (!(delta >= 0.0f)) return LANTERN_E_DELTA;  // also rejects NaN
     if (N == 0) return LANTERN_OK;
@@ -29,6 +33,8 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.target = target_logits;
     a.draft = draft_logits;
     a.N = N;
+    a.R = R;
+    a.row_index = row_index;
     a.V = V;
     a.stride = row_stride_elems;
     a.tokens = draft_tokens;
@@ -56,7 +62,7 @@ int lantern_verify(const void* target_logits, const void* draft_logits, lantern_
                    int N, int V, int64_t row_stride_elems, const int32_t* draft_tokens,
                    const int32_t* knn, int k, float delta, const float* uniforms,
                    int32_t* out_accept, int32_t* out_resample, void* hip_stream) {
-    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, nullptr, N, V, row_stride_elems,
                        draft_tokens, knn, k, LANTERN_DIV_TVD, delta, uniforms, out_accept, out_resample, nullptr,
                        nullptr, nullptr, nullptr, nullptr, hip_stream);
 }
@@ -67,7 +73,7 @@ int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                       const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                       float* out_accept_prob, float* out_mass, float* out_g_tok,
                       int32_t* out_a_size, int32_t* out_path, void* hip_stream) {
-    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, nullptr, N, V, row_stride_elems,
                        draft_tokens, knn, k, LANTERN_DIV_TVD, delta, uniforms, out_accept, out_resample,
                        out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
 }
@@ -78,24 +84,39 @@ int lantern_verify_divergence(const void* target_logits, const void* draft_logit
                               float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                               float* out_accept_prob, float* out_mass, float* out_g_tok,
                               int32_t* out_a_size, int32_t* out_path, void* hip_stream) {
-    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, V, row_stride_elems,
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, N, nullptr, N, V, row_stride_elems,
                        draft_tokens, knn, k, divergence, delta, uniforms, out_accept, out_resample,
                        out_accept_prob, out_mass, out_g_tok, out_a_size, out_path, hip_stream);
 }
 
-int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype, int N, int V,
-                          int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
-                          float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
-                          void* hip_stream) {
-    if (!dtype_ok((int)logits_dtype)) return LANTERN_E_DTYPE;
-    if (N < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
+int lantern_verify_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                        int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                        const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
+                        const float* uniforms, int32_t* out_accept, int32_t* out_resample, void* hip_stream) {
+    if (N > 0 && !row_index) return LANTERN_E_NULL;
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
+                       draft_tokens, knn, k, divergence, delta, uniforms, out_accept, out_resample, nullptr,
+                       nullptr, nullptr, nullptr, nullptr, hip_stream);
+}
+
+namespace {
+
+int greedy_impl(const void* target_logits, int logits_dtype, int R, const int32_t* row_index, int N, int V,
+                int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
+                float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
+                void* hip_stream) {
+    if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
+    if (N < 0 || R < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
         return LANTERN_E_SHAPE;
+    if (N > 0 && R < 1) return LANTERN_E_SHAPE;
     if (!(delta >= 0.0f)) return LANTERN_E_DELTA;
     if (N == 0) return LANTERN_OK;
     if (!target_logits || !draft_tokens || !knn || !out_accept || !out_token) return LANTERN_E_NULL;
     lantern::GreedyArgs a;
     a.target = target_logits;
     a.N = N;
+    a.R = R;
+    a.row_index = row_index;
     a.V = V;
     a.stride = row_stride_elems;
     a.tokens = draft_tokens;
@@ -105,7 +126,36 @@ int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype,
     a.out_accept = out_accept;
     a.out_token = out_token;
     a.out_path = out_path;
-    const hipError_t e = lantern::launch_verify_greedy(a, (int)logits_dtype, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = lantern::launch_verify_greedy(a, logits_dtype, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
+}  // namespace
+
+int lantern_verify_greedy(const void* target_logits, lantern_dtype logits_dtype, int N, int V,
+                          int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
+                          float delta, int32_t* out_accept, int32_t* out_token, int32_t* out_path,
+                          void* hip_stream) {
+    return greedy_impl(target_logits, (int)logits_dtype, N, nullptr, N, V, row_stride_elems, draft_tokens, knn,
+                       k, delta, out_accept, out_token, out_path, hip_stream);
+}
+
+int lantern_verify_greedy_rows(const void* target_logits, lantern_dtype logits_dtype, int R, int V,
+                               int64_t row_stride_elems, const int32_t* row_index, int N,
+                               const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                               int32_t* out_accept, int32_t* out_token, void* hip_stream) {
+    if (N > 0 && !row_index) return LANTERN_E_NULL;
+    return greedy_impl(target_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems, draft_tokens,
+                       knn, k, delta, out_accept, out_token, nullptr, hip_stream);
+}
+
+int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B, int M,
+                         int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream) {
+    if (B < 0 || M < 1) return LANTERN_E_SHAPE;
+    if (B == 0) return LANTERN_OK;
+    if (!accept || !resample || !parent || !out_len || !out_path || !out_next) return LANTERN_E_NULL;
+    const hipError_t e = lantern::launch_accept_trees(accept, resample, parent, B, M, out_len, out_path,
+                                                      out_next, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 

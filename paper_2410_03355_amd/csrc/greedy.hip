@@ -80,13 +80,16 @@ __device__ void greedy_exact_row(const GreedyArgs& a, int row, unsigned char* ex
     int* sidx = reinterpret_cast<int*>(sval + NW);
     const int nvec = (V + EPV - 1) / EPV;
     const int nchunk = (nvec + NT - 1) / NT;
-    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
+    bool row_ok;
+    const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
+    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride;
     const int xt = a.tokens[row];
     const double delta = (double)a.delta;
 
     // usability and maximum
     int bad = ((unsigned)xt < (unsigned)V) ? 0 : 1;
     const int32_t* nrow = a.knn + (int64_t)(bad ? 0 : xt) * k;
+    if (!row_ok) bad = 1;
     if (!bad)
         for (int j = tid; j < k; j += NT)
             if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
@@ -187,11 +190,13 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     const int nvec = V / EPV;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
     const int row = blockIdx.x;
+    bool row_ok;
+    const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
     // ---- stream the target row: NV 16-byte loads per thread, coalesced ----
     uint4 T[NV];
     {
-        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride);
+        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride);
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
             const int vi = c * NT + tid;
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
         for (int w = 0; w < NW; ++w) { Zt += sh.wsum[w]; Emax = fmaxf(Emax, sh.wemax[w]); }
         const CutResult cut = scan_cut<LT>(Zt, 0, a.delta, 0.f, xt, xs, k, V, a.knn, s_row, ct, scan);
         const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX);
-        const bool cut_ok = cut.definite && !cut.bad && tok_ok && sums_ok;
+        const bool cut_ok = cut.definite && !cut.bad && tok_ok && row_ok && sums_ok;
         const float mass_z = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct)) + cut.S;
         // no term of the row, inside or outside A, reaches the mass of A: accepted without looking at A
         const bool early = cut_ok && (mass_z * (1.f - TAU_ACC) > Emax * (1.f + TAU_ACC) + ABS_SLACK);

@@ -84,12 +84,14 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     const int nvec = V / EPV;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
     const int row = blockIdx.x;
+    bool row_ok;
+    const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
     // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
     uint4 T[NV], G[NV];
     {
-        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride);
-        const uint4* gv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride);
+        const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride);
+        const uint4* gv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride);
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
             const int vi = c * NT + tid;
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             for (int q = 0; q < 4; ++q) m.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
         }
         m.u_acc = a.uniforms[2 * (int64_t)row];
-        m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride, xs0);
+        m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
     }
 
     {
@@ -193,7 +195,7 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             }
             const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
             const CutResult cut = scan_cut<LT>(Zt, a.divergence, a.delta, e_tx, xt, xs, k, V, a.knn, s_row, ct, scan);
-            const int bad = cut.bad | (tok_ok ? 0 : 1);
+            const int bad = cut.bad | ((tok_ok && row_ok) ? 0 : 1);
             const bool cut_definite = cut.definite;
             const int a_size = cut.a_size;
             const float S = cut.S;
@@ -278,8 +280,10 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     double* wtot = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(mask) + (((size_t)nwords * 4 + 7) & ~size_t(7)));
     const int nvec = (V + EPV - 1) / EPV;
     const int nchunk = (nvec + NT - 1) / NT;
-    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)row * a.stride;
-    const LT* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)row * a.stride;
+    bool row_ok;
+    const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
+    const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride;
+    const LT* grow = reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride;
     const int xt = a.tokens[row];
     const double delta = (double)a.delta;
     const double u_acc = (double)a.uniforms[2 * (int64_t)row];
@@ -288,6 +292,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     // ---- usability and maxima: token and table entries in range, no NaN / +inf ----
     int bad = ((unsigned)xt < (unsigned)V) ? 0 : 1;
     const int32_t* nrow = a.knn + (int64_t)(bad ? 0 : xt) * k;
+    if (!row_ok) bad = 1;
     if (!bad)
         for (int j = tid; j < k; j += NT)
             if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;

@@ -7,9 +7,11 @@
 namespace lantern {
 
 struct VerifyArgs {
-    const void* target;       // [N, stride] logits of the target model
-    const void* draft;        // [N, stride] logits of the drafter
-    int N;
+    const void* target;       // [R, stride] logits of the target model
+    const void* draft;        // [R, stride] logits of the drafter
+    int N;                    // verifications
+    int R;                    // logit rows (N without an index array)
+    const int32_t* row_index; // [N] logit row of every verification, or null: row i
     int V;
     int64_t stride;           // elements between rows
     const int32_t* tokens;    // [N] draft tokens
@@ -36,8 +38,10 @@ namespace lantern {
 
 // Greedy-decoding variant: target logits only, no random draws.
 struct GreedyArgs {
-    const void* target;       // [N, stride] logits of the target model
-    int N;
+    const void* target;       // [R, stride] logits of the target model
+    int N;                    // verifications
+    int R;                    // logit rows (N without an index array)
+    const int32_t* row_index; // [N] logit row of every verification, or null: row i
     int V;
     int64_t stride;
     const int32_t* tokens;    // [N] draft tokens
@@ -57,5 +61,9 @@ namespace lantern {
 
 hipError_t launch_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L,
                                 int32_t* out_len, int32_t* out_next, hipStream_t stream);
+
+hipError_t launch_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B,
+                               int M, int32_t* out_len, int32_t* out_path, int32_t* out_next,
+                               hipStream_t stream);
 
 }  // namespace lantern

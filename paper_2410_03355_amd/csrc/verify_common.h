@@ -14,6 +14,15 @@
 
 namespace lantern {
 
+// Row of the logit matrices that verification `row` reads: the row itself, or the entry of the
+// caller's index array (the siblings of a draft tree share the rows of their parent's context).
+// *ok is false for an entry outside [0, R); the row returned is then 0, so loads stay in bounds.
+__device__ __forceinline__ int logit_row(const int32_t* row_index, int R, int row, bool* ok) {
+    const int r = row_index ? row_index[row] : row;
+    *ok = (unsigned)r < (unsigned)R;
+    return *ok ? r : 0;
+}
+
 constexpr float LOG2E_F = 1.44269504088896340736f;
 
 // ---- rounding margins of the fp32 pass -------------------------------------

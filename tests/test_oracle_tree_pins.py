@@ -4,6 +4,7 @@ import numpy as np
 import torch
 
 from synth import workloads
+from parity_utils import random_trees
 
 
 def test_hand_trees(oracle_mod):
@@ -54,21 +55,6 @@ def test_chain_is_the_one_child_case(oracle_mod):
     np.testing.assert_array_equal(next_t, next_c)
     for b in range(B):
         assert list(path[b][: n_t[b]]) == list(range(n_t[b]))
-
-
-def random_trees(rng, B, M, max_children=4):
-    """Random drafting-order trees: every node picks a parent among the earlier nodes (or the
-    prefix) that still has fewer than max_children children."""
-    parent = np.empty((B, M), dtype=np.int32)
-    for b in range(B):
-        count = {-1: 0}
-        for i in range(M):
-            open_nodes = [p for p, c in count.items() if c < max_children]
-            p = int(rng.choice(open_nodes))
-            parent[b, i] = p
-            count[p] += 1
-            count[i] = 0
-    return parent
 
 
 def test_properties_on_random_trees(oracle_mod):
