@@ -274,3 +274,31 @@ def verify_greedy_rows(target_logits, row_index, draft_tokens, knn, k: int, delt
     acc[~ok] = -1
     tok[~ok] = -1
     return acc, tok, diag
+
+
+def philox4x32_10(counter, key):
+    """One Philox4x32-10 block: counter 4 words, key 2 words -> 4 words (uint32)."""
+    lib = _load()
+    U = ctypes.POINTER(ctypes.c_uint32)
+    lib.oracle_philox4x32_10.argtypes = [U, U, U]
+    lib.oracle_philox4x32_10.restype = None
+    c = np.ascontiguousarray(np.asarray(counter, dtype=np.uint32).reshape(4))
+    kk = np.ascontiguousarray(np.asarray(key, dtype=np.uint32).reshape(2))
+    out = np.empty(4, dtype=np.uint32)
+    lib.oracle_philox4x32_10(_p(c, ctypes.c_uint32), _p(kk, ctypes.c_uint32), _p(out, ctypes.c_uint32))
+    return out
+
+
+def build_random(V: int, k: int, seed: int, rows=None) -> np.ndarray:
+    """Random neighbourhood table: token itself, then k-1 other tokens in random order.
+    Returns int32 [r1-r0, k] for rows=(r0, r1), the whole table by default."""
+    lib = _load()
+    lib.oracle_build_random_rows.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int,
+                                             ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+    lib.oracle_build_random_rows.restype = ctypes.c_int
+    r0, r1 = (0, V) if rows is None else rows
+    out = np.empty((r1 - r0, k), dtype=np.int32)
+    if lib.oracle_build_random_rows(int(V), int(k), int(seed) & 0xFFFFFFFFFFFFFFFF, r0, r1,
+                                    _p(out, ctypes.c_int32)) != 0:
+        raise ValueError("oracle_build_random_rows: bad arguments")
+    return out

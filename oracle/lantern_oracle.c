@@ -645,3 +645,73 @@ int oracle_accept_trees(const int32_t* accept, const int32_t* resample, const in
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Random neighbourhoods (Section 5.3.1 and Table 3, the "random selection"   */
+/* row of the ablation on latent proximity measures)                          */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), written out: ten rounds
+ * of two 32x32 -> 64 bit multiplications, the key advanced by the Weyl
+ * constants between rounds.
+ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+typedef struct { uint32_t key; int32_t token; } keyed_token;
+
+static int cmp_keyed_token(const void* a, const void* b) {
+    const keyed_token* x = (const keyed_token*)a;
+    const keyed_token* y = (const keyed_token*)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return (x->token > y->token) - (x->token < y->token);
+}
+
+/*
+ * The paper only says that the k tokens are selected at random.  The reading
+ * taken here: B_k(x) holds x itself in slot 0 and then k-1 other tokens, a
+ * uniform sample without replacement in uniformly random order, fixed once
+ * per token like the nearest-neighbour table.  Every pair (x, y) gets a 32-bit
+ * key: word y mod 4 of Philox4x32-10 at counter (y div 4, x, 0, 0) under the
+ * key (seed low word, seed high word); row x lists the other tokens by
+ * increasing (key, token).  Writes rows r0 .. r1-1 into out[(r1-r0) * k].
+ */
+int oracle_build_random_rows(int V, int k, uint64_t seed, int r0, int r1, int32_t* out) {
+    if (V < 1 || k < 1 || k > V || r0 < 0 || r1 > V || r0 > r1 || !out) return -1;
+    const uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
+    keyed_token* others = (keyed_token*)malloc(sizeof(keyed_token) * (size_t)V);
+    if (!others) return -2;
+    for (int x = r0; x < r1; ++x) {
+        int n = 0;
+        for (int y = 0; y < V; ++y) {
+            if (y == x) continue;
+            uint32_t ctr[4] = {(uint32_t)(y / 4), (uint32_t)x, 0u, 0u};
+            uint32_t words[4];
+            oracle_philox4x32_10(ctr, key, words);
+            others[n].key = words[y % 4];
+            others[n].token = y;
+            n = n + 1;
+        }
+        qsort(others, (size_t)n, sizeof(keyed_token), cmp_keyed_token);
+        int32_t* row = out + (size_t)(x - r0) * k;
+        row[0] = x;
+        for (int j = 1; j < k; ++j) row[j] = others[j - 1].token;
+    }
+    free(others);
+    return 0;
+}
