@@ -215,6 +215,26 @@ int lantern_accept_chains(const int32_t* accept, const int32_t* resample, int B,
                           int32_t* out_next, void* hip_stream);
 
 /*
+ * Random neighbourhood table (Section 5.3.1 and Table 3: the ablation that
+ * selects the k tokens at random instead of by latent proximity).  Row x holds
+ * x in slot 0 and then k-1 other tokens, a uniform sample without replacement
+ * in random order, fixed by the seed: the pair (x, y) gets as key word y mod 4
+ * of Philox4x32-10 at counter (y div 4, x, 0, 0) under the key (seed low word,
+ * seed high word), and the row lists the other tokens by increasing
+ * (key, token).  The table for a smaller k is a prefix of the one for a
+ * larger k.  It feeds lantern_verify like the table of lantern_build_knn.
+ *
+ *   out_knn  device, [V, k] int32, written
+ * Limits: k <= LANTERN_RANDOM_MAX_K.  Should more than 4096 keys of one row
+ * share a 32-bit value (not with this generator), that row's slots 1..k-1
+ * are written as -1, which lantern_verify reports as unusable.
+ * Errors: E_SHAPE (V < 1, V > LANTERN_MAX_VOCAB, k < 1, k > V, k over the
+ * limit), E_NULL, E_DEVICE.
+ */
+#define LANTERN_RANDOM_MAX_K 4096
+int lantern_build_random(int V, int k, uint64_t seed, int32_t* out_knn, void* hip_stream);
+
+/*
  * Verification over shared logit rows.  A draft tree holds several candidate
  * tokens for one position (the paper verifies 60 candidates per step of the
  * target model, Appendix on experimental details); the siblings are verified

@@ -289,16 +289,16 @@ def philox4x32_10(counter, key):
     return out
 
 
-def build_random(V: int, k: int, seed: int, rows=None) -> np.ndarray:
+def build_random(V: int, k: int, seed: int, rows=None, threads: int = 8) -> np.ndarray:
     """Random neighbourhood table: token itself, then k-1 other tokens in random order.
     Returns int32 [r1-r0, k] for rows=(r0, r1), the whole table by default."""
     lib = _load()
     lib.oracle_build_random_rows.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int,
-                                             ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+                                             ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
     lib.oracle_build_random_rows.restype = ctypes.c_int
     r0, r1 = (0, V) if rows is None else rows
     out = np.empty((r1 - r0, k), dtype=np.int32)
     if lib.oracle_build_random_rows(int(V), int(k), int(seed) & 0xFFFFFFFFFFFFFFFF, r0, r1,
-                                    _p(out, ctypes.c_int32)) != 0:
+                                    _p(out, ctypes.c_int32), int(threads)) != 0:
         raise ValueError("oracle_build_random_rows: bad arguments")
     return out

@@ -691,12 +691,20 @@ static int cmp_keyed_token(const void* a, const void* b) {
  * key (seed low word, seed high word); row x lists the other tokens by
  * increasing (key, token).  Writes rows r0 .. r1-1 into out[(r1-r0) * k].
  */
-int oracle_build_random_rows(int V, int k, uint64_t seed, int r0, int r1, int32_t* out) {
+int oracle_build_random_rows(int V, int k, uint64_t seed, int r0, int r1, int32_t* out, int threads) {
     if (V < 1 || k < 1 || k > V || r0 < 0 || r1 > V || r0 > r1 || !out) return -1;
     const uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
-    keyed_token* others = (keyed_token*)malloc(sizeof(keyed_token) * (size_t)V);
-    if (!others) return -2;
+    int failed = 0;
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 16) num_threads(threads > 0 ? threads : 1)
+#endif
     for (int x = r0; x < r1; ++x) {
+        keyed_token* others = (keyed_token*)malloc(sizeof(keyed_token) * (size_t)V);
+        if (!others) {
+            failed = 1;
+            continue;
+        }
         int n = 0;
         for (int y = 0; y < V; ++y) {
             if (y == x) continue;
@@ -711,7 +719,7 @@ int oracle_build_random_rows(int V, int k, uint64_t seed, int r0, int r1, int32_
         int32_t* row = out + (size_t)(x - r0) * k;
         row[0] = x;
         for (int j = 1; j < k; ++j) row[j] = others[j - 1].token;
+        free(others);
     }
-    free(others);
-    return 0;
+    return failed ? -2 : 0;
 }

@@ -24,6 +24,7 @@ EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
+    "lantern_build_random",
     "lantern_status_string",
     "lantern_version",
 )
@@ -72,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_greedy_rows.restype = i32
     lib.lantern_accept_trees.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.lantern_accept_trees.restype = i32
+    lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
+    lib.lantern_build_random.restype = i32
     lib.lantern_status_string.argtypes = [i32]
     lib.lantern_status_string.restype = ctypes.c_char_p
     lib.lantern_version.argtypes = []
@@ -334,3 +337,17 @@ def accept_trees(accept, resample, parent, M: int, stream=None):
     if rc != OK:
         raise LanternError(rc, "lantern_accept_trees")
     return n, path, nxt
+
+
+RANDOM_MAX_K = 4096
+
+
+def build_random(V: int, k: int, seed: int, device="cuda", stream=None):
+    """lantern_build_random; returns the [V, k] int32 table on the device."""
+    lib = load()
+    out = torch.empty((V, k), dtype=torch.int32, device=device)
+    rc = lib.lantern_build_random(int(V), int(k), int(seed) & 0xFFFFFFFFFFFFFFFF, out.data_ptr(),
+                                  _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_build_random")
+    return out

@@ -203,6 +203,23 @@ int lantern_build_knn(const void* codebook, lantern_dtype cb_dtype, int V, int d
                                     workspace, workspace_bytes, hip_stream);
 }
 
+int lantern_build_random(int V, int k, uint64_t seed, int32_t* out_knn, void* hip_stream) {
+    if (V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || k > LANTERN_RANDOM_MAX_K) return LANTERN_E_SHAPE;
+    if (!out_knn) return LANTERN_E_NULL;
+    static_assert(LANTERN_RANDOM_MAX_K == lantern::RANDOM_MAX_K, "limits of the header and the kernel differ");
+    // keys are uniform on [0, 2^32): the k-1 smallest of V-1 lie below this with about three
+    // standard deviations to spare (the kernel moves the threshold when they do not)
+    uint64_t t0 = 1ull << 32;
+    if (V > 1) {
+        const double need = (double)(k - 1);
+        const double frac = (need + 3.0 * sqrt(need) + 8.0) / (double)(V - 1);
+        if (frac < 1.0) t0 = (uint64_t)ceil(frac * 4294967296.0);
+        if (t0 < 1) t0 = 1;
+    }
+    const hipError_t e = lantern::launch_build_random(V, k, seed, t0, out_knn, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 const char* lantern_status_string(int status) {
     switch (status) {
         case LANTERN_OK: return "ok";

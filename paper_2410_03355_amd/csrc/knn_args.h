@@ -21,4 +21,8 @@ struct KnnArgs {
 size_t knn_workspace_bytes(int V, int d, int k);
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream);
 
+// Random table of k <= RANDOM_MAX_K entries per row; t0: first threshold on the 32-bit keys, in [1, 2^32].
+constexpr int RANDOM_MAX_K = 4096;
+hipError_t launch_build_random(int V, int k, uint64_t seed, uint64_t t0, int32_t* out, hipStream_t stream);
+
 }  // namespace lantern
