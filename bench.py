@@ -42,12 +42,15 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent"])
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
-    ap.add_argument("--mode", default="sample", choices=["sample", "greedy"],
-                    help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only")
+    ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree"],
+                    help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only; "
+                         "tree: rows_per_step/60 random draft trees of 60 candidates, siblings sharing logit rows "
+                         "(lantern_verify_rows, then lantern_accept_trees)")
     ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
                     help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
+                    help="the CPU oracle is timed on whole steps of the workload until this much time has passed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a counter run has a kernel of "
@@ -93,10 +96,42 @@ def main() -> int:
     torch.cuda.synchronize()
 
     greedy = args.mode == "greedy"
+    tree = args.mode == "tree"
     lib = lantern.load()
     dcode = lantern.BF16 if cfg.logit_dtype == "bf16" else lantern.F32
 
+    if tree:
+        import numpy as np
+        from synth import trees
+        M = 60
+        B = cfg.rows // M
+        rows_per_step = B * M
+        parent_host = trees.random_trees(np.random.default_rng(workloads.BASE_SEED), B, M)
+        parent = torch.from_numpy(parent_host).to(dev).reshape(-1)
+        tbufs = []
+        for s_ in range(nbuf):
+            st_, ri, tok, un = trees.tree_step(cfg, parent_host, step=s_, variant=args.variant, device=dev)
+            tbufs.append((st_, torch.from_numpy(ri).to(dev), torch.from_numpy(tok).to(dev), un))
+        distinct_rows = len(set(tbufs[0][1].cpu().tolist()))
+        t_len = torch.empty(B, dtype=torch.int32, device=dev)
+        t_path = torch.empty(B * M, dtype=torch.int32, device=dev)
+        t_next = torch.empty(B, dtype=torch.int32, device=dev)
+        del bufs
+        torch.cuda.synchronize()
+
     def step(i: int):
+        if tree:
+            st_, ri, tok, un = tbufs[i % nbuf]
+            acc, res = out_acc[i % nbuf], out_res[i % nbuf]
+            rc = lib.lantern_verify_rows(st_.target_logits.data_ptr(), st_.draft_logits.data_ptr(), dcode,
+                                         B * (M + 1), cfg.V, cfg.V, ri.data_ptr(), rows_per_step, tok.data_ptr(),
+                                         knn.data_ptr(), cfg.k, 0, float(delta), un.data_ptr(), acc.data_ptr(),
+                                         res.data_ptr(), stream.cuda_stream)
+            assert rc == 0, rc
+            rc = lib.lantern_accept_trees(acc.data_ptr(), res.data_ptr(), parent.data_ptr(), B, M, t_len.data_ptr(),
+                                          t_path.data_ptr(), t_next.data_ptr(), stream.cuda_stream)
+            assert rc == 0, rc
+            return
         b = bufs[i % nbuf]
         if greedy:
             rc = lib.lantern_verify_greedy(b.target_logits.data_ptr(), dcode, cfg.rows, cfg.V, cfg.V,
@@ -139,15 +174,17 @@ def main() -> int:
     # average launch duration: includes the gap between consecutive launches on the stream
     kernel_ms_avg = ev0.elapsed_time(ev1) / args.steps
 
-    rows = cfg.rows
+    rows = rows_per_step if tree else cfg.rows
     logit_bytes = 2 if cfg.logit_dtype == "bf16" else 4
     bytes_per_launch = algorithmic_bytes_per_verification(cfg.V, cfg.k, logit_bytes) * rows
+    if tree:  # every distinct pair of logit rows once; per verification the table row and the small items
+        bytes_per_launch = 2 * cfg.V * logit_bytes * distinct_rows + (4 * cfg.k + 24) * rows
     if greedy:  # one logit row, the table row, token, two outputs
         bytes_per_launch = (cfg.V * logit_bytes + 4 * cfg.k + 12) * rows
     achieved_gbs = bytes_per_launch / (kernel_ms_avg * 1e-3) / 1e9
     value = rows * args.steps / wall
 
-    acc_all = torch.stack(out_acc[: min(nbuf, args.steps)])
+    acc_all = torch.stack(out_acc[: min(nbuf, args.steps)])[:, :rows]
     accept_frac = float((acc_all == 1).float().mean().item())
 
     result = {
@@ -169,49 +206,55 @@ def main() -> int:
             "rows_per_step": rows,
             "distinct_step_buffers": nbuf,
             "accepted_fraction": accept_frac,
+            **({"trees": B, "candidates_per_tree": M, "distinct_logit_rows": distinct_rows,
+                "mean_accepted_length": float(t_len.float().mean().item())} if tree else {}),
         },
         "roofline": {
             "bound": "hbm",
             "kernel": "greedy_fast" if greedy else "verify_fast",
+            **({"note": "per step: verify_fast over shared rows plus the tree walk"} if tree else {}),
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": args.traffic_bytes if args.traffic_bytes is not None
-            else (None if greedy or args.divergence != "tvd" else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
+            else (None if greedy or tree or args.divergence != "tvd"
+                  else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "kernel_ms_avg": kernel_ms_avg,
         },
         "knn_build_ms": knn_build_ms,
     }
 
-    if not args.no_cpu_baseline and not greedy and args.divergence == "tvd":
+    if not args.no_cpu_baseline and not greedy and not tree and args.divergence == "tvd":
         import numpy as np
         import oracle  # CPU baseline leg only
         threads = min(os.cpu_count() or 1, 16, oracle.max_threads())
-        n_cpu = max(1, min(args.cpu_steps, nbuf))
         knn_host = knn.cpu().numpy()
         host = [(b.target_logits.float().cpu().numpy(), b.draft_logits.float().cpu().numpy(),
-                 b.draft_tokens.cpu().numpy(), b.uniforms.cpu().numpy()) for b in bufs[:n_cpu]]
-        c0 = time.perf_counter()
+                 b.draft_tokens.cpu().numpy(), b.uniforms.cpu().numpy()) for b in bufs]
+        # untimed: the GPU's outputs of the timed region against the oracle, buffer by buffer
         mism = 0
-        for i, (tl, dl, tok, un) in enumerate(host):
+        for i, (tl, dl, tok, un) in enumerate(host[: min(nbuf, args.steps, 2)]):
             acc, res, _ = oracle.verify(tl, dl, tok, knn_host, cfg.k, delta, un, threads=threads,
                                         want_diag=False)
-            if args.steps > i:
-                mism += int((acc != out_acc[i].cpu().numpy()).sum() + (res != out_res[i].cpu().numpy()).sum())
-        c1 = time.perf_counter()
-        # the comparison above is outside what is timed below: time the oracle alone on the same rows
+            mism += int((acc != out_acc[i].cpu().numpy()).sum() + (res != out_res[i].cpu().numpy()).sum())
+        # timed: the oracle alone, whole steps of the same workload until the time is up
+        n_cpu = 0
         c0 = time.perf_counter()
-        for tl, dl, tok, un in host:
+        while True:
+            tl, dl, tok, un = host[n_cpu % nbuf]
             oracle.verify(tl, dl, tok, knn_host, cfg.k, delta, un, threads=threads, want_diag=False)
-        c1 = time.perf_counter()
+            n_cpu += 1
+            c1 = time.perf_counter()
+            if c1 - c0 >= args.cpu_seconds:
+                break
         result["cpu_baseline"] = {
             "value": n_cpu * rows / (c1 - c0),
             "unit": "verifications/s",
             "cores": threads,
             "kind": "oracle",
-            "sample": f"{n_cpu} step(s) of {rows} rows of the same workload, rows split over "
+            "sample": f"{n_cpu} step(s) of {rows} rows of the same workload ({c1 - c0:.1f} s), rows split over "
                       f"{threads} threads",
             "mismatches_vs_gpu": mism,
         }

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     const int k = a.k;
     const int nvec = V / EPV;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
-    const int row = blockIdx.x;
+    const int row = verification_of_block(blockIdx.x, a.N, a.row_index != nullptr);
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
 template <typename LT>
 __global__ __launch_bounds__(NT) void greedy_exact(GreedyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    greedy_exact_row<LT, false>(a, blockIdx.x, smem, nullptr);
+    greedy_exact_row<LT, false>(a, verification_of_block(blockIdx.x, a.N, a.row_index != nullptr), smem, nullptr);
 }
 
 template <typename K>

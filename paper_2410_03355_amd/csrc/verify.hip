@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     const int k = a.k;
     const int nvec = V / EPV;
     const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
-    const int row = blockIdx.x;
+    const int row = verification_of_block(blockIdx.x, a.N, a.row_index != nullptr);
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
@@ -488,7 +488,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
 template <typename LT>
 __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    exact_row<LT, false>(a, blockIdx.x, smem, nullptr, false, 0.f, 0.f);
+    exact_row<LT, false>(a, verification_of_block(blockIdx.x, a.N, a.row_index != nullptr), smem, nullptr, false, 0.f, 0.f);
 }
 
 // ---------------------------------------------------------------------------

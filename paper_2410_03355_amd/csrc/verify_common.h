@@ -14,6 +14,20 @@
 
 namespace lantern {
 
+// Verification handled by workgroup b of N.  Without an index array every verification has logit
+// rows of its own and workgroup b takes verification b.  With one, candidates that are neighbours
+// in drafting order share logit rows (the siblings of a draft tree); workgroups go to the 8 XCDs
+// round-robin (b mod 8) and every XCD has an L2 of its own, so XCD x is given the contiguous range
+// x*N/8 .. (x+1)*N/8 of the verifications and siblings meet in one L2 instead of fetching their
+// row once per XCD.
+constexpr int XCDS = 8;
+__device__ __forceinline__ int verification_of_block(int b, int N, bool shared_rows) {
+    if (!shared_rows) return b;
+    const int x = b % XCDS, slot = b / XCDS;
+    const int q = N / XCDS, r = N % XCDS;
+    return x * q + (x < r ? x : r) + slot;
+}
+
 // Row of the logit matrices that verification `row` reads: the row itself, or the entry of the
 // caller's index array (the siblings of a draft tree share the rows of their parent's context).
 // *ok is false for an entry outside [0, R); the row returned is then 0, so loads stay in bounds.

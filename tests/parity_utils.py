@@ -5,6 +5,8 @@ from __future__ import annotations
 import numpy as np
 import torch
 
+from synth.trees import random_trees, tree_step  # noqa: F401  (used by the tree tests)
+
 # tolerance on probabilities and acceptance ratios: 1e-5 relative for fp32
 # logits, 2e-3 for bf16 logits (decisions and indices are compared exactly)
 PROB_TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
@@ -71,38 +73,3 @@ def compare_verify(oracle, lantern, target, draft, tokens, table, delta, uniform
         np.testing.assert_allclose(g[name][ok], ref[ok], rtol=tol, atol=1e-30, err_msg=f"{label} {name}")
     assert np.all(np.isnan(g["accept_prob"][~ok]))
     return acc_o, res_o, diag, g
-
-
-def random_trees(rng, B, M, max_children=4):
-    """Random drafting-order trees: every node picks a parent among the earlier nodes (or the
-    prefix, -1) that still has fewer than max_children children.  Returns parent int32[B, M]."""
-    parent = np.empty((B, M), dtype=np.int32)
-    for b in range(B):
-        count = {-1: 0}
-        for i in range(M):
-            open_nodes = [p for p, c in count.items() if c < max_children]
-            p = int(rng.choice(open_nodes))
-            parent[b, i] = p
-            count[p] += 1
-            count[i] = 0
-    return parent
-
-
-def tree_step(cfg, parent, step, variant="plain"):
-    """Synthetic verification step of B draft trees: one pair of logit rows per context (the prefix
-    and every node, M + 1 per tree), row_index[i] = the row after node i's parent, and as draft
-    token of the j-th child of a context the j-th most likely token of the drafter's row."""
-    from synth import workloads
-    B, M = parent.shape
-    st = workloads.make_step(cfg, step=step, rows=B * (M + 1), variant=variant)
-    row_index = (np.arange(B, dtype=np.int64)[:, None] * (M + 1) + parent + 1).astype(np.int32)
-    rank = np.zeros((B, M), dtype=np.int64)
-    for b in range(B):
-        seen = {}
-        for i in range(M):
-            rank[b, i] = seen.get(parent[b, i], 0)
-            seen[parent[b, i]] = rank[b, i] + 1
-    top = torch.topk(st.draft_logits.float(), int(rank.max()) + 1, dim=1).indices.numpy()
-    tokens = top[row_index.reshape(-1), rank.reshape(-1)].astype(np.int32)
-    un = st.uniforms[: B * M].contiguous()
-    return st, row_index.reshape(-1), tokens, un
