@@ -25,9 +25,11 @@ if ROOT not in sys.path:
 METRIC = "relaxed verifications/sec at V=16384,k=1000 (bf16 logits); % HBM peak"
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of verify_fast on the stress/plain workload, from the rocprofv3 FETCH_SIZE and
-# WRITE_SIZE runs summarised in profiles/verify_fast_stress_plain.md (FETCH_SIZE scaled by the factor a
+# WRITE_SIZE runs summarised under profiles/ (one file per mode; FETCH_SIZE scaled by the factor a
 # plain 256 MiB copy gives in the same run).  Other workloads have no counter run: traffic is null.
-MEASURED_TRAFFIC_BYTES = {("stress", "plain"): 131062.1 * 1.99972 * 1024 + 240.0 * 1024}
+MEASURED_TRAFFIC_BYTES = {("stress", "plain", "sample"): 131140.3 * 1.99972 * 1024 + 240.1 * 1024,
+                          ("stress", "plain", "greedy"): 69196.9 * 1.99973 * 1024 + 240.0 * 1024,
+                          ("stress", "plain", "tree"): 85349.3 * 1.99973 * 1024 + 240.0 * 1024}
 
 
 def algorithmic_bytes_per_verification(V: int, k: int, logit_bytes: int) -> int:
@@ -218,8 +220,8 @@ def main() -> int:
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": args.traffic_bytes if args.traffic_bytes is not None
-            else (None if greedy or tree or args.divergence != "tvd"
-                  else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant))),
+            else (None if args.divergence != "tvd"
+                  else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant, args.mode))),
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "kernel_ms_avg": kernel_ms_avg,
         },
