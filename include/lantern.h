@@ -270,7 +270,10 @@ int lantern_verify_greedy_rows(const void* target_logits, lantern_dtype logits_d
  * index order, the first accepted one is taken and the walk goes on from it.
  * With one child per node this is lantern_accept_chains.
  *
- *   accept, resample  [B*M] int32, as written by lantern_verify_rows
+ *   accept, resample  [B*M] int32, as written by lantern_verify_rows;
+ *             resample may be NULL: out_next then holds, where it would hold a
+ *             resampled token, the index b*M + node of the verification whose
+ *             resampled token it is (for lantern_resample_selected)
  *   parent    [B*M] int32
  *   out_len   [B] int32: number of accepted nodes
  *   out_path  [B*M] int32: the accepted nodes of tree b, in order, then -1
@@ -284,6 +287,59 @@ int lantern_verify_greedy_rows(const void* target_logits, lantern_dtype logits_d
  * Errors: E_NULL, E_SHAPE (B < 0, M < 1), E_DEVICE.  B = 0 does nothing.
  */
 int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B, int M,
+                         int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream);
+
+/*
+ * The same verification split in two, for callers that need the resampled
+ * token of few verifications only.  Algorithm 1 leaves its loop at the first
+ * rejection: of all the candidates of a chain or tree, one residual is sampled.
+ *
+ * lantern_decide_rows: the decisions of lantern_verify_rows without the
+ * resampled tokens (a rejection is then settled by the fp32 pass as well).
+ *   row_index  may be NULL when R == N: verification i reads row i
+ *   out_accept [N] int32: 1, 0, or -1 for an unusable verification; equal to
+ *              what lantern_verify_rows writes
+ *
+ * lantern_resample_selected: for i < n_sel, the resampled token of
+ * verification select[i], from the same inputs.
+ *   select     device, [n_sel] int32: verification indices in [0, N); a
+ *              negative entry is copied to out_token[i] unchanged (the codes of
+ *              lantern_accept_trees pass through)
+ *   out_token  device, [n_sel] int32: the token lantern_verify_rows would write
+ *              to out_resample[select[i]] if that verification is rejected; -1
+ *              if it is accepted; -2 if it is unusable or select[i] >= N.  May
+ *              be the same array as select.
+ * Errors: as lantern_verify_rows; E_SHAPE also for n_sel < 0, for n_sel > 0
+ * with N == 0, and for a NULL row_index with R != N.
+ */
+int lantern_decide_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                        int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                        const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
+                        const float* uniforms, int32_t* out_accept, void* hip_stream);
+
+int lantern_resample_selected(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                              int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                              const int32_t* draft_tokens, const int32_t* knn, int k, int divergence,
+                              float delta, const float* uniforms, const int32_t* select, int n_sel,
+                              int32_t* out_token, void* hip_stream);
+
+/*
+ * One verification step over B draft trees of M candidates (Algorithm 1 along
+ * the branches; rule of lantern_accept_trees): decisions of all B*M
+ * candidates, the walk, and the residual draw of the one candidate per tree
+ * whose token is needed.  Same results as lantern_verify_rows followed by
+ * lantern_accept_trees, without the resampling work that the walk never
+ * looks at.
+ *
+ *   row_index, draft_tokens, uniforms, parent  [B*M], candidate i of tree b at b*M + i
+ *   out_accept [B*M], out_len [B], out_path [B*M], out_next [B]  as in
+ *              lantern_verify_rows / lantern_accept_trees
+ * Errors: those of the three calls; E_SHAPE also when B*M exceeds INT_MAX.
+ */
+int lantern_verify_trees(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                         int R, int V, int64_t row_stride_elems, const int32_t* row_index,
+                         const int32_t* parent, int B, int M, const int32_t* draft_tokens, const int32_t* knn,
+                         int k, int divergence, float delta, const float* uniforms, int32_t* out_accept,
                          int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream);
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -24,7 +24,7 @@ EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
-    "lantern_build_random",
+    "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
     "lantern_status_string",
     "lantern_version",
 )
@@ -73,6 +73,14 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_greedy_rows.restype = i32
     lib.lantern_accept_trees.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.lantern_accept_trees.restype = i32
+    lib.lantern_decide_rows.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp, vp]
+    lib.lantern_decide_rows.restype = i32
+    lib.lantern_resample_selected.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp,
+                                              i32, vp, vp]
+    lib.lantern_resample_selected.restype = i32
+    lib.lantern_verify_trees.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, i32, f32, vp,
+                                         vp, vp, vp, vp, vp]
+    lib.lantern_verify_trees.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
     lib.lantern_build_random.restype = i32
     lib.lantern_status_string.argtypes = [i32]
@@ -321,18 +329,20 @@ def accept_trees(accept, resample, parent, M: int, stream=None):
     """lantern_accept_trees; accept / resample / parent are int32 device tensors of B*M rows.
     Returns (len int32[B], path int32[B, M], next_token int32[B])."""
     lib = load()
-    _need_cuda(accept, resample, parent)
-    for t in (accept, resample, parent):
+    given = [t for t in (accept, resample, parent) if t is not None]
+    _need_cuda(*given)
+    for t in given:
         if t.dtype != torch.int32 or not t.is_contiguous():
             raise TypeError("accept, resample and parent must be contiguous int32 tensors")
-    if accept.numel() != resample.numel() or accept.numel() != parent.numel() or M < 1 or accept.numel() % M:
+    if any(t.numel() != accept.numel() for t in given) or M < 1 or accept.numel() % M:
         raise ValueError("accept, resample and parent must hold B*M rows")
     B = accept.numel() // M
     dev = accept.device
     n = torch.empty(B, dtype=torch.int32, device=dev)
     path = torch.empty((B, M), dtype=torch.int32, device=dev)
     nxt = torch.empty(B, dtype=torch.int32, device=dev)
-    rc = lib.lantern_accept_trees(accept.data_ptr(), resample.data_ptr(), parent.data_ptr(), B, int(M),
+    rc = lib.lantern_accept_trees(accept.data_ptr(), None if resample is None else resample.data_ptr(),
+                                  parent.data_ptr(), B, int(M),
                                   n.data_ptr(), path.data_ptr(), nxt.data_ptr(), _stream_ptr(stream))
     if rc != OK:
         raise LanternError(rc, "lantern_accept_trees")
@@ -351,3 +361,90 @@ def build_random(V: int, k: int, seed: int, device="cuda", stream=None):
     if rc != OK:
         raise LanternError(rc, "lantern_build_random")
     return out
+
+
+def _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms):
+    _need_cuda(target_logits, draft_logits, draft_tokens, knn, uniforms)
+    if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape or \
+            target_logits.dtype != draft_logits.dtype:
+        raise ValueError("logits must be two [R, V] tensors of equal shape and dtype")
+    if target_logits.stride(1) != 1 or draft_logits.stride(1) != 1 or \
+            target_logits.stride(0) != draft_logits.stride(0):
+        raise ValueError("logit rows must be dense and both tensors must share the row stride")
+    R, V = target_logits.shape
+    N = draft_tokens.numel()
+    if row_index is not None:
+        _need_cuda(row_index)
+        _check_row_index(row_index, N)
+    elif R != N:
+        raise ValueError("without row_index there must be one logit row per verification")
+    if draft_tokens.dtype != torch.int32 or knn.dtype != torch.int32 or uniforms.dtype != torch.float32:
+        raise TypeError("draft_tokens and knn must be int32, uniforms float32")
+    if uniforms.numel() != 2 * N or knn.dim() != 2 or knn.shape[0] != V:
+        raise ValueError("shape mismatch between tokens, uniforms and the table")
+    if not (draft_tokens.is_contiguous() and knn.is_contiguous() and uniforms.is_contiguous()):
+        raise ValueError("draft_tokens, knn and uniforms must be contiguous")
+    return R, V, N, target_logits.stride(0) if R > 1 else V
+
+
+def decide_rows(target_logits, draft_logits, row_index, draft_tokens, knn, delta: float, uniforms,
+                divergence: str = "tvd", stream=None):
+    """lantern_decide_rows; returns accept int32[N] (device)."""
+    lib = load()
+    R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
+    acc = torch.empty(N, dtype=torch.int32, device=target_logits.device)
+    rc = lib.lantern_decide_rows(target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits),
+                                 R, V, stride, None if row_index is None else row_index.data_ptr(), N,
+                                 draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
+                                 {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta),
+                                 uniforms.data_ptr(), acc.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_decide_rows")
+    return acc
+
+
+def resample_selected(target_logits, draft_logits, row_index, draft_tokens, knn, delta: float, uniforms,
+                      select, divergence: str = "tvd", stream=None):
+    """lantern_resample_selected; returns token int32[len(select)] (device)."""
+    lib = load()
+    R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
+    _need_cuda(select)
+    if select.dtype != torch.int32 or not select.is_contiguous():
+        raise TypeError("select must be a contiguous int32 tensor")
+    out = torch.empty(select.numel(), dtype=torch.int32, device=target_logits.device)
+    rc = lib.lantern_resample_selected(target_logits.data_ptr(), draft_logits.data_ptr(),
+                                       _dtype_code(target_logits), R, V, stride,
+                                       None if row_index is None else row_index.data_ptr(), N,
+                                       draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
+                                       {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta),
+                                       uniforms.data_ptr(), select.data_ptr(), select.numel(), out.data_ptr(),
+                                       _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_resample_selected")
+    return out
+
+
+def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_tokens, knn, delta: float,
+                 uniforms, divergence: str = "tvd", stream=None):
+    """lantern_verify_trees; returns (accept int32[B*M], len int32[B], path int32[B, M], next int32[B])."""
+    lib = load()
+    R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
+    _need_cuda(parent)
+    if row_index is None:
+        raise ValueError("row_index is required")
+    if parent.dtype != torch.int32 or not parent.is_contiguous() or parent.numel() != N or M < 1 or N % M:
+        raise ValueError("parent must be a contiguous int32 tensor of B*M entries")
+    B = N // M
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev)
+    n = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, M), dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib.lantern_verify_trees(target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits),
+                                  R, V, stride, row_index.data_ptr(), parent.data_ptr(), B, int(M),
+                                  draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
+                                  {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta), uniforms.data_ptr(),
+                                  acc.data_ptr(), n.data_ptr(), path.data_ptr(), nxt.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_trees")
+    return acc, n, path, nxt

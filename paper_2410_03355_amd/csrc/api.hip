@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation on the host, then kernel launches.
 #include <hip/hip_runtime.h>
+#include <limits.h>
 #include <math.h>
 #include <stdint.h>
 
@@ -18,17 +19,20 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
                 int64_t row_stride_elems, const int32_t* draft_tokens, const int32_t* knn, int k,
                 int divergence, float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                 float* out_accept_prob, float* out_mass, float* out_g_tok, int32_t* out_a_size,
-                int32_t* out_path, void* hip_stream) {
+                int32_t* out_path, void* hip_stream, int mode = lantern::VERIFY_FULL,
+                const int32_t* select = nullptr, int n_sel = 0) {
     if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
     if (N < 0 || R < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
         return LANTERN_E_SHAPE;
     if (N > 0 && R < 1) return LANTERN_E_SHAPE;
     if (divergence != LANTERN_DIV_TVD && divergence != LANTERN_DIV_JSD) return LANTERN_E_SHAPE;
     if (!(delta >= 0.0f)) return LANTERN_E_DELTA;  // also rejects NaN
-    if (N == 0) return LANTERN_OK;
-    if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms || !out_accept ||
-        !out_resample)
-        return LANTERN_E_NULL;
+    if (n_sel < 0 || (n_sel > 0 && N == 0)) return LANTERN_E_SHAPE;
+    if (mode == lantern::VERIFY_SELECTED ? n_sel == 0 : N == 0) return LANTERN_OK;
+    if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms) return LANTERN_E_NULL;
+    if (mode != lantern::VERIFY_SELECTED && !out_accept) return LANTERN_E_NULL;
+    if (mode != lantern::VERIFY_DECIDE && !out_resample) return LANTERN_E_NULL;
+    if (mode == lantern::VERIFY_SELECTED && !select) return LANTERN_E_NULL;
     lantern::VerifyArgs a;
     a.target = target_logits;
     a.draft = draft_logits;
@@ -41,6 +45,9 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.knn = knn;
     a.k = k;
     a.divergence = divergence;
+    a.mode = mode;
+    a.select = select;
+    a.n_sel = n_sel;
     a.delta = delta;
     a.uniforms = uniforms;
     a.out_accept = out_accept;
@@ -50,7 +57,9 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.out_gtok = out_g_tok;
     a.out_asize = out_a_size;
     a.out_path = out_path;
-    const hipError_t e = lantern::launch_verify(a, logits_dtype, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = mode == lantern::VERIFY_SELECTED
+                             ? lantern::launch_resample_selected(a, logits_dtype, static_cast<hipStream_t>(hip_stream))
+                             : lantern::launch_verify(a, logits_dtype, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
@@ -97,6 +106,27 @@ int lantern_verify_rows(const void* target_logits, const void* draft_logits, lan
     return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
                        draft_tokens, knn, k, divergence, delta, uniforms, out_accept, out_resample, nullptr,
                        nullptr, nullptr, nullptr, nullptr, hip_stream);
+}
+
+int lantern_decide_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                        int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                        const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
+                        const float* uniforms, int32_t* out_accept, void* hip_stream) {
+    if (!row_index && R != N) return LANTERN_E_SHAPE;   // without an index array row i belongs to verification i
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
+                       draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr, nullptr,
+                       nullptr, nullptr, nullptr, nullptr, hip_stream, lantern::VERIFY_DECIDE);
+}
+
+int lantern_resample_selected(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                              int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
+                              const int32_t* draft_tokens, const int32_t* knn, int k, int divergence,
+                              float delta, const float* uniforms, const int32_t* select, int n_sel,
+                              int32_t* out_token, void* hip_stream) {
+    if (!row_index && R != N) return LANTERN_E_SHAPE;
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
+                       draft_tokens, knn, k, divergence, delta, uniforms, nullptr, out_token, nullptr,
+                       nullptr, nullptr, nullptr, nullptr, hip_stream, lantern::VERIFY_SELECTED, select, n_sel);
 }
 
 namespace {
@@ -153,7 +183,7 @@ int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const i
                          int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream) {
     if (B < 0 || M < 1) return LANTERN_E_SHAPE;
     if (B == 0) return LANTERN_OK;
-    if (!accept || !resample || !parent || !out_len || !out_path || !out_next) return LANTERN_E_NULL;
+    if (!accept || !parent || !out_len || !out_path || !out_next) return LANTERN_E_NULL;   // resample may be null
     const hipError_t e = lantern::launch_accept_trees(accept, resample, parent, B, M, out_len, out_path,
                                                       out_next, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
@@ -218,6 +248,26 @@ int lantern_build_random(int V, int k, uint64_t seed, int32_t* out_knn, void* hi
     }
     const hipError_t e = lantern::launch_build_random(V, k, seed, t0, out_knn, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
+int lantern_verify_trees(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                         int R, int V, int64_t row_stride_elems, const int32_t* row_index,
+                         const int32_t* parent, int B, int M, const int32_t* draft_tokens, const int32_t* knn,
+                         int k, int divergence, float delta, const float* uniforms, int32_t* out_accept,
+                         int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream) {
+    if (B < 0 || M < 1 || (int64_t)B * M > INT_MAX) return LANTERN_E_SHAPE;
+    const int N = B * M;
+    if (B > 0 && (!row_index || !parent || !out_len || !out_path || !out_next)) return LANTERN_E_NULL;
+    // decisions of all candidates, the walk (which leaves in out_next the verification to resample
+    // or a negative code), then the residual draw of that one verification per tree, in place
+    int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index, N,
+                                 draft_tokens, knn, k, divergence, delta, uniforms, out_accept, hip_stream);
+    if (rc != LANTERN_OK || B == 0) return rc;
+    rc = lantern_accept_trees(out_accept, nullptr, parent, B, M, out_len, out_path, out_next, hip_stream);
+    if (rc != LANTERN_OK) return rc;
+    return lantern_resample_selected(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index,
+                                     N, draft_tokens, knn, k, divergence, delta, uniforms, out_next, B, out_next,
+                                     hip_stream);
 }
 
 const char* lantern_status_string(int status) {

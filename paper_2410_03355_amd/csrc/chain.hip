@@ -38,6 +38,8 @@ __global__ __launch_bounds__(NT) void accept_chains_kernel(const int32_t* accept
 // (-1: the node follows the committed prefix).  Standing at a node, its children are tried in
 // index order and the first accepted one is taken; Algorithm 1 is the case of one child per node.
 // One wavefront per tree; every step scans the nodes after the current one, 64 at a time.
+// Without resampled tokens (resample null) the walk reports, in place of the token, which
+// verification (tree * M + node) has to be resampled.
 __global__ __launch_bounds__(NT) void accept_trees_kernel(const int32_t* accept, const int32_t* resample,
                                                           const int32_t* parent, int B, int M, int32_t* out_len,
                                                           int32_t* out_path, int32_t* out_next) {
@@ -78,7 +80,8 @@ __global__ __launch_bounds__(NT) void accept_trees_kernel(const int32_t* accept,
                 continue;
             }
             if (decisive >= 0) next = -2;                     // an unusable row ends the walk
-            else if (first_child >= 0) next = res[first_child];  // every child was rejected
+            else if (first_child >= 0)                        // every child was rejected
+                next = resample ? res[first_child] : tree * M + first_child;
             else next = -1;                                   // a leaf: every draft on the branch accepted
             break;
         }

@@ -203,14 +203,16 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             const float MA = e_tx + S;                // mass * Zt
             const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
             const float rhs = MA * Zg;                // mass  * Zt * Zg
-            const bool accept = (lhs + ABS_SLACK) < rhs * (1.f - TAU_ACC);
+            const bool accept = (lhs + ACC_SLACK) < rhs * (1.f - TAU_ACC);
+            // a definite rejection settles the row only when no resampled token is asked for
+            const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + ACC_SLACK);
             // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
             const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
-            const bool settled = !bad && sums_ok && cut_definite && accept;
+            const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
             if (lane == 0) {
                 if (settled) {
-                    a.out_accept[row] = 1;
-                    a.out_resample[row] = -1;
+                    a.out_accept[row] = accept ? 1 : 0;
+                    if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
                     const float mass = MA / Zt;
                     const float gx = e_gx / Zg;
                     if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
@@ -266,6 +268,8 @@ __device__ __forceinline__ double resid_term(int x, int xt, int V, float lt, flo
 template <typename LT, bool VEC>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g) {
+    const bool selected = a.mode == VERIFY_SELECTED;
+    const int out = selected ? (int)blockIdx.x : row;   // slot of the outputs this workgroup writes
     using L = Lane<LT>;
     constexpr int EPV = EXV;
     ExactShared& sh = *reinterpret_cast<ExactShared*>(ex);
@@ -326,13 +330,17 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     bad = block_or_i(bad, sh.ired, tid);
     if (bad) {
         if (tid == 0) {
-            a.out_accept[row] = -1;
-            a.out_resample[row] = -1;
-            if (a.out_prob) a.out_prob[row] = NAN;
-            if (a.out_mass) a.out_mass[row] = NAN;
-            if (a.out_gtok) a.out_gtok[row] = NAN;
-            if (a.out_asize) a.out_asize[row] = -1;
-            if (a.out_path) a.out_path[row] = 1;
+            if (selected) {
+                a.out_resample[out] = -2;
+            } else {
+                a.out_accept[row] = -1;
+                if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
+                if (a.out_prob) a.out_prob[row] = NAN;
+                if (a.out_mass) a.out_mass[row] = NAN;
+                if (a.out_gtok) a.out_gtok[row] = NAN;
+                if (a.out_asize) a.out_asize[row] = -1;
+                if (a.out_path) a.out_path[row] = 1;
+            }
         }
         return;
     }
@@ -373,7 +381,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;
     const double mass = t_tok + S;
     const bool accepted = (u_acc * g_tok < mass);
-    if (tid == 0) {
+    if (tid == 0 && !selected) {
         double ap;
         if (g_tok > 0.0) ap = fmin(1.0, mass / g_tok);
         else ap = mass > 0.0 ? 1.0 : 0.0;
@@ -383,10 +391,14 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
         if (a.out_asize) a.out_asize[row] = a_size;
         if (a.out_path) a.out_path[row] = 1;
     }
-    if (accepted) {
+    if (accepted || a.mode == VERIFY_DECIDE) {
         if (tid == 0) {
-            a.out_accept[row] = 1;
-            a.out_resample[row] = -1;
+            if (selected) {
+                a.out_resample[out] = -1;
+            } else {
+                a.out_accept[row] = accepted ? 1 : 0;
+                if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
+            }
         }
         return;
     }
@@ -476,8 +488,8 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
                     if (found < 0 && cum > cthr && r[e] > 0.0) found = vi * EPV + e;
                 }
                 if (found < 0) found = lastpos;
-                a.out_accept[row] = 0;
-                a.out_resample[row] = found;
+                if (!selected) a.out_accept[row] = 0;
+                a.out_resample[out] = found;
             }
         }
         break;
@@ -489,6 +501,18 @@ template <typename LT>
 __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     exact_row<LT, false>(a, verification_of_block(blockIdx.x, a.N, a.row_index != nullptr), smem, nullptr, false, 0.f, 0.f);
+}
+
+// VERIFY_SELECTED: workgroup i evaluates verification select[i] and writes out_resample[i].
+template <typename LT, bool VEC>
+__global__ __launch_bounds__(NT) void resample_selected(VerifyArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int v = a.select[blockIdx.x];
+    if (v < 0 || v >= a.N) {   // uniform per workgroup
+        if (threadIdx.x == 0) a.out_resample[blockIdx.x] = v < 0 ? v : -2;
+        return;
+    }
+    exact_row<LT, VEC>(a, v, smem, nullptr, false, 0.f, 0.f);
 }
 
 // ---------------------------------------------------------------------------
@@ -543,6 +567,26 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((verify_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
+}
+
+template <typename LT>
+static hipError_t launch_selected_typed(const VerifyArgs& a, hipStream_t stream) {
+    const size_t lds = exact_lds_bytes(a.V);
+    const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
+                            (uintptr_t)(a.stride * (int64_t)sizeof(LT));
+    const bool vec = (align & 15) == 0 && (a.V % EXV) == 0;   // rows 16-byte aligned, whole vectors
+    const hipError_t e = vec ? allow_lds(&resample_selected<LT, true>, lds) : allow_lds(&resample_selected<LT, false>, lds);
+    if (e != hipSuccess) return e;
+    if (vec)
+        hipLaunchKernelGGL((resample_selected<LT, true>), dim3(a.n_sel), dim3(NT), lds, stream, a);
+    else
+        hipLaunchKernelGGL((resample_selected<LT, false>), dim3(a.n_sel), dim3(NT), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {
+    if (logits_dtype == 0) return launch_selected_typed<float>(a, stream);
+    return launch_selected_typed<uint16_t>(a, stream);
 }
 
 hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {

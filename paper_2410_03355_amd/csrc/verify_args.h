@@ -6,6 +6,13 @@
 
 namespace lantern {
 
+// VERIFY_FULL: decision, and the resampled token of every rejected row.
+// VERIFY_DECIDE: decision only; out_resample is not touched (rejections settle in fp32 as well).
+// VERIFY_SELECTED: workgroup i evaluates verification select[i] in fp64 and writes only
+//   out_resample[i]: the resampled token, -1 if that verification is accepted, -2 if it is
+//   unusable or out of range; a negative select[i] is copied through.
+enum { VERIFY_FULL = 0, VERIFY_DECIDE = 1, VERIFY_SELECTED = 2 };
+
 struct VerifyArgs {
     const void* target;       // [R, stride] logits of the target model
     const void* draft;        // [R, stride] logits of the drafter
@@ -18,6 +25,9 @@ struct VerifyArgs {
     const int32_t* knn;       // [V, k] neighbour table
     int k;
     int divergence;           // bound on A: 0 total variation distance, 1 Jensen-Shannon divergence
+    int mode;                 // VERIFY_FULL, VERIFY_DECIDE or VERIFY_SELECTED
+    const int32_t* select;    // VERIFY_SELECTED: [n_sel] verification per workgroup (negative: passed through)
+    int n_sel;
     float delta;
     const float* uniforms;    // [N, 2]
     int32_t* out_accept;      // [N]
@@ -31,6 +41,9 @@ struct VerifyArgs {
 
 // Enqueues the fp32 pass and the fp64 pass on the stream.  logits_dtype: 0 fp32, 1 bf16.
 hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream);
+
+// VERIFY_SELECTED: one workgroup per entry of a.select.
+hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipStream_t stream);
 
 }  // namespace lantern
 

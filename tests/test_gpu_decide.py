@@ -1,0 +1,189 @@
+"""GPU parity of the split verification (lantern_decide_rows, lantern_resample_selected) and of the
+fused tree step (lantern_verify_trees) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from synth import workloads
+from parity_utils import random_table, random_trees, sparse_table_from_oracle, tree_step
+
+pytestmark = pytest.mark.gpu
+
+
+def _decide_and_select(oracle, lantern, target, draft, tokens, table, delta, uniforms, divergence="tvd",
+                       threads=8, row_index=None):
+    """decide_rows must give the oracle's decisions; resample_selected on every rejected row (plus
+    an accepted one, a negative code and an index past the end) the oracle's tokens."""
+    k = table.shape[1]
+    if row_index is None:
+        acc_o, res_o, _ = oracle.verify(target, draft, tokens, table, k, delta, uniforms, threads=threads,
+                                        divergence=divergence)
+    else:
+        acc_o, res_o, _ = oracle.verify_rows(target, draft, row_index, tokens, table, k, delta, uniforms,
+                                             threads=threads, divergence=divergence)
+    dev = "cuda"
+    args = (target.to(dev), draft.to(dev), None if row_index is None else torch.from_numpy(row_index).to(dev),
+            torch.as_tensor(tokens).to(dev), torch.from_numpy(np.ascontiguousarray(table)).to(dev), delta,
+            uniforms.to(dev))
+    acc = lantern.decide_rows(*args, divergence=divergence)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    N = len(acc_o)
+    sel = list(np.nonzero(acc_o == 0)[0][:200]) + list(np.nonzero(acc_o == 1)[0][:3]) + \
+        list(np.nonzero(acc_o == -1)[0][:3]) + [-1, -2, -3, N, N + 5]
+    sel = np.array(sel, dtype=np.int32)
+    got = lantern.resample_selected(*args, torch.from_numpy(sel).to(dev), divergence=divergence).cpu().numpy()
+    want = np.array([s if s < 0 else (-2 if s >= N else (res_o[s] if acc_o[s] == 0 else (-1 if acc_o[s] == 1 else -2)))
+                     for s in sel], dtype=np.int32)
+    np.testing.assert_array_equal(got, want)
+    return acc_o, res_o
+
+
+@pytest.mark.parametrize("divergence", ["tvd", "jsd"])
+@pytest.mark.parametrize("delta", [0.0, 0.1, 0.5])
+def test_tiny(oracle_mod, lantern_gpu, divergence, delta):
+    cfg = workloads.CONFIGS["tiny"]
+    table = oracle_mod.build_knn(workloads.make_codebook(cfg).numpy(), cfg.k, threads=8)
+    st = workloads.make_step(cfg, step=9)
+    acc, res = _decide_and_select(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                  st.draft_tokens.numpy(), table, delta, st.uniforms, divergence)
+    assert (acc == 0).any() and (acc == 1).any()
+
+
+@pytest.mark.parametrize("variant,delta", [("plain", 0.4), ("plain", 0.002), ("reject", 0.0), ("peaked", 0.01),
+                                           ("peaked", 0.3)])
+def test_llamagen_shape(oracle_mod, lantern_gpu, variant, delta):
+    cfg = workloads.CONFIGS["llamagen_step"]
+    st = workloads.make_step(cfg, step=4, rows=300, variant=variant)
+    table = sparse_table_from_oracle(oracle_mod, workloads.make_codebook(cfg).numpy(), cfg.k,
+                                     st.draft_tokens.numpy())
+    _decide_and_select(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens.numpy(), table,
+                       delta, st.uniforms)
+
+
+def test_stress_reject_mix_full_step(oracle_mod, lantern_gpu):
+    """3840 rows of which most are rejected: the fp32 pass settles the rejections too."""
+    cfg = workloads.CONFIGS["stress"]
+    st = workloads.make_step(cfg, step=3, variant="reject")
+    table = random_table(cfg.V, cfg.k, seed=8)
+    acc, res = _decide_and_select(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
+                                  st.draft_tokens.numpy(), table, 0.0, st.uniforms, threads=16)
+    assert (acc == 0).mean() > 0.3
+
+
+def test_wide_latent_fp32_and_unusable_rows(oracle_mod, lantern_gpu):
+    cfg = workloads.CONFIGS["wide_latent"]
+    st = workloads.make_step(cfg, step=2, rows=256, variant="reject")
+    table = random_table(cfg.V, cfg.k, seed=4)
+    t = st.target_logits.clone()
+    g = st.draft_logits.clone()
+    tok = st.draft_tokens.numpy().copy()
+    t[3, 100] = float("nan")
+    g[5, :] = float("-inf")
+    tok[7] = -1
+    tok[9] = cfg.V
+    acc, res = _decide_and_select(oracle_mod, lantern_gpu, t, g, tok, table, 0.05, st.uniforms)
+    assert list(acc[[3, 5, 7, 9]]) == [-1] * 4
+
+
+@pytest.mark.parametrize("V,k,N,dtype", [(7, 7, 5, torch.float32), (1003, 50, 40, torch.bfloat16),
+                                         (4096, 2500, 9, torch.bfloat16), (40000, 100, 6, torch.float32)])
+def test_shapes_off_the_fast_path(oracle_mod, lantern_gpu, V, k, N, dtype):
+    rng = np.random.default_rng(V + k)
+    t = torch.from_numpy((rng.standard_normal((N, V)) * 2).astype(np.float32)).to(dtype)
+    g = (t.float() + torch.from_numpy(rng.standard_normal((N, V)).astype(np.float32))).to(dtype)
+    tok = rng.integers(0, V, N).astype(np.int32)
+    un = torch.from_numpy(rng.random((N, 2)).astype(np.float32))
+    table = random_table(V, k, seed=V)
+    for delta in (0.0, 0.2):
+        _decide_and_select(oracle_mod, lantern_gpu, t, g, tok, table, delta, un)
+
+
+def _expected_tree_outputs(oracle, acc_o, res_o, parent, M):
+    n_o, path_o, next_o = oracle.accept_trees(acc_o.reshape(-1, M), res_o.reshape(-1, M), parent, M)
+    # the verification whose token follows: the first child of the last accepted node
+    stop = next_o.copy()
+    for b in range(parent.shape[0]):
+        if next_o[b] >= 0:
+            cur = path_o[b, n_o[b] - 1] if n_o[b] else -1
+            stop[b] = b * M + int(np.flatnonzero(parent[b] == cur)[0])
+    return n_o, path_o, next_o, stop
+
+
+@pytest.mark.parametrize("cfg_name,B,variant,delta", [("tiny", 12, "plain", 0.3), ("llamagen_step", 4, "plain", 0.4),
+                                                      ("llamagen_step", 4, "reject", 0.05),
+                                                      ("llamagen_step", 3, "peaked", 0.01)])
+def test_verify_trees(oracle_mod, lantern_gpu, cfg_name, B, variant, delta):
+    cfg = workloads.CONFIGS[cfg_name]
+    M = 9 if cfg_name == "tiny" else 60
+    rng = np.random.default_rng(B + M)
+    parent = random_trees(rng, B, M, max_children=4)
+    st, row_index, tokens, un = tree_step(cfg, parent, step=5, variant=variant)
+    if cfg_name == "tiny":
+        table = oracle_mod.build_knn(workloads.make_codebook(cfg).numpy(), cfg.k, threads=8)
+        row_index[11] = -1                                  # an unusable verification inside a tree
+    else:
+        table = sparse_table_from_oracle(oracle_mod, workloads.make_codebook(cfg).numpy(), cfg.k, tokens)
+    acc_o, res_o, _ = oracle_mod.verify_rows(st.target_logits, st.draft_logits, row_index, tokens, table, cfg.k,
+                                             delta, un, threads=8)
+    n_o, path_o, next_o, stop = _expected_tree_outputs(oracle_mod, acc_o, res_o, parent, M)
+    dev = "cuda"
+    par_d = torch.from_numpy(parent).to(dev).reshape(-1)
+    args = (st.target_logits.to(dev), st.draft_logits.to(dev), torch.from_numpy(row_index).to(dev))
+    tail = (torch.from_numpy(tokens).to(dev), torch.from_numpy(np.ascontiguousarray(table)).to(dev), delta,
+            un.to(dev))
+    acc, n, path, nxt = lantern_gpu.verify_trees(*args, par_d, M, *tail)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+    np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+    # the walk without resampled tokens names the verification to resample
+    n2, path2, stop2 = lantern_gpu.accept_trees(acc, None, par_d, M)
+    np.testing.assert_array_equal(stop2.cpu().numpy(), stop)
+    np.testing.assert_array_equal(n2.cpu().numpy(), n_o)
+
+
+def test_stress_trees_fused_step(oracle_mod, lantern_gpu):
+    """64 trees of 60 candidates, mostly rejected candidates as under the paper's acceptance rates."""
+    cfg = workloads.CONFIGS["stress"]
+    rng = np.random.default_rng(21)
+    B, M = 64, 60
+    parent = random_trees(rng, B, M, max_children=4)
+    st, row_index, tokens, un = tree_step(cfg, parent, step=8, variant="reject")
+    table = random_table(cfg.V, cfg.k, seed=8)
+    delta = 0.0
+    acc_o, res_o, _ = oracle_mod.verify_rows(st.target_logits, st.draft_logits, row_index, tokens, table, cfg.k,
+                                             delta, un, threads=16)
+    n_o, path_o, next_o, _ = _expected_tree_outputs(oracle_mod, acc_o, res_o, parent, M)
+    dev = "cuda"
+    acc, n, path, nxt = lantern_gpu.verify_trees(st.target_logits.to(dev), st.draft_logits.to(dev),
+                                                 torch.from_numpy(row_index).to(dev),
+                                                 torch.from_numpy(parent).to(dev).reshape(-1), M,
+                                                 torch.from_numpy(tokens).to(dev), torch.from_numpy(table).to(dev),
+                                                 delta, un.to(dev))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+    np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+    assert (acc_o == 0).mean() > 0.3 and (next_o >= 0).sum() > 10
+
+
+def test_argument_errors(lantern_gpu):
+    lib = lantern_gpu.load()
+    t = torch.zeros((2, 16), device="cuda")
+    tok = torch.zeros(3, dtype=torch.int32, device="cuda")
+    knn = torch.arange(16, dtype=torch.int32, device="cuda").reshape(16, 1)
+    un = torch.zeros((3, 2), device="cuda")
+    # no row_index although R != N
+    rc = lib.lantern_decide_rows(t.data_ptr(), t.data_ptr(), 0, 2, 16, 16, None, 3, tok.data_ptr(), knn.data_ptr(), 1,
+                                 0, 0.1, un.data_ptr(), tok.data_ptr(), None)
+    assert rc == -2
+    rc = lib.lantern_resample_selected(t.data_ptr(), t.data_ptr(), 0, 3, 16, 16, None, 3, tok.data_ptr(),
+                                       knn.data_ptr(), 1, 0, 0.1, un.data_ptr(), None, 2, tok.data_ptr(), None)
+    assert rc == -1
+    rc = lib.lantern_resample_selected(t.data_ptr(), t.data_ptr(), 0, 3, 16, 16, None, 3, tok.data_ptr(),
+                                       knn.data_ptr(), 1, 0, 0.1, un.data_ptr(), tok.data_ptr(), -1, tok.data_ptr(),
+                                       None)
+    assert rc == -2
