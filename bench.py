@@ -47,7 +47,7 @@ def main() -> int:
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree"],
                     help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only; "
                          "tree: rows_per_step/60 random draft trees of 60 candidates, siblings sharing logit rows "
-                         "(lantern_verify_rows, then lantern_accept_trees)")
+                         "(lantern_verify_trees: decisions, walk, one residual draw per tree)")
     ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
                     help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
@@ -125,13 +125,11 @@ def main() -> int:
         if tree:
             st_, ri, tok, un = tbufs[i % nbuf]
             acc, res = out_acc[i % nbuf], out_res[i % nbuf]
-            rc = lib.lantern_verify_rows(st_.target_logits.data_ptr(), st_.draft_logits.data_ptr(), dcode,
-                                         B * (M + 1), cfg.V, cfg.V, ri.data_ptr(), rows_per_step, tok.data_ptr(),
-                                         knn.data_ptr(), cfg.k, 0, float(delta), un.data_ptr(), acc.data_ptr(),
-                                         res.data_ptr(), stream.cuda_stream)
-            assert rc == 0, rc
-            rc = lib.lantern_accept_trees(acc.data_ptr(), res.data_ptr(), parent.data_ptr(), B, M, t_len.data_ptr(),
-                                          t_path.data_ptr(), t_next.data_ptr(), stream.cuda_stream)
+            rc = lib.lantern_verify_trees(st_.target_logits.data_ptr(), st_.draft_logits.data_ptr(), dcode,
+                                          B * (M + 1), cfg.V, cfg.V, ri.data_ptr(), parent.data_ptr(), B, M,
+                                          tok.data_ptr(), knn.data_ptr(), cfg.k, 0, float(delta), un.data_ptr(),
+                                          acc.data_ptr(), t_len.data_ptr(), t_path.data_ptr(), t_next.data_ptr(),
+                                          stream.cuda_stream)
             assert rc == 0, rc
             return
         b = bufs[i % nbuf]
@@ -214,7 +212,8 @@ def main() -> int:
         "roofline": {
             "bound": "hbm",
             "kernel": "greedy_fast" if greedy else "verify_fast",
-            **({"note": "per step: verify_fast over shared rows plus the tree walk"} if tree else {}),
+            **({"note": "per step: verify_fast over shared rows, the tree walk, one fp64 residual draw per tree"}
+               if tree else {}),
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

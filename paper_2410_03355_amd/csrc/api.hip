@@ -48,6 +48,7 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.mode = mode;
     a.select = select;
     a.n_sel = n_sel;
+    a.stage_rows = 0;
     a.delta = delta;
     a.uniforms = uniforms;
     a.out_accept = out_accept;

@@ -45,9 +45,9 @@ constexpr size_t FAST_SHARED_HEAD = offsetof(FastShared, gs);
 constexpr size_t FAST_SHARED_TAIL = sizeof(FastShared) - FAST_SHARED_HEAD;
 static_assert(FAST_SHARED_HEAD % 16 == 0, "the exact path's LDS region must be 16-byte aligned");
 
-template <typename LT, bool VEC>
+template <typename LT, bool VEC, int TNT = NT>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
-                          bool have_max, float max_t, float max_g);
+                          bool have_max, float max_t, float max_g, const unsigned char* lds_grow = nullptr);
 
 // Per-row scalars and table slots, fetched together with the row.
 struct RowMeta {
@@ -238,10 +238,11 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
 
 // LDS the exact path needs beyond whatever precedes it: reductions, a bitmask
 // of A over the vocabulary, one fp64 partial sum per (vector chunk, wavefront).
-__host__ __device__ inline size_t exact_lds_bytes(int V) {
+__host__ __device__ inline size_t exact_lds_bytes(int V, int threads = NT) {
     const size_t nvec = ((size_t)V + EXV - 1) / EXV;
-    const size_t nchunk = (nvec + NT - 1) / NT;
-    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 + nchunk * NW * sizeof(double);
+    const size_t nchunk = (nvec + threads - 1) / threads;
+    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 +
+           nchunk * (threads / WAVE) * sizeof(double);
 }
 
 // One residual term: max(0, t_A(x) - g(x)) (or t_A(x) when the residual has no mass).
@@ -260,14 +261,15 @@ __device__ __forceinline__ double resid_term(int x, int xt, int V, float lt, flo
 }
 
 // Evaluates one row in fp64 with the whole workgroup.  ex: LDS region of
-// exact_lds_bytes().  lds_row: the raw target row in LDS, or null.  have_max:
+// exact_lds_bytes().  lds_row, lds_grow: the raw target / draft row in LDS, or null.  have_max:
 // the caller has the row maxima and knows both rows are free of NaN and +inf.
-// Token order of the vector layout: vector vi = chunk*NT + tid, so (chunk,
+// TNT: threads of the calling workgroup.  Token order of the vector layout: vector vi = chunk*TNT + tid, so (chunk,
 // wavefront, lane, element) is ascending token order.  Every pass over the row
 // loads the next chunk's vectors before it works on the current one.
-template <typename LT, bool VEC>
+template <typename LT, bool VEC, int TNT>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
-                          bool have_max, float max_t, float max_g) {
+                          bool have_max, float max_t, float max_g, const unsigned char* lds_grow) {
+    constexpr int TNW = TNT / WAVE;
     const bool selected = a.mode == VERIFY_SELECTED;
     const int out = selected ? (int)blockIdx.x : row;   // slot of the outputs this workgroup writes
     using L = Lane<LT>;
@@ -283,7 +285,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     const int nwords = (V + 31) >> 5;
     double* wtot = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(mask) + (((size_t)nwords * 4 + 7) & ~size_t(7)));
     const int nvec = (V + EPV - 1) / EPV;
-    const int nchunk = (nvec + NT - 1) / NT;
+    const int nchunk = (nvec + TNT - 1) / TNT;
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
     const LT* trow = reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride;
@@ -298,7 +300,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     const int32_t* nrow = a.knn + (int64_t)(bad ? 0 : xt) * k;
     if (!row_ok) bad = 1;
     if (!bad)
-        for (int j = tid; j < k; j += NT)
+        for (int j = tid; j < k; j += TNT)
             if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
     float mtf = neg_inf_f(), mgf = neg_inf_f();
     if (have_max) {
@@ -307,14 +309,14 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     } else {
         float tn[EPV], gn[EPV];
         VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
-        VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+        VecLoad<LT, VEC>::load(grow, lds_grow, tid, V, gn);
         for (int c = 0; c < nchunk; ++c) {
             float tf[EPV], gf[EPV];
 #pragma unroll
             for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
             if (c + 1 < nchunk) {
-                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * NT + tid, V, tn);
-                VecLoad<LT, VEC>::load(grow, nullptr, (c + 1) * NT + tid, V, gn);
+                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * TNT + tid, V, tn);
+                VecLoad<LT, VEC>::load(grow, lds_grow, (c + 1) * TNT + tid, V, gn);
             }
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
@@ -324,10 +326,10 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
             }
         }
     }
-    const double mt = block_max((double)mtf, sh.red, tid);
-    const double mg = block_max((double)mgf, sh.red2, tid);
+    const double mt = block_max<TNW>((double)mtf, sh.red, tid);
+    const double mg = block_max<TNW>((double)mgf, sh.red2, tid);
     if (mt == -INFINITY || mg == -INFINITY) bad = 1;
-    bad = block_or_i(bad, sh.ired, tid);
+    bad = block_or_i<TNW>(bad, sh.ired, tid);
     if (bad) {
         if (tid == 0) {
             if (selected) {
@@ -350,14 +352,14 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     {
         float tn[EPV], gn[EPV];
         VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
-        VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+        VecLoad<LT, VEC>::load(grow, lds_grow, tid, V, gn);
         for (int c = 0; c < nchunk; ++c) {
             float tf[EPV], gf[EPV];
 #pragma unroll
             for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
             if (c + 1 < nchunk) {
-                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * NT + tid, V, tn);
-                VecLoad<LT, VEC>::load(grow, nullptr, (c + 1) * NT + tid, V, gn);
+                VecLoad<LT, VEC>::load(trow, lds_row, (c + 1) * TNT + tid, V, tn);
+                VecLoad<LT, VEC>::load(grow, lds_grow, (c + 1) * TNT + tid, V, gn);
             }
             double st = 0.0, sg = 0.0;
 #pragma unroll
@@ -369,14 +371,14 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
             zg += sg;
         }
     }
-    zt = block_sum(zt, sh.red, tid);
-    zg = block_sum(zg, sh.red2, tid);
+    zt = block_sum<TNW>(zt, sh.red, tid);
+    zg = block_sum<TNW>(zg, sh.red2, tid);
 
     // ---- nearest-first walk over the table row ----
     const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
     int a_size;
     double S;
-    exact_walk<LT>(trow, lds_row, nrow, k, xt, mt, zt, a.divergence, t_tok, delta, sh, tid, &a_size, &S);
+    exact_walk<LT, TNT>(trow, lds_row, nrow, k, xt, mt, zt, a.divergence, t_tok, delta, sh, tid, &a_size, &S);
 
     const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;
     const double mass = t_tok + S;
@@ -404,9 +406,9 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     }
 
     // ---- rejected: distorted target t_A, residual max(0, t_A - g), inverse CDF ----
-    for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
+    for (int w = tid; w < nwords; w += TNT) mask[w] = 0u;
     __syncthreads();
-    for (int j = tid; j < a_size; j += NT) {
+    for (int j = tid; j < a_size; j += TNT) {
         const int n = nrow[j];
         if (n != xt) atomicOr(&mask[n >> 5], 1u << (n & 31));
     }
@@ -419,15 +421,15 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
         {
             float tn[EPV], gn[EPV];
             VecLoad<LT, VEC>::load(trow, lds_row, tid, V, tn);
-            VecLoad<LT, VEC>::load(grow, nullptr, tid, V, gn);
+            VecLoad<LT, VEC>::load(grow, lds_grow, tid, V, gn);
             for (int c = 0; c < nchunk; ++c) {
-                const int vi = c * NT + tid;
+                const int vi = c * TNT + tid;
                 float tf[EPV], gf[EPV];
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) { tf[e] = tn[e]; gf[e] = gn[e]; }
                 if (c + 1 < nchunk) {
-                    VecLoad<LT, VEC>::load(trow, lds_row, vi + NT, V, tn);
-                    VecLoad<LT, VEC>::load(grow, nullptr, vi + NT, V, gn);
+                    VecLoad<LT, VEC>::load(trow, lds_row, vi + TNT, V, tn);
+                    VecLoad<LT, VEC>::load(grow, lds_grow, vi + TNT, V, gn);
                 }
                 double s = 0.0;
 #pragma unroll
@@ -435,33 +437,44 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
                     s += resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass,
                                     zero_resid);
                 s = wave_sum(s);
-                if (lane == 0) wtot[c * NW + wave] = s;
+                if (lane == 0) wtot[c * TNW + wave] = s;
             }
         }
         __syncthreads();
-        const int nent = nchunk * NW;
+        // every wavefront scans the partial sums itself, 64 entries at a time in token order
+        const int nent = nchunk * TNW;
         double Z = 0.0;
-        for (int e = 0; e < nent; ++e) Z += wtot[e];
+        for (int base = 0; base < nent; base += WAVE) Z += wave_sum(base + lane < nent ? wtot[base + lane] : 0.0);
         if (!(Z > 0.0) && !zero_resid) {  // residual without mass: sample t_A itself
             zero_resid = 1;
             __syncthreads();
             continue;
         }
         const double cthr = u_res * Z;
-        // first (chunk, wavefront) whose running sum exceeds the threshold
+        // first (chunk, wavefront) whose running sum exceeds the threshold; P: the sum before it
         double P = 0.0;
-        int ent = nent - 1;
-        for (int e = 0; e < nent; ++e) {
-            const double nx = P + wtot[e];
-            if (nx > cthr) { ent = e; break; }
-            P = nx;
+        int ent = -1;
+        for (int base = 0; base < nent && ent < 0; base += WAVE) {
+            const double incl = P + wave_scan_incl(base + lane < nent ? wtot[base + lane] : 0.0);
+            const unsigned long long cross = __ballot(base + lane < nent && incl > cthr);
+            if (cross) {
+                const int l = __ffsll((long long)cross) - 1;
+                ent = base + l;
+                P = l ? __shfl(incl, l - 1, WAVE) : P;
+            } else {
+                P = __shfl(incl, WAVE - 1, WAVE);
+            }
         }
-        if (wave == (ent % NW)) {
-            const int c = ent / NW;
-            const int vi = c * NT + tid;
+        if (ent < 0) {   // rounding left no crossing: the last entry takes the draw
+            ent = nent - 1;
+            P -= wtot[ent];
+        }
+        if (wave == (ent % TNW)) {
+            const int c = ent / TNW;
+            const int vi = c * TNT + tid;
             float tf[EPV], gf[EPV];
             VecLoad<LT, VEC>::load(trow, lds_row, vi, V, tf);
-            VecLoad<LT, VEC>::load(grow, nullptr, vi, V, gf);
+            VecLoad<LT, VEC>::load(grow, lds_grow, vi, V, gf);
             double r[EPV];
             double s = 0.0;
 #pragma unroll
@@ -504,15 +517,39 @@ __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
 }
 
 // VERIFY_SELECTED: workgroup i evaluates verification select[i] and writes out_resample[i].
+// Few rows per launch, so each gets a workgroup of 1024 threads: the fp64 passes of a row are
+// latency-bound at one wavefront per SIMD.
+constexpr int SEL_NT = 1024;
 template <typename LT, bool VEC>
-__global__ __launch_bounds__(NT) void resample_selected(VerifyArgs a) {
+__global__ __launch_bounds__(SEL_NT) void resample_selected(VerifyArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int v = a.select[blockIdx.x];
     if (v < 0 || v >= a.N) {   // uniform per workgroup
         if (threadIdx.x == 0) a.out_resample[blockIdx.x] = v < 0 ? v : -2;
         return;
     }
-    exact_row<LT, VEC>(a, v, smem, nullptr, false, 0.f, 0.f);
+    const unsigned char* lds_t = nullptr;
+    const unsigned char* lds_g = nullptr;
+    if (VEC && a.stage_rows) {
+        // both rows into LDS once, all loads in flight together; the fp64 passes then read LDS
+        const int row_bytes = a.V * (int)sizeof(LT);          // a multiple of 8 (VEC: V % 4 == 0)
+        const size_t ex_bytes = (exact_lds_bytes(a.V, SEL_NT) + 15) & ~size_t(15);
+        unsigned char* st = smem + ex_bytes;
+        unsigned char* sg = st + ((row_bytes + 15) & ~15);
+        bool row_ok;
+        const int lrow = logit_row(a.row_index, a.R, v, &row_ok);
+        const uint2* tsrc = reinterpret_cast<const uint2*>(reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride);
+        const uint2* gsrc = reinterpret_cast<const uint2*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride);
+        const int n8 = row_bytes >> 3;
+        for (int i = threadIdx.x; i < n8; i += SEL_NT) {
+            reinterpret_cast<uint2*>(st)[i] = tsrc[i];
+            reinterpret_cast<uint2*>(sg)[i] = gsrc[i];
+        }
+        __syncthreads();
+        lds_t = st;
+        lds_g = sg;
+    }
+    exact_row<LT, VEC, SEL_NT>(a, v, smem, lds_t, false, 0.f, 0.f, lds_g);
 }
 
 // ---------------------------------------------------------------------------
@@ -570,17 +607,21 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
 }
 
 template <typename LT>
-static hipError_t launch_selected_typed(const VerifyArgs& a, hipStream_t stream) {
-    const size_t lds = exact_lds_bytes(a.V);
+static hipError_t launch_selected_typed(const VerifyArgs& a_in, hipStream_t stream) {
+    VerifyArgs a = a_in;
+    size_t lds = exact_lds_bytes(a.V, SEL_NT);
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
                             (uintptr_t)(a.stride * (int64_t)sizeof(LT));
     const bool vec = (align & 15) == 0 && (a.V % EXV) == 0;   // rows 16-byte aligned, whole vectors
+    const size_t staged = ((lds + 15) & ~size_t(15)) + 2 * (((size_t)a.V * sizeof(LT) + 15) & ~size_t(15));
+    a.stage_rows = (vec && staged <= 150 * 1024) ? 1 : 0;      // both rows beside the exact path's data
+    if (a.stage_rows) lds = staged;
     const hipError_t e = vec ? allow_lds(&resample_selected<LT, true>, lds) : allow_lds(&resample_selected<LT, false>, lds);
     if (e != hipSuccess) return e;
     if (vec)
-        hipLaunchKernelGGL((resample_selected<LT, true>), dim3(a.n_sel), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((resample_selected<LT, true>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a);
     else
-        hipLaunchKernelGGL((resample_selected<LT, false>), dim3(a.n_sel), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((resample_selected<LT, false>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a);
     return hipGetLastError();
 }
 

@@ -28,6 +28,7 @@ struct VerifyArgs {
     int mode;                 // VERIFY_FULL, VERIFY_DECIDE or VERIFY_SELECTED
     const int32_t* select;    // VERIFY_SELECTED: [n_sel] verification per workgroup (negative: passed through)
     int n_sel;
+    int stage_rows;           // VERIFY_SELECTED: both logit rows fit into LDS beside the exact path's data
     float delta;
     const float* uniforms;    // [N, 2]
     int32_t* out_accept;      // [N]

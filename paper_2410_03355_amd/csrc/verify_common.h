@@ -112,14 +112,18 @@ struct Lane<uint16_t> {  // bfloat16 storage
 
 // ---- fp64 workgroup helpers of the exact paths ----
 
+// Sized for workgroups of up to MAXW wavefronts: the helpers below take the number of
+// wavefronts of the calling workgroup as a template argument (NW unless stated).
+constexpr int MAXW = 16;
 struct ExactShared {
-    double red[NW];
-    double red2[NW];
+    double red[MAXW];
+    double red2[MAXW];
     double bcast[4];
-    int ired[NW];
+    int ired[MAXW];
     int ibcast[2];
 };
 
+template <int TNW = NW>
 __device__ __forceinline__ double block_sum(double v, double* red, int tid) {
     v = wave_sum(v);
     __syncthreads();
@@ -127,10 +131,11 @@ __device__ __forceinline__ double block_sum(double v, double* red, int tid) {
     __syncthreads();
     double s = 0.0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
+    for (int w = 0; w < TNW; ++w) s += red[w];
     return s;
 }
 
+template <int TNW = NW>
 __device__ __forceinline__ double block_max(double v, double* red, int tid) {
     v = wave_max(v);
     __syncthreads();
@@ -138,10 +143,11 @@ __device__ __forceinline__ double block_max(double v, double* red, int tid) {
     __syncthreads();
     double s = red[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) s = fmax(s, red[w]);
+    for (int w = 1; w < TNW; ++w) s = fmax(s, red[w]);
     return s;
 }
 
+template <int TNW = NW>
 __device__ __forceinline__ int block_min_i(int v, int* red, int tid) {
     v = wave_min(v);
     __syncthreads();
@@ -149,10 +155,11 @@ __device__ __forceinline__ int block_min_i(int v, int* red, int tid) {
     __syncthreads();
     int s = red[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) s = min(s, red[w]);
+    for (int w = 1; w < TNW; ++w) s = min(s, red[w]);
     return s;
 }
 
+template <int TNW = NW>
 __device__ __forceinline__ int block_or_i(int v, int* red, int tid) {
     v = wave_or(v);
     __syncthreads();
@@ -160,11 +167,12 @@ __device__ __forceinline__ int block_or_i(int v, int* red, int tid) {
     __syncthreads();
     int s = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s |= red[w];
+    for (int w = 0; w < TNW; ++w) s |= red[w];
     return s;
 }
 
 // Inclusive prefix sum over the workgroup in thread order; *total gets the sum.
+template <int TNW = NW>
 __device__ __forceinline__ double block_scan_incl(double v, double* red, int tid, double* total) {
     const double incl = wave_scan_incl(v);
     __syncthreads();
@@ -172,7 +180,7 @@ __device__ __forceinline__ double block_scan_incl(double v, double* red, int tid
     __syncthreads();
     double off = 0.0, tot = 0.0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < TNW; ++w) {
         const double x = red[w];
         if (w < (tid >> 6)) off += x;
         tot += x;
@@ -254,12 +262,12 @@ __device__ __forceinline__ double prefix_divergence64(int divergence, double t0,
 }
 
 // Nearest-first walk of the neighbourhood in fp64 (Algorithm 2, inference part), by the
-// whole workgroup: inclusive sums of t over the table slots, 256 slots at a time; the walk
+// whole workgroup (TNT threads): inclusive sums of t over the table slots, TNT slots at a time; the walk
 // ends at the first slot, other than the token itself, at which the divergence of the prefix
 // (a function of t_tok = t(xt) and of the inclusive sum) is not below delta.
 // *a_size: slots taken; *S: sum of t over the taken slots other than the token.
 // trow: the target row in global memory; lds_row: the same raw row in LDS, or null.
-template <typename LT>
+template <typename LT, int TNT = NT>
 __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* lds_row, const int32_t* nrow,
                                            int k, int xt, double mt, double zt, int divergence, double t_tok,
                                            double delta, ExactShared& sh, int tid, int* a_size, double* S) {
@@ -268,7 +276,7 @@ __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* 
     *a_size = k;
     *S = 0.0;
     bool cut_found = false;
-    for (int base = 0; base < k && !cut_found; base += NT) {
+    for (int base = 0; base < k && !cut_found; base += TNT) {
         const int j = base + tid;
         const bool valid = j < k;
         const int n = valid ? nrow[j] : xt;
@@ -276,9 +284,9 @@ __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* 
         const float ln = lds_row ? L::lds(lds_row, n) : L::glob(trow, n);
         const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
         double ctot;
-        const double incl = carry + block_scan_incl(tj, sh.red, tid, &ctot);
+        const double incl = carry + block_scan_incl<TNT / WAVE>(tj, sh.red, tid, &ctot);
         const int fail_j = (valid && !self && !(prefix_divergence64(divergence, t_tok, incl) < delta)) ? j : INT_MAX;
-        const int first = block_min_i(fail_j, sh.ired, tid);
+        const int first = block_min_i<TNT / WAVE>(fail_j, sh.ired, tid);
         if (first != INT_MAX) {
             cut_found = true;
             *a_size = first;
