@@ -44,9 +44,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent"])
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
-    ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree"],
+    ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree", "decide"],
                     help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only; "
-                         "tree: rows_per_step/60 random draft trees of 60 candidates, siblings sharing logit rows "
+                         "decide: lantern_decide_rows, the decisions without resampled tokens (rejections settle in "
+                         "the fp32 pass too); tree: rows_per_step/60 random draft trees of 60 candidates, siblings sharing logit rows "
                          "(lantern_verify_trees: decisions, walk, one residual draw per tree)")
     ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
                     help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
@@ -139,6 +140,12 @@ def main() -> int:
                                            out_acc[i % nbuf].data_ptr(), out_res[i % nbuf].data_ptr(), None,
                                            stream.cuda_stream)
             assert rc == 0, rc
+        elif args.mode == "decide":
+            rc = lib.lantern_decide_rows(b.target_logits.data_ptr(), b.draft_logits.data_ptr(), dcode, cfg.rows,
+                                         cfg.V, cfg.V, None, cfg.rows, b.draft_tokens.data_ptr(), knn.data_ptr(),
+                                         cfg.k, 1 if args.divergence == "jsd" else 0, float(delta),
+                                         b.uniforms.data_ptr(), out_acc[i % nbuf].data_ptr(), stream.cuda_stream)
+            assert rc == 0, rc
         elif args.divergence == "jsd":
             rc = lib.lantern_verify_divergence(b.target_logits.data_ptr(), b.draft_logits.data_ptr(), dcode,
                                                cfg.rows, cfg.V, cfg.V, b.draft_tokens.data_ptr(), knn.data_ptr(),
@@ -227,7 +234,7 @@ def main() -> int:
         "knn_build_ms": knn_build_ms,
     }
 
-    if not args.no_cpu_baseline and not greedy and not tree and args.divergence == "tvd":
+    if not args.no_cpu_baseline and args.mode == "sample" and args.divergence == "tvd":
         import numpy as np
         import oracle  # CPU baseline leg only
         threads = min(os.cpu_count() or 1, 16, oracle.max_threads())
