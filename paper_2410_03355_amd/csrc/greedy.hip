@@ -10,6 +10,7 @@
 // rows that do not clear it are re-evaluated in fp64 by the same workgroup.
 // One workgroup per row; the target row is streamed from HBM once.
 #include "fast_cut.h"
+#include "lds_limit.h"
 #include "verify_args.h"
 #include "verify_common.h"
 
@@ -346,20 +347,13 @@ __global__ __launch_bounds__(NT) void greedy_exact(GreedyArgs a) {
     greedy_exact_row<LT, false>(a, verification_of_block(blockIdx.x, a.N, a.row_index != nullptr), smem, nullptr);
 }
 
-template <typename K>
-static hipError_t allow_lds_g(K kernel, size_t lds) {
-    if (lds <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-}
-
 template <typename LT, int NV>
 static hipError_t launch_greedy_nv(const GreedyArgs& a, hipStream_t stream) {
     const size_t row_bytes = ((size_t)a.V * sizeof(LT) + 15) & ~size_t(15);
     const size_t tail = greedy_exact_lds_bytes(a.V) > GREEDY_SHARED_TAIL ? greedy_exact_lds_bytes(a.V) : GREEDY_SHARED_TAIL;
     const size_t lds = row_bytes + GREEDY_SHARED_HEAD + tail;
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    const hipError_t e = full ? allow_lds_g(&greedy_fast<LT, NV, true>, lds) : allow_lds_g(&greedy_fast<LT, NV, false>, lds);
+    const hipError_t e = full ? allow_lds(&greedy_fast<LT, NV, true>, lds) : allow_lds(&greedy_fast<LT, NV, false>, lds);
     if (e != hipSuccess) return e;
     if (full)
         hipLaunchKernelGGL((greedy_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
@@ -382,7 +376,7 @@ static hipError_t launch_greedy_typed(const GreedyArgs& a, hipStream_t stream) {
         if (nv <= 16) return launch_greedy_nv<LT, 16>(a, stream);
     }
     const size_t lds = greedy_exact_lds_bytes(a.V);
-    const hipError_t e = allow_lds_g(&greedy_exact<LT>, lds);
+    const hipError_t e = allow_lds(&greedy_exact<LT>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((greedy_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();

@@ -24,6 +24,7 @@
 #include <stdint.h>
 
 #include "fast_cut.h"
+#include "lds_limit.h"
 #include "verify_args.h"
 #include "verify_common.h"
 
@@ -555,13 +556,6 @@ __global__ __launch_bounds__(SEL_NT) void resample_selected(VerifyArgs a) {
 // ---------------------------------------------------------------------------
 // host-side launch
 // ---------------------------------------------------------------------------
-
-template <typename K>
-static hipError_t allow_lds(K kernel, size_t lds) {
-    if (lds <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-}
 
 // Dynamic LDS of verify_fast: raw row, the head of FastShared, then a region that holds either
 // the neighbour partial sums or the exact path's data.

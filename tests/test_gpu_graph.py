@@ -59,3 +59,55 @@ def test_capture_and_replay(oracle_mod, lantern_gpu):
                                                  threads=8)
         np.testing.assert_array_equal(gacc.cpu().numpy(), ga_o)
         np.testing.assert_array_equal(gtok.cpu().numpy(), gt_o)
+
+
+def test_capture_tree_step(oracle_mod, lantern_gpu):
+    """The fused tree step (three launches, the last with more than 64 KiB of LDS) in a graph."""
+    from parity_utils import random_trees, tree_step
+    cfg = workloads.CONFIGS["llamagen_step"]
+    B, M = 3, 60
+    rng = np.random.default_rng(77)
+    parent = random_trees(rng, B, M, max_children=4)
+    table = random_table(cfg.V, cfg.k, seed=5)
+    tb = torch.from_numpy(table).cuda()
+    par_d = torch.from_numpy(parent).cuda().reshape(-1)
+    steps = [tree_step(cfg, parent, step=s, variant=v) for s, v in ((1, "reject"), (2, "plain"), (3, "peaked"))]
+    R = B * (M + 1)
+    tl = torch.empty((R, cfg.V), dtype=torch.bfloat16, device="cuda")
+    dl = torch.empty_like(tl)
+    ri = torch.empty(B * M, dtype=torch.int32, device="cuda")
+    tok = torch.empty(B * M, dtype=torch.int32, device="cuda")
+    un = torch.empty((B * M, 2), dtype=torch.float32, device="cuda")
+
+    def load(step):
+        st, row_index, tokens, uniforms = step
+        tl.copy_(st.target_logits); dl.copy_(st.draft_logits)
+        ri.copy_(torch.from_numpy(row_index)); tok.copy_(torch.from_numpy(tokens)); un.copy_(uniforms)
+
+    delta = 0.05
+    load(steps[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm up outside the capture
+        lantern_gpu.verify_trees(tl, dl, ri, par_d, M, tok, tb, delta, un, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        acc, n, path, nxt = lantern_gpu.verify_trees(tl, dl, ri, par_d, M, tok, tb, delta, un,
+                                                     stream=torch.cuda.current_stream())
+
+    for step in (steps[1], steps[2], steps[0], steps[1]):
+        load(step)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        st, row_index, tokens, uniforms = step
+        acc_o, res_o, _ = oracle_mod.verify_rows(st.target_logits, st.draft_logits, row_index, tokens, table, cfg.k,
+                                                 delta, uniforms, threads=8)
+        n_o, path_o, next_o = oracle_mod.accept_trees(acc_o, res_o, parent, M)
+        np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
