@@ -27,6 +27,30 @@ def random_trees(rng: np.random.Generator, B: int, M: int, max_children: int = 4
     return parent
 
 
+def level_order(parent: np.ndarray) -> np.ndarray:
+    """The same trees with their nodes renumbered level by level, the children of a node next to
+    each other (the order in which a tree drafter that expands a level at a time lists its
+    candidates): parent int32 [B, M], still with parent[b, i] < i."""
+    B, M = parent.shape
+    out = np.empty_like(parent)
+    for b in range(B):
+        kids = {}
+        for i in range(M):
+            kids.setdefault(int(parent[b, i]), []).append(i)
+        order, new_parent = [], []
+        frontier = [(-1, -1)]                   # (old node, its new number)
+        while frontier:
+            nxt = []
+            for old, new in frontier:
+                for c in kids.get(old, []):
+                    order.append(c)
+                    new_parent.append(new)
+                    nxt.append((c, len(order) - 1))
+            frontier = nxt
+        out[b] = np.array(new_parent, dtype=np.int32)
+    return out
+
+
 def tree_step(cfg, parent: np.ndarray, step: int, variant: str = "plain", device="cpu"):
     """One verification step over B trees: a pair of logit rows per context (the prefix and every
     node: M + 1 rows per tree), row_index[i] = the row after node i's parent, and as draft token of

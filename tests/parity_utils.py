@@ -5,7 +5,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from synth.trees import random_trees, tree_step  # noqa: F401  (used by the tree tests)
+from synth.trees import level_order, random_trees, tree_step  # noqa: F401  (used by the tree tests)
 
 # tolerance on probabilities and acceptance ratios: 1e-5 relative for fp32
 # logits, 2e-3 for bf16 logits (decisions and indices are compared exactly)

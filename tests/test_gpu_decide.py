@@ -187,3 +187,77 @@ def test_argument_errors(lantern_gpu):
                                        knn.data_ptr(), 1, 0, 0.1, un.data_ptr(), tok.data_ptr(), -1, tok.data_ptr(),
                                        None)
     assert rc == -2
+
+
+# ---- runs: consecutive verifications that share a pair of logit rows are evaluated by one workgroup ----
+
+def _rows_all_modes(oracle, lantern, st, row_index, tokens, un, table, delta, divergence="tvd", threads=8):
+    k = table.shape[1]
+    acc_o, res_o, _ = oracle.verify_rows(st.target_logits, st.draft_logits, row_index, tokens, table, k, delta, un,
+                                         threads=threads, divergence=divergence)
+    dev = "cuda"
+    args = (st.target_logits.to(dev), st.draft_logits.to(dev), torch.from_numpy(row_index).to(dev),
+            torch.from_numpy(tokens).to(dev), torch.from_numpy(np.ascontiguousarray(table)).to(dev), delta,
+            un.to(dev))
+    acc, res = lantern.verify_rows(*args, divergence=divergence)
+    dacc = lantern.decide_rows(*args, divergence=divergence)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(res.cpu().numpy(), res_o)
+    np.testing.assert_array_equal(dacc.cpu().numpy(), acc_o)
+    return acc_o, res_o
+
+
+@pytest.mark.parametrize("variant,delta", [("plain", 0.4), ("reject", 0.0), ("peaked", 0.01)])
+def test_level_ordered_trees(oracle_mod, lantern_gpu, variant, delta):
+    """Siblings next to each other, as a drafter that expands a level at a time lists them."""
+    from parity_utils import level_order
+    cfg = workloads.CONFIGS["llamagen_step"]
+    rng = np.random.default_rng(31)
+    B, M = 5, 60
+    parent = level_order(random_trees(rng, B, M, max_children=6))
+    st, row_index, tokens, un = tree_step(cfg, parent, step=11, variant=variant)
+    assert (np.diff(row_index) == 0).sum() > B * M // 3          # many runs
+    table = sparse_table_from_oracle(oracle_mod, workloads.make_codebook(cfg).numpy(), cfg.k, tokens)
+    acc_o, res_o = _rows_all_modes(oracle_mod, lantern_gpu, st, row_index, tokens, un, table, delta)
+    n_o, path_o, next_o, _ = _expected_tree_outputs(oracle_mod, acc_o, res_o, parent, M)
+    dev = "cuda"
+    acc, n, path, nxt = lantern_gpu.verify_trees(st.target_logits.to(dev), st.draft_logits.to(dev),
+                                                 torch.from_numpy(row_index).to(dev),
+                                                 torch.from_numpy(parent).to(dev).reshape(-1), M,
+                                                 torch.from_numpy(tokens).to(dev), torch.from_numpy(table).to(dev),
+                                                 delta, un.to(dev))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+    np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+
+
+@pytest.mark.parametrize("cfg_name,divergence", [("tiny", "tvd"), ("tiny", "jsd"), ("llamagen_step", "tvd")])
+def test_long_and_odd_runs(oracle_mod, lantern_gpu, cfg_name, divergence):
+    """Runs longer than 64, runs across multiples of 64, runs of invalid indices, single members."""
+    cfg = workloads.CONFIGS[cfg_name]
+    R = 7
+    st = workloads.make_step(cfg, step=13, rows=R, variant="reject" if cfg_name == "tiny" else "plain")
+    rng = np.random.default_rng(5)
+    pieces = [np.full(150, 2), np.full(3, -1), np.array([0, 1, 0, 1]), np.full(70, 5), np.full(2, R), np.full(61, 6),
+              np.arange(R), np.full(5, R + 100), np.full(66, 3)]
+    row_index = np.concatenate(pieces).astype(np.int32)
+    N = len(row_index)
+    if cfg_name == "tiny":
+        tokens = rng.integers(0, cfg.V, N).astype(np.int32)
+        table = oracle_mod.build_knn(workloads.make_codebook(cfg).numpy(), cfg.k, threads=8)
+    else:
+        top = torch.topk(st.draft_logits.float(), 40, dim=1).indices.numpy()
+        safe = np.clip(row_index, 0, R - 1)
+        tokens = top[safe, rng.integers(0, 40, N)].astype(np.int32)
+        table = sparse_table_from_oracle(oracle_mod, workloads.make_codebook(cfg).numpy(), cfg.k, tokens)
+    tokens[20] = -3                                               # an unusable member inside a run
+    tokens[160] = cfg.V
+    un = torch.from_numpy(rng.random((N, 2)).astype(np.float32))
+    un[::2, 0] = 1.0 - 2.0 ** -24                                 # every other member is hard to accept
+    for delta in (0.0, cfg.delta):
+        acc_o, res_o = _rows_all_modes(oracle_mod, lantern_gpu, st, row_index, tokens, un, table, delta, divergence)
+        assert acc_o[20] == -1 and acc_o[150] == -1 and (acc_o == 1).any()
+        assert delta > 0 or (acc_o == 0).any()
