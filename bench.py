@@ -51,6 +51,9 @@ def main() -> int:
                          "(lantern_verify_trees: decisions, walk, one residual draw per tree)")
     ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
                     help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
+    ap.add_argument("--tree-order", default="level", choices=["level", "random"],
+                    help="tree mode: candidates listed level by level with siblings next to each other (as a "
+                         "drafter that expands one level at a time lists them), or in random drafting order")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="the CPU oracle is timed on whole steps of the workload until this much time has passed")
@@ -110,6 +113,8 @@ def main() -> int:
         B = cfg.rows // M
         rows_per_step = B * M
         parent_host = trees.random_trees(np.random.default_rng(workloads.BASE_SEED), B, M)
+        if args.tree_order == "level":
+            parent_host = trees.level_order(parent_host)
         parent = torch.from_numpy(parent_host).to(dev).reshape(-1)
         tbufs = []
         for s_ in range(nbuf):
@@ -213,7 +218,7 @@ def main() -> int:
             "rows_per_step": rows,
             "distinct_step_buffers": nbuf,
             "accepted_fraction": accept_frac,
-            **({"trees": B, "candidates_per_tree": M, "distinct_logit_rows": distinct_rows,
+            **({"trees": B, "candidates_per_tree": M, "tree_order": args.tree_order, "distinct_logit_rows": distinct_rows,
                 "mean_accepted_length": float(t_len.float().mean().item())} if tree else {}),
         },
         "roofline": {

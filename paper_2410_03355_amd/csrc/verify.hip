@@ -58,35 +58,8 @@ struct RowMeta {
     int nb[4];     // table slots 4*tid .. 4*tid+3
 };
 
-// Token of verification v, its table slots 4*tid .. 4*tid+3, acceptance draw, draft logit of the token.
-template <typename LT>
-__device__ __forceinline__ RowMeta load_meta(const VerifyArgs& a, int v, int xt, int lrow, bool nvec_ok) {
-    using L = Lane<LT>;
-    const int tid = threadIdx.x;
-    const int k = a.k;
-    RowMeta m;
-    m.xt = xt;
-    const int xs0 = ((unsigned)xt < (unsigned)a.V) ? xt : 0;
-    const int32_t* nrow = a.knn + (int64_t)xs0 * k;
-    const int j0 = tid * 4;
-    if (nvec_ok && j0 + 3 < k) {
-        const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
-        m.nb[0] = q.x; m.nb[1] = q.y; m.nb[2] = q.z; m.nb[3] = q.w;
-    } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) m.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
-    }
-    m.u_acc = a.uniforms[2 * (int64_t)v];
-    m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
-    return m;
-}
-
 // fp32 path, one workgroup per row.
 // FULL: the row fills all NV vector slots of every thread (no bounds checks).
-// RUNS: the launch has an index array.  Consecutive verifications with the same index (the
-// siblings of a draft tree, listed together) form a run: the workgroup of the first one streams
-// the pair of rows once and then walks the neighbourhood of every member, the workgroups of the
-// others exit at once.
 //
 // Exponentials are taken as 2^(l*log2e - c) with one reference c per row, common to all
 // terms of that row, so its own rounding cancels in every comparison.  The reference is
@@ -94,7 +67,7 @@ __device__ __forceinline__ RowMeta load_meta(const VerifyArgs& a, int v, int xt,
 // rather than the row maximum: any element of the row works, because the sum then holds
 // a term equal to one (Z >= 1) and every term is at most Z; rows whose sum exceeds 2^46
 // (an element more than 32 above the reference) are left to the exact path.
-template <typename LT, int NV, bool FULL, bool RUNS>
+template <typename LT, int NV, bool FULL>
 __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
@@ -114,12 +87,6 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
     const int row = verification_of_block(blockIdx.x, a.N, a.row_index != nullptr);
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
-    int mine = 0;
-    if (RUNS) {
-        mine = a.row_index[row];
-        // a member of the run that started earlier (runs are cut at multiples of 64 verifications)
-        if ((row & 63) != 0 && a.row_index[row - 1] == mine) return;
-    }
 
     // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
     uint4 T[NV], G[NV];
@@ -138,15 +105,29 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             }
         }
     }
-    RowMeta m = load_meta<LT>(a, row, a.tokens[row], lrow, nvec_ok);
-    // length of the run and the token of its second member
-    int run = 1, xt_next = 0;
-    if (RUNS) {
-        while (row + run < a.N && ((row + run) & 63) != 0 && a.row_index[row + run] == mine) ++run;
-        if (run > 1) xt_next = a.tokens[row + 1];
+    // token, its table slots 4*tid .. 4*tid+3, acceptance draw, draft logit of the token
+    RowMeta m;
+    {
+        m.xt = a.tokens[row];
+        const int xs0 = ((unsigned)m.xt < (unsigned)V) ? m.xt : 0;
+        const int32_t* nrow = a.knn + (int64_t)xs0 * k;
+        const int j0 = tid * 4;
+        if (nvec_ok && j0 + 3 < k) {
+            const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
+            m.nb[0] = q.x; m.nb[1] = q.y; m.nb[2] = q.z; m.nb[3] = q.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) m.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
+        }
+        m.u_acc = a.uniforms[2 * (int64_t)row];
+        m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
     }
 
     {
+        const int xt = m.xt;
+        const bool tok_ok = (unsigned)xt < (unsigned)V;
+        const int xs = tok_ok ? xt : 0;
+
         // ---- raw target row to LDS; reference = maximum over vector slot 0 of every thread ----
 #pragma unroll
         for (int c = 0; c < NV; ++c) {
@@ -199,86 +180,55 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
         st = wave_sum(st);
         sg = wave_sum(sg);
 
-        if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; }
+        // ---- neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront ----
         const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
+        scan_publish<LT>(m.nb, xt, k, V, s_row, ct, scan);
+        if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; }
+        __syncthreads();  // sums and neighbour partial sums are published
 
-        // ---- one verification after the other of the run (a single one without an index array);
-        //      those the fp32 pass does not settle are noted and evaluated in fp64 afterwards ----
-        unsigned long long pending = 0;   // bit j: member row + j is not settled
-        for (int v = row;;) {
-            const int xt = m.xt;
-            const bool tok_ok = (unsigned)xt < (unsigned)V;
-            const int xs = tok_ok ? xt : 0;
-
-            // neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront
-            scan_publish<LT>(m.nb, xt, k, V, s_row, ct, scan);
-            // the next member's table slots and scalars travel while this one is decided
-            const bool has_next = RUNS && (v + 1 < row + run);
-            RowMeta m_next;
-            int xt_next2 = 0;
-            if (has_next) {
-                m_next = load_meta<LT>(a, v + 1, xt_next, lrow, nvec_ok);
-                if (v + 2 < row + run) xt_next2 = a.tokens[v + 2];
-            }
-            __syncthreads();  // sums and neighbour partial sums are published
-
-            // ---- wavefront 0: cut, mass, acceptance ----
-            if (wave == 0) {
-                float Zt = 0.f, Zg = 0.f;
+        // ---- wavefront 0: cut, mass, acceptance ----
+        if (wave == 0) {
+            float Zt = 0.f, Zg = 0.f;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    Zt += sh.wsum_t[w];
-                    Zg += sh.wsum_g[w];
-                }
-                const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
-                const CutResult cut = scan_cut<LT>(Zt, a.divergence, a.delta, e_tx, xt, xs, k, V, a.knn, s_row, ct, scan);
-                const int bad = cut.bad | ((tok_ok && row_ok) ? 0 : 1);
-                const bool cut_definite = cut.definite;
-                const int a_size = cut.a_size;
-                const float S = cut.S;
-                const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
-                const float MA = e_tx + S;                // mass * Zt
-                const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
-                const float rhs = MA * Zg;                // mass  * Zt * Zg
-                const bool accept = (lhs + ACC_SLACK) < rhs * (1.f - TAU_ACC);
-                // a definite rejection settles the row only when no resampled token is asked for
-                const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + ACC_SLACK);
-                // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
-                const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
-                const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
-                if (lane == 0) {
-                    if (settled) {
-                        a.out_accept[v] = accept ? 1 : 0;
-                        if (a.mode == VERIFY_FULL) a.out_resample[v] = -1;
-                        const float mass = MA / Zt;
-                        const float gx = e_gx / Zg;
-                        if (a.out_prob) a.out_prob[v] = fminf(1.f, mass / gx);
-                        if (a.out_mass) a.out_mass[v] = mass;
-                        if (a.out_gtok) a.out_gtok[v] = gx;
-                        if (a.out_asize) a.out_asize[v] = a_size;
-                        if (a.out_path) a.out_path[v] = 0;
-                    }
-                    sh.settled = settled ? 1 : 0;
-                }
+            for (int w = 0; w < NW; ++w) {
+                Zt += sh.wsum_t[w];
+                Zg += sh.wsum_g[w];
             }
-            __syncthreads();  // the decision is published; wavefront 0 is done with the LDS row
-            if (!sh.settled) pending |= 1ull << (v - row);
-            if (!has_next) break;
-            __syncthreads();  // everyone has read the decision
-            m = m_next;
-            xt_next = xt_next2;
-            ++v;
+            const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
+            const CutResult cut = scan_cut<LT>(Zt, a.divergence, a.delta, e_tx, xt, xs, k, V, a.knn, s_row, ct, scan);
+            const int bad = cut.bad | ((tok_ok && row_ok) ? 0 : 1);
+            const bool cut_definite = cut.definite;
+            const int a_size = cut.a_size;
+            const float S = cut.S;
+            const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
+            const float MA = e_tx + S;                // mass * Zt
+            const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
+            const float rhs = MA * Zg;                // mass  * Zt * Zg
+            const bool accept = (lhs + ACC_SLACK) < rhs * (1.f - TAU_ACC);
+            // a definite rejection settles the row only when no resampled token is asked for
+            const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + ACC_SLACK);
+            // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
+            const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
+            const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
+            if (lane == 0) {
+                if (settled) {
+                    a.out_accept[row] = accept ? 1 : 0;
+                    if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
+                    const float mass = MA / Zt;
+                    const float gx = e_gx / Zg;
+                    if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
+                    if (a.out_mass) a.out_mass[row] = mass;
+                    if (a.out_gtok) a.out_gtok[row] = gx;
+                    if (a.out_asize) a.out_asize[row] = a_size;
+                    if (a.out_path) a.out_path[row] = 0;
+                }
+                sh.settled = settled ? 1 : 0;
+            }
         }
-        // the fp64 path reuses the LDS of the scan; the raw target row stays in LDS
-        if (!RUNS) {
-            if (pending) exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
-        } else {
-            while (pending) {
-                const int j = __ffsll((long long)pending) - 1;
-                pending &= pending - 1;
-                exact_row<LT, true>(a, row + j, ex_lds, s_row, false, 0.f, 0.f);
-                __syncthreads();
-            }
+        __syncthreads();  // the decision is published; wavefront 0 is done with the LDS row
+        if (!sh.settled) {
+            // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
+            exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
         }
     }
 }
@@ -620,12 +570,12 @@ template <typename LT, int NV>
 static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
     const size_t lds = fast_lds_bytes<LT>(a.V);
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    void (*kernel)(VerifyArgs) =
-        a.row_index ? (full ? &verify_fast<LT, NV, true, true> : &verify_fast<LT, NV, false, true>)
-                    : (full ? &verify_fast<LT, NV, true, false> : &verify_fast<LT, NV, false, false>);
-    const hipError_t e = allow_lds(kernel, lds);
+    const hipError_t e = full ? allow_lds(&verify_fast<LT, NV, true>, lds) : allow_lds(&verify_fast<LT, NV, false>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kernel, dim3(a.N), dim3(NT), lds, stream, a);
+    if (full)
+        hipLaunchKernelGGL((verify_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
+    else
+        hipLaunchKernelGGL((verify_fast<LT, NV, false>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
 }
 

@@ -189,7 +189,7 @@ def test_argument_errors(lantern_gpu):
     assert rc == -2
 
 
-# ---- runs: consecutive verifications that share a pair of logit rows are evaluated by one workgroup ----
+# ---- runs of consecutive verifications that share a pair of logit rows (siblings listed together) ----
 
 def _rows_all_modes(oracle, lantern, st, row_index, tokens, un, table, delta, divergence="tvd", threads=8):
     k = table.shape[1]
