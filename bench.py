@@ -149,7 +149,7 @@ def main() -> int:
             rc = lib.lantern_decide_rows(b.target_logits.data_ptr(), b.draft_logits.data_ptr(), dcode, cfg.rows,
                                          cfg.V, cfg.V, None, cfg.rows, b.draft_tokens.data_ptr(), knn.data_ptr(),
                                          cfg.k, 1 if args.divergence == "jsd" else 0, float(delta),
-                                         b.uniforms.data_ptr(), out_acc[i % nbuf].data_ptr(), stream.cuda_stream)
+                                         b.uniforms.data_ptr(), out_acc[i % nbuf].data_ptr(), None, stream.cuda_stream)
             assert rc == 0, rc
         elif args.divergence == "jsd":
             rc = lib.lantern_verify_divergence(b.target_logits.data_ptr(), b.draft_logits.data_ptr(), dcode,

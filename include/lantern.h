@@ -299,6 +299,7 @@ int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const i
  *   row_index  may be NULL when R == N: verification i reads row i
  *   out_accept [N] int32: 1, 0, or -1 for an unusable verification; equal to
  *              what lantern_verify_rows writes
+ *   out_path   [N] int32 or NULL: 0 settled by the fp32 pass, 1 evaluated in fp64
  *
  * lantern_resample_selected: for i < n_sel, the resampled token of
  * verification select[i], from the same inputs.
@@ -315,7 +316,7 @@ int lantern_accept_trees(const int32_t* accept, const int32_t* resample, const i
 int lantern_decide_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
                         int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
                         const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
-                        const float* uniforms, int32_t* out_accept, void* hip_stream);
+                        const float* uniforms, int32_t* out_accept, int32_t* out_path, void* hip_stream);
 
 int lantern_resample_selected(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
                               int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,

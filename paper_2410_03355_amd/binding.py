@@ -73,7 +73,7 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_greedy_rows.restype = i32
     lib.lantern_accept_trees.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.lantern_accept_trees.restype = i32
-    lib.lantern_decide_rows.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp, vp]
+    lib.lantern_decide_rows.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp, vp, vp]
     lib.lantern_decide_rows.restype = i32
     lib.lantern_resample_selected.argtypes = [vp, vp, i32, i32, i32, i64, vp, i32, vp, vp, i32, i32, f32, vp, vp,
                                               i32, vp, vp]
@@ -388,19 +388,21 @@ def _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, unifor
 
 
 def decide_rows(target_logits, draft_logits, row_index, draft_tokens, knn, delta: float, uniforms,
-                divergence: str = "tvd", stream=None):
-    """lantern_decide_rows; returns accept int32[N] (device)."""
+                divergence: str = "tvd", stream=None, want_path: bool = False):
+    """lantern_decide_rows; returns accept int32[N] (device), and the per-row path tensor when want_path."""
     lib = load()
     R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
     acc = torch.empty(N, dtype=torch.int32, device=target_logits.device)
+    path = torch.empty(N, dtype=torch.int32, device=target_logits.device) if want_path else None
     rc = lib.lantern_decide_rows(target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits),
                                  R, V, stride, None if row_index is None else row_index.data_ptr(), N,
                                  draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
                                  {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta),
-                                 uniforms.data_ptr(), acc.data_ptr(), _stream_ptr(stream))
+                                 uniforms.data_ptr(), acc.data_ptr(),
+                                 path.data_ptr() if want_path else None, _stream_ptr(stream))
     if rc != OK:
         raise LanternError(rc, "lantern_decide_rows")
-    return acc
+    return (acc, path) if want_path else acc
 
 
 def resample_selected(target_logits, draft_logits, row_index, draft_tokens, knn, delta: float, uniforms,

@@ -112,11 +112,11 @@ int lantern_verify_rows(const void* target_logits, const void* draft_logits, lan
 int lantern_decide_rows(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
                         int R, int V, int64_t row_stride_elems, const int32_t* row_index, int N,
                         const int32_t* draft_tokens, const int32_t* knn, int k, int divergence, float delta,
-                        const float* uniforms, int32_t* out_accept, void* hip_stream) {
+                        const float* uniforms, int32_t* out_accept, int32_t* out_path, void* hip_stream) {
     if (!row_index && R != N) return LANTERN_E_SHAPE;   // without an index array row i belongs to verification i
     return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
                        draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr, nullptr,
-                       nullptr, nullptr, nullptr, nullptr, hip_stream, lantern::VERIFY_DECIDE);
+                       nullptr, nullptr, nullptr, out_path, hip_stream, lantern::VERIFY_DECIDE);
 }
 
 int lantern_resample_selected(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
@@ -262,7 +262,7 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
     // decisions of all candidates, the walk (which leaves in out_next the verification to resample
     // or a negative code), then the residual draw of that one verification per tree, in place
     int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index, N,
-                                 draft_tokens, knn, k, divergence, delta, uniforms, out_accept, hip_stream);
+                                 draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr, hip_stream);
     if (rc != LANTERN_OK || B == 0) return rc;
     rc = lantern_accept_trees(out_accept, nullptr, parent, B, M, out_len, out_path, out_next, hip_stream);
     if (rc != LANTERN_OK) return rc;

@@ -69,6 +69,13 @@ def test_stress_reject_mix_full_step(oracle_mod, lantern_gpu):
     acc, res = _decide_and_select(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits,
                                   st.draft_tokens.numpy(), table, 0.0, st.uniforms, threads=16)
     assert (acc == 0).mean() > 0.3
+    # the rejections are settled by the fp32 pass, not handed to the fp64 path
+    acc2, path = lantern_gpu.decide_rows(st.target_logits.cuda(), st.draft_logits.cuda(), None,
+                                         st.draft_tokens.cuda(), torch.from_numpy(table).cuda(), 0.0,
+                                         st.uniforms.cuda(), want_path=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc2.cpu().numpy(), acc)
+    assert (path.cpu().numpy() == 0).mean() > 0.99
 
 
 def test_wide_latent_fp32_and_unusable_rows(oracle_mod, lantern_gpu):
@@ -178,7 +185,7 @@ def test_argument_errors(lantern_gpu):
     un = torch.zeros((3, 2), device="cuda")
     # no row_index although R != N
     rc = lib.lantern_decide_rows(t.data_ptr(), t.data_ptr(), 0, 2, 16, 16, None, 3, tok.data_ptr(), knn.data_ptr(), 1,
-                                 0, 0.1, un.data_ptr(), tok.data_ptr(), None)
+                                 0, 0.1, un.data_ptr(), tok.data_ptr(), None, None)
     assert rc == -2
     rc = lib.lantern_resample_selected(t.data_ptr(), t.data_ptr(), 0, 3, 16, 16, None, 3, tok.data_ptr(),
                                        knn.data_ptr(), 1, 0, 0.1, un.data_ptr(), None, 2, tok.data_ptr(), None)
