@@ -268,3 +268,25 @@ def test_long_and_odd_runs(oracle_mod, lantern_gpu, cfg_name, divergence):
         acc_o, res_o = _rows_all_modes(oracle_mod, lantern_gpu, st, row_index, tokens, un, table, delta, divergence)
         assert acc_o[20] == -1 and acc_o[150] == -1 and (acc_o == 1).any()
         assert delta > 0 or (acc_o == 0).any()
+
+
+def test_empty_inputs(lantern_gpu):
+    """N = 0, n_sel = 0 and B = 0 launch nothing and report success."""
+    dev = "cuda"
+    t = torch.zeros((0, 16), device=dev)
+    knn = torch.arange(16, dtype=torch.int32, device=dev).reshape(16, 1)
+    none_i = torch.zeros(0, dtype=torch.int32, device=dev)
+    none_u = torch.zeros((0, 2), device=dev)
+    assert lantern_gpu.decide_rows(t, t, None, none_i, knn, 0.1, none_u).numel() == 0
+    assert lantern_gpu.verify_rows(t, t, none_i, none_i, knn, 0.1, none_u)[0].numel() == 0
+    assert lantern_gpu.verify_greedy_rows(t, none_i, none_i, knn, 0.1)[0].numel() == 0
+    acc, n, path, nxt = lantern_gpu.verify_trees(t, t, none_i, none_i, 5, none_i, knn, 0.1, none_u)
+    assert acc.numel() == 0 and n.numel() == 0 and path.numel() == 0 and nxt.numel() == 0
+    n, path, nxt = lantern_gpu.accept_trees(none_i, none_i, none_i, 7)
+    assert n.numel() == 0
+    # nothing selected, with verifications present
+    t3 = torch.zeros((3, 16), device=dev)
+    tok = torch.zeros(3, dtype=torch.int32, device=dev)
+    un = torch.zeros((3, 2), device=dev)
+    assert lantern_gpu.resample_selected(t3, t3, None, tok, knn, 0.1, un, none_i).numel() == 0
+    torch.cuda.synchronize()
