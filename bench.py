@@ -65,8 +65,9 @@ def main() -> int:
                     help="HBM bytes per launch from rocprofv3 counters, if known")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for "
-              "how the path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (verifications are independent, so more GPUs "
+              "would each take a share of the rows with the table replicated); run with --gpus 1",
+              file=sys.stderr)
         return 2
 
     import torch
