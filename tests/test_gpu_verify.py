@@ -217,3 +217,36 @@ def test_side_stream(oracle_mod, lantern_gpu):
     s.synchronize()
     np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
     np.testing.assert_array_equal(res.cpu().numpy(), res_o)
+
+
+def test_maximum_vocabulary(oracle_mod, lantern_gpu):
+    """V = LANTERN_MAX_VOCAB (2^19), the largest row the library takes, in both logit types; all
+    entry points of the sampling path and the greedy one."""
+    V = lantern_gpu.MAX_VOCAB
+    N, k = 3, 40
+    rng = np.random.default_rng(19)
+    base = (rng.standard_normal((N, V)) * 2.0).astype(np.float32)
+    tokens = rng.integers(0, V, N).astype(np.int32)
+    tokens[0] = V - 1                                            # the last token of the vocabulary
+    table = np.empty((V, k), dtype=np.int32)
+    table[:, 0] = np.arange(V)
+    table[:, 1:] = (np.arange(V)[:, None] + rng.integers(1, V, k - 1)[None, :]) % V   # distinct shifts, never 0
+    un = torch.from_numpy(rng.random((N, 2)).astype(np.float32))
+    un[1, 0] = 1.0 - 2.0 ** -24                                  # a rejection: the residual over 2^19 tokens
+    for dtype in (torch.float32, torch.bfloat16):
+        t = torch.from_numpy(base).to(dtype)
+        gl = base + rng.standard_normal((N, V)).astype(np.float32)
+        gl[1, tokens[1]] = 14.0                                  # the drafter is far too sure of this token
+        g = torch.from_numpy(gl).to(dtype)
+        acc, res, diag, gout = compare_verify(oracle_mod, lantern_gpu, t, g, torch.from_numpy(tokens), table, 0.05,
+                                              un, label=f"max vocabulary {dtype}")
+        assert (acc == 0).any()
+        dacc = lantern_gpu.decide_rows(t.cuda(), g.cuda(), None, torch.from_numpy(tokens).cuda(),
+                                       torch.from_numpy(table).cuda(), 0.05, un.cuda())
+        np.testing.assert_array_equal(dacc.cpu().numpy(), acc)
+        ga_o, gt_o, _ = oracle_mod.verify_greedy(t, tokens, table, k, 0.05)
+        ga, gt = lantern_gpu.verify_greedy(t.cuda(), torch.from_numpy(tokens).cuda(), torch.from_numpy(table).cuda(),
+                                           0.05)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(ga.cpu().numpy(), ga_o)
+        np.testing.assert_array_equal(gt.cpu().numpy(), gt_o)
