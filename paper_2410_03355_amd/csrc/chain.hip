@@ -3,6 +3,7 @@
 // is not accepted ends the chain with its resampled token.
 // Integer work on the outputs of lantern_verify; one wavefront per chain (or tree).
 #include <hip/hip_runtime.h>
+#include <limits.h>
 #include <stdint.h>
 
 #include "device_utils.h"
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(NT) void accept_chains_kernel(const int32_t* accept
 // One wavefront per tree; every step scans the nodes after the current one, 64 at a time.
 // Without resampled tokens (resample null) the walk reports, in place of the token, which
 // verification (tree * M + node) has to be resampled.
+constexpr int CACHED = 4;   // nodes per lane that the walk keeps in registers: trees of up to 256 nodes
 __global__ __launch_bounds__(NT) void accept_trees_kernel(const int32_t* accept, const int32_t* resample,
                                                           const int32_t* parent, int B, int M, int32_t* out_len,
                                                           int32_t* out_path, int32_t* out_next) {
@@ -59,6 +61,42 @@ __global__ __launch_bounds__(NT) void accept_trees_kernel(const int32_t* accept,
     int cur = -1, len = 0, next = -1;
     if (malformed) {
         next = -3;
+    } else if (M <= CACHED * WAVE) {
+        // small trees (the usual case): every lane keeps its nodes' parent and decision in registers,
+        // node i in slot i / 64 of lane i % 64, so a step of the walk touches no memory
+        int cp[CACHED], ca[CACHED];
+#pragma unroll
+        for (int q = 0; q < CACHED; ++q) {
+            const int i = q * WAVE + lane;
+            cp[q] = i < M ? par[i] : INT_MIN;
+            ca[q] = i < M ? acc[i] : 0;
+        }
+        for (;;) {            // cur grows with every step: at most M steps
+            int first_child = -1, decisive = -1, decisive_acc = 0;
+#pragma unroll
+            for (int q = 0; q < CACHED; ++q) {
+                if (decisive >= 0) continue;
+                const bool child = cp[q] == cur;
+                const unsigned long long cm = __ballot(child);
+                const unsigned long long dm = __ballot(child && ca[q] != 0);
+                if (first_child < 0 && cm) first_child = q * WAVE + __ffsll((long long)cm) - 1;
+                if (dm) {
+                    const int l = __ffsll((long long)dm) - 1;
+                    decisive = q * WAVE + l;
+                    decisive_acc = __builtin_amdgcn_readlane(ca[q], l);
+                }
+            }
+            if (decisive >= 0 && decisive_acc == 1) {
+                if (lane == 0) path[len] = decisive;
+                ++len;
+                cur = decisive;
+                continue;
+            }
+            if (decisive >= 0) next = -2;
+            else if (first_child >= 0) next = resample ? res[first_child] : tree * M + first_child;
+            else next = -1;
+            break;
+        }
     } else {
         for (;;) {            // cur grows with every step: at most M steps
             int first_child = -1, decisive = -1;
