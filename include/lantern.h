@@ -330,7 +330,8 @@ int lantern_resample_selected(const void* target_logits, const void* draft_logit
  * candidates, the walk, and the residual draw of the one candidate per tree
  * whose token is needed.  Same results as lantern_verify_rows followed by
  * lantern_accept_trees, without the resampling work that the walk never
- * looks at.
+ * looks at.  Two launches: the decisions; then one workgroup per tree walks
+ * it and draws the residual.
  *
  *   row_index, draft_tokens, uniforms, parent  [B*M], candidate i of tree b at b*M + i
  *   out_accept [B*M], out_len [B], out_path [B*M], out_next [B]  as in

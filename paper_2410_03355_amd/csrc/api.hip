@@ -259,16 +259,40 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
     if (B < 0 || M < 1 || (int64_t)B * M > INT_MAX) return LANTERN_E_SHAPE;
     const int N = B * M;
     if (B > 0 && (!row_index || !parent || !out_len || !out_path || !out_next)) return LANTERN_E_NULL;
-    // decisions of all candidates, the walk (which leaves in out_next the verification to resample
-    // or a negative code), then the residual draw of that one verification per tree, in place
-    int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index, N,
-                                 draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr, hip_stream);
+    // decisions of all candidates; then, one workgroup per tree, the walk and the residual draw of the
+    // one candidate it asks for
+    const int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index,
+                                       N, draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr,
+                                       hip_stream);
     if (rc != LANTERN_OK || B == 0) return rc;
-    rc = lantern_accept_trees(out_accept, nullptr, parent, B, M, out_len, out_path, out_next, hip_stream);
-    if (rc != LANTERN_OK) return rc;
-    return lantern_resample_selected(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index,
-                                     N, draft_tokens, knn, k, divergence, delta, uniforms, out_next, B, out_next,
-                                     hip_stream);
+    lantern::VerifyArgs a;
+    a.target = target_logits;
+    a.draft = draft_logits;
+    a.N = N;
+    a.R = R;
+    a.row_index = row_index;
+    a.V = V;
+    a.stride = row_stride_elems;
+    a.tokens = draft_tokens;
+    a.knn = knn;
+    a.k = k;
+    a.divergence = divergence;
+    a.mode = lantern::VERIFY_SELECTED;
+    a.select = nullptr;
+    a.n_sel = B;
+    a.stage_rows = 0;
+    a.delta = delta;
+    a.uniforms = uniforms;
+    a.out_accept = out_accept;
+    a.out_resample = out_next;
+    a.out_prob = nullptr;
+    a.out_mass = nullptr;
+    a.out_gtok = nullptr;
+    a.out_asize = nullptr;
+    a.out_path = nullptr;
+    const hipError_t e = lantern::launch_tree_finish(a, parent, M, out_len, out_path, (int)logits_dtype,
+                                                     static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
 const char* lantern_status_string(int status) {

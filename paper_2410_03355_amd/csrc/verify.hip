@@ -25,6 +25,7 @@
 
 #include "fast_cut.h"
 #include "lds_limit.h"
+#include "tree_walk.h"
 #include "verify_args.h"
 #include "verify_common.h"
 
@@ -521,18 +522,14 @@ __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
 // Few rows per launch, so each gets a workgroup of 1024 threads: the fp64 passes of a row are
 // latency-bound at one wavefront per SIMD.
 constexpr int SEL_NT = 1024;
+// Evaluates verification v in fp64 with the 1024 threads of this workgroup (VERIFY_SELECTED: only
+// out_resample[blockIdx.x] is written).  When they fit, both logit rows are first copied into LDS,
+// all loads in flight together, so the fp64 passes read LDS.
 template <typename LT, bool VEC>
-__global__ __launch_bounds__(SEL_NT) void resample_selected(VerifyArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int v = a.select[blockIdx.x];
-    if (v < 0 || v >= a.N) {   // uniform per workgroup
-        if (threadIdx.x == 0) a.out_resample[blockIdx.x] = v < 0 ? v : -2;
-        return;
-    }
+__device__ __forceinline__ void selected_row(const VerifyArgs& a, int v, unsigned char* smem) {
     const unsigned char* lds_t = nullptr;
     const unsigned char* lds_g = nullptr;
     if (VEC && a.stage_rows) {
-        // both rows into LDS once, all loads in flight together; the fp64 passes then read LDS
         const int row_bytes = a.V * (int)sizeof(LT);          // a multiple of 8 (VEC: V % 4 == 0)
         const size_t ex_bytes = (exact_lds_bytes(a.V, SEL_NT) + 15) & ~size_t(15);
         unsigned char* st = smem + ex_bytes;
@@ -551,6 +548,47 @@ __global__ __launch_bounds__(SEL_NT) void resample_selected(VerifyArgs a) {
         lds_g = sg;
     }
     exact_row<LT, VEC, SEL_NT>(a, v, smem, lds_t, false, 0.f, 0.f, lds_g);
+}
+
+// VERIFY_SELECTED: workgroup i evaluates verification select[i] and writes out_resample[i].
+template <typename LT, bool VEC>
+__global__ __launch_bounds__(SEL_NT) void resample_selected(VerifyArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int v = a.select[blockIdx.x];
+    if (v < 0 || v >= a.N) {   // uniform per workgroup
+        if (threadIdx.x == 0) a.out_resample[blockIdx.x] = v < 0 ? v : -2;
+        return;
+    }
+    selected_row<LT, VEC>(a, v, smem);
+}
+
+// Second half of a tree step: workgroup b walks tree b over the decisions in a.out_accept (its
+// first wavefront), then draws the one residual the walk asks for and writes a.out_resample[b].
+template <typename LT, bool VEC>
+__global__ __launch_bounds__(SEL_NT) void tree_finish(VerifyArgs a, const int32_t* parent, int M, int32_t* out_len,
+                                                      int32_t* out_path) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tree = blockIdx.x;
+    int32_t* path = out_path + (int64_t)tree * M;
+    int* bcast = reinterpret_cast<int*>(smem);
+    if (threadIdx.x < WAVE) {
+        int len;
+        const int next = walk_tree(a.out_accept + (int64_t)tree * M, nullptr, parent + (int64_t)tree * M, M, tree,
+                                   path, &len);
+        for (int j = len + threadIdx.x; j < M; j += WAVE) path[j] = -1;
+        if (threadIdx.x == 0) {
+            out_len[tree] = len;
+            bcast[0] = next;
+        }
+    }
+    __syncthreads();
+    const int v = bcast[0];
+    __syncthreads();              // the exact path reuses this LDS
+    if (v < 0) {                  // uniform per workgroup: nothing to resample
+        if (threadIdx.x == 0) a.out_resample[tree] = v;
+        return;
+    }
+    selected_row<LT, VEC>(a, v, smem);
 }
 
 // ---------------------------------------------------------------------------
@@ -601,7 +639,8 @@ static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
 }
 
 template <typename LT>
-static hipError_t launch_selected_typed(const VerifyArgs& a_in, hipStream_t stream) {
+static hipError_t launch_selected_typed(const VerifyArgs& a_in, const int32_t* parent, int M, int32_t* out_len,
+                                        int32_t* out_path, hipStream_t stream) {
     VerifyArgs a = a_in;
     size_t lds = exact_lds_bytes(a.V, SEL_NT);
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
@@ -610,6 +649,17 @@ static hipError_t launch_selected_typed(const VerifyArgs& a_in, hipStream_t stre
     const size_t staged = ((lds + 15) & ~size_t(15)) + 2 * (((size_t)a.V * sizeof(LT) + 15) & ~size_t(15));
     a.stage_rows = (vec && staged <= 150 * 1024) ? 1 : 0;      // both rows beside the exact path's data
     if (a.stage_rows) lds = staged;
+    if (parent) {   // walk and draw in one launch, one workgroup per tree
+        const hipError_t e = vec ? allow_lds(&tree_finish<LT, true>, lds) : allow_lds(&tree_finish<LT, false>, lds);
+        if (e != hipSuccess) return e;
+        if (vec)
+            hipLaunchKernelGGL((tree_finish<LT, true>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a, parent, M, out_len,
+                               out_path);
+        else
+            hipLaunchKernelGGL((tree_finish<LT, false>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a, parent, M, out_len,
+                               out_path);
+        return hipGetLastError();
+    }
     const hipError_t e = vec ? allow_lds(&resample_selected<LT, true>, lds) : allow_lds(&resample_selected<LT, false>, lds);
     if (e != hipSuccess) return e;
     if (vec)
@@ -620,8 +670,14 @@ static hipError_t launch_selected_typed(const VerifyArgs& a_in, hipStream_t stre
 }
 
 hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {
-    if (logits_dtype == 0) return launch_selected_typed<float>(a, stream);
-    return launch_selected_typed<uint16_t>(a, stream);
+    if (logits_dtype == 0) return launch_selected_typed<float>(a, nullptr, 0, nullptr, nullptr, stream);
+    return launch_selected_typed<uint16_t>(a, nullptr, 0, nullptr, nullptr, stream);
+}
+
+hipError_t launch_tree_finish(const VerifyArgs& a, const int32_t* parent, int M, int32_t* out_len, int32_t* out_path,
+                              int logits_dtype, hipStream_t stream) {
+    if (logits_dtype == 0) return launch_selected_typed<float>(a, parent, M, out_len, out_path, stream);
+    return launch_selected_typed<uint16_t>(a, parent, M, out_len, out_path, stream);
 }
 
 hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {

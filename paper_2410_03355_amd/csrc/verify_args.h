@@ -46,6 +46,11 @@ hipError_t launch_verify(const VerifyArgs& a, int logits_dtype, hipStream_t stre
 // VERIFY_SELECTED: one workgroup per entry of a.select.
 hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipStream_t stream);
 
+// Second half of a tree step, one workgroup per tree (a.n_sel trees of M nodes): the walk over the
+// decisions in a.out_accept, then the residual draw it asks for into a.out_resample[tree].
+hipError_t launch_tree_finish(const VerifyArgs& a, const int32_t* parent, int M, int32_t* out_len, int32_t* out_path,
+                              int logits_dtype, hipStream_t stream);
+
 }  // namespace lantern
 
 namespace lantern {
