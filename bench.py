@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # plain 256 MiB copy gives in the same run).  Other workloads have no counter run: traffic is null.
 MEASURED_TRAFFIC_BYTES = {("stress", "plain", "sample"): 131140.3 * 1.99972 * 1024 + 240.1 * 1024,
                           ("stress", "plain", "greedy"): 69196.9 * 1.99973 * 1024 + 240.0 * 1024,
-                          ("stress", "plain", "tree"): 85349.3 * 1.99973 * 1024 + 240.0 * 1024}
+                          ("stress", "plain", "tree"): 75298.4 * 1.99973 * 1024 + 240.0 * 1024}
 
 
 def algorithmic_bytes_per_verification(V: int, k: int, logit_bytes: int) -> int:
