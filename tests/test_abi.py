@@ -95,3 +95,59 @@ def test_binding_refuses_host_tensors():
                  torch.zeros(2, 2))
     with pytest.raises(ValueError):
         L.build_knn(torch.zeros(8, 2), 2)
+
+
+def test_tree_and_split_argument_errors(lib):
+    """Host-side validation of the tree, shared-row, split and random-table entry points."""
+    import paper_2410_03355_amd as L
+    B_ = L.binding
+    p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+
+    def rows(ri=p, R=3, N=4, V=16, k=4, div=0, delta=0.1, oa=p, orr=p):
+        return lib.lantern_verify_rows(p, p, L.F32, R, V, 16, ri, N, p, p, k, div, delta, p, oa, orr, nul)
+
+    assert rows(ri=nul) == B_.E_NULL
+    assert rows(R=0) == B_.E_SHAPE
+    assert rows(div=2) == B_.E_SHAPE
+    assert rows(delta=-1.0) == B_.E_DELTA
+    assert rows(orr=nul) == B_.E_NULL
+    assert rows(N=0, ri=nul) == B_.OK
+
+    def decide(ri=p, R=4, N=4, oa=p):
+        return lib.lantern_decide_rows(p, p, L.F32, R, 16, 16, ri, N, p, p, 4, 0, 0.1, p, oa, nul, nul)
+
+    assert decide(ri=nul, R=3) == B_.E_SHAPE          # no index array: one row per verification
+    assert decide(oa=nul) == B_.E_NULL
+    assert decide(N=0, R=0, ri=nul) == B_.OK
+
+    def selected(sel=p, n_sel=2, N=4, out=p):
+        return lib.lantern_resample_selected(p, p, L.F32, N, 16, 16, nul, N, p, p, 4, 0, 0.1, p, sel, n_sel, out, nul)
+
+    assert selected(sel=nul) == B_.E_NULL
+    assert selected(out=nul) == B_.E_NULL
+    assert selected(n_sel=-1) == B_.E_SHAPE
+    assert selected(n_sel=2, N=0) == B_.E_SHAPE
+    assert selected(n_sel=0) == B_.OK
+
+    def trees(B=2, M=3, par=p, ri=p, on=p):
+        return lib.lantern_verify_trees(p, p, L.F32, 8, 16, 16, ri, par, B, M, p, p, 4, 0, 0.1, p, p, p, p, on, nul)
+
+    assert trees(M=0) == B_.E_SHAPE
+    assert trees(B=-1) == B_.E_SHAPE
+    assert trees(B=1 << 20, M=1 << 12) == B_.E_SHAPE   # B*M beyond int
+    assert trees(par=nul) == B_.E_NULL
+    assert trees(ri=nul) == B_.E_NULL
+    assert trees(on=nul) == B_.E_NULL
+    assert trees(B=0) == B_.OK
+
+    assert lib.lantern_accept_trees(p, p, p, 2, 0, p, p, p, nul) == B_.E_SHAPE
+    assert lib.lantern_accept_trees(p, nul, nul, 2, 3, p, p, p, nul) == B_.E_NULL
+    assert lib.lantern_accept_trees(nul, nul, nul, 0, 3, nul, nul, nul, nul) == B_.OK
+    assert lib.lantern_accept_chains(p, p, 2, 0, p, p, nul) == B_.E_SHAPE
+
+    assert lib.lantern_build_random(0, 1, 1, p, nul) == B_.E_SHAPE
+    assert lib.lantern_build_random(8, 9, 1, p, nul) == B_.E_SHAPE
+    assert lib.lantern_build_random(8192, L.binding.RANDOM_MAX_K + 1, 1, p, nul) == B_.E_SHAPE
+    assert lib.lantern_build_random(L.MAX_VOCAB + 1, 2, 1, p, nul) == B_.E_SHAPE
+    assert lib.lantern_build_random(8, 4, 1, nul, nul) == B_.E_NULL
