@@ -33,12 +33,27 @@ def hipcc_path() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
-           "-o", LIB_PATH, *srcs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    """Compiles every source to an object (in parallel, in a scratch directory) and links the library."""
+    import concurrent.futures
+    import tempfile
+
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    inc = ["-I", os.path.join(_ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="lantern_build_") as tmp:
+        def compile_one(name: str) -> str:
+            obj = os.path.join(tmp, os.path.splitext(name)[0] + ".o")
+            cmd = [hipcc_path(), *flags, *inc, "-c", os.path.join(CSRC, name), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     return LIB_PATH
 
 
