@@ -322,18 +322,12 @@ __global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const f
 }
 
 // ---- stage 2: select, re-rank exactly, emit ----
-constexpr int HBINS = 2048;          // histogram bins per refinement level (11 bits of the key)
-constexpr int HB_PER_THREAD = HBINS / NT;
-
 template <int CAP>
 struct SelectShared {
-    double key[CAP];      // the histogram lives in the first bytes until the candidates are known
+    double key[CAP];
     int idx[CAP];
     unsigned red_u[2 * NW];
-    int count;
-    unsigned thr_max;
-    int sel_bin;
-    int sel_below;
+    int red_c[2][NW];     // per-wavefront counts of a counting pass, double-buffered
 };
 
 // Error model of the approximate keys:
@@ -342,9 +336,9 @@ struct SelectShared {
 //
 // NK > 0: the row's V <= NK * 256 approximate keys are held in registers as order-preserving
 // unsigned integers; NK == 0: they are re-read from the workspace in every pass.
-// The (k-1+pad)-th smallest key is located with histograms of 2048 bins over the keys'
-// integer range, refined inside the threshold bin until the candidate set fits the LDS
-// (at most three levels cover 32 bits).
+// A threshold with between k-1+pad and `fit` keys at or below it is found by bisection over the
+// keys' integer range, every step one counting pass over the registers (compare, add, one
+// reduction): no sorting network or histogram over all V keys is needed to pick candidates.
 // Runs body(e) for every key slot of a thread: fully unrolled when the keys sit in registers.
 template <int NK, typename F>
 __device__ __forceinline__ void for_keys(int npt, F body) {
@@ -361,9 +355,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
                                                  const float* dist, float err_rel, float err_abs,
                                                  float err_norm, const float* norms, const float* nmax,
                                                  int32_t* out, int* flags) {
-    static_assert(CAP * sizeof(double) >= HBINS * sizeof(unsigned), "histogram must fit in the key array");
     __shared__ SelectShared<CAP> sh;
-    unsigned* hist = reinterpret_cast<unsigned*>(sh.key);
     const int row = blockIdx.x;
     const int i = r0 + row;
     const int tid = threadIdx.x;
@@ -389,17 +381,35 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     constexpr int NKR = NK > 0 ? NK : 1;
     uint32_t keys[NKR];
     const int npt = NK > 0 ? NK : (V + NT - 1) / NT;   // keys per thread
-    // key of element e of this thread (token e * NT + tid); 0xFFFFFFFF for the row's own token and padding
+    // Token of element e of this thread.  Keys in registers: groups of four consecutive tokens per
+    // thread, (e / 4) * NT + tid being the group, so that a group is one 16-byte load; else e * NT + tid.
+    auto token_of = [&](int e) -> int {
+        return NK > 0 ? (((e >> 2) * NT + tid) << 2) + (e & 3) : e * NT + tid;
+    };
+    // key of element e; 0xFFFFFFFF for the row's own token and padding
     auto key_at = [&](int e) -> uint32_t {
         if (NK > 0) return keys[e];
         const int j = e * NT + tid;
         return (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
     };
     if (NK > 0) {
+        const bool row_vec = (V & 3) == 0;   // then every row of the key block starts 16-byte aligned
 #pragma unroll
-        for (int e = 0; e < NKR; ++e) {
-            const int j = e * NT + tid;
-            keys[e] = (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+        for (int g = 0; g < NKR / 4; ++g) {
+            const int j0 = (g * NT + tid) << 2;
+            float f[4];
+            if (row_vec && j0 + 3 < V) {
+                const float4 q = *reinterpret_cast<const float4*>(drow + j0);
+                f[0] = q.x; f[1] = q.y; f[2] = q.z; f[3] = q.w;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) f[q] = (j0 + q < V) ? drow[j0 + q] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + q;
+                keys[4 * g + q] = (j < V && j != i) ? min(ord_key(f[q]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+            }
         }
     }
 
@@ -418,84 +428,85 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
 #pragma unroll
     for (int w = 1; w < NW; ++w) { kmin = min(kmin, sh.red_u[w]); kmax = max(kmax, sh.red_u[NW + w]); }
 
-    // histogram refinement: keys in [lo, lo + (HBINS << shift)) are binned by (key - lo) >> shift
-    uint32_t lo = kmin;
-    int shift = 0;
-    while (((uint64_t)(kmax - kmin) >> shift) >= (uint64_t)HBINS) ++shift;
-    // the sort works on a power of two: refine until the candidates fit the smallest one that holds `want`
+    // the sort works on a power of two: aim at the smallest one that holds `want`
     int fit = 1;
     while (fit < want) fit <<= 1;
     if (fit > CAP) fit = CAP;
-    int below = 0;               // keys strictly below lo: all of them are candidates
-    uint32_t thr_key = kmax;     // every key <= thr_key is a candidate
-    for (int level = 0; level < 4; ++level) {
-        __syncthreads();
-#pragma unroll
-        for (int b = 0; b < HB_PER_THREAD; ++b) hist[b * NT + tid] = 0;
-        __syncthreads();
-        const uint64_t span = (uint64_t)HBINS << shift;
-        for_keys<NK>(npt, [&](int e) {
-            const uint32_t key = key_at(e);
-            if (key != 0xFFFFFFFFu && key >= lo && (uint64_t)(key - lo) < span)
-                atomicAdd(&hist[(key - lo) >> shift], 1u);
-        });
-        __syncthreads();
-        // bin whose cumulative count first reaches the number still wanted: thread tid owns bins 8 tid .. 8 tid + 7
-        const int still = want - below;
-        unsigned local[HB_PER_THREAD];
-        unsigned tsum = 0;
-#pragma unroll
-        for (int b = 0; b < HB_PER_THREAD; ++b) { local[b] = hist[tid * HB_PER_THREAD + b]; tsum += local[b]; }
-        const int incl = wave_scan_i<OpSum>((int)tsum, 0);
-        if (lane == WAVE - 1) sh.red_u[wave] = (unsigned)incl;
-        __syncthreads();
-        int woff = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) if (w < wave) woff += (int)sh.red_u[w];
-        int cum = woff + incl - (int)tsum;   // keys in bins before this thread's
-        if (cum < still && cum + (int)tsum >= still) {
-#pragma unroll
-            for (int b = 0; b < HB_PER_THREAD; ++b) {
-                if (cum < still && cum + (int)local[b] >= still) { sh.sel_bin = tid * HB_PER_THREAD + b; sh.sel_below = cum; }
-                cum += (int)local[b];
-            }
+    // Bisection over [kmin - 1, kmax] (as 64-bit integers): count(lo) < want <= count(hi).  The best
+    // threshold seen is kept: the one with the fewest keys at or below it that still has `want` and
+    // fits the LDS; the search stops as soon as that number fits the aimed-at power of two.
+    int64_t lo = (int64_t)kmin - 1, hi = (int64_t)kmax;
+    int c_lo = 0, c_hi = V - 1;  // counts at lo and hi
+    uint32_t thr_key = kmax;
+    int best = V - 1;            // count(kmax): every other token
+    const int aim = want + ((fit - want) >> 1);
+    for (int pass = 0; pass < 64 && best > fit && hi - lo > 1; ++pass) {
+        // every other step interpolates the count linearly between the ends (the keys are dense and
+        // their distribution smooth, so this lands close); the steps between halve the interval
+        int64_t mid64 = lo + ((hi - lo) >> 1);
+        if ((pass & 1) == 0 && c_hi > c_lo) {
+            const double frac = (double)(aim - c_lo) / (double)(c_hi - c_lo);
+            mid64 = lo + (int64_t)((double)(hi - lo) * frac);
+            if (mid64 <= lo) mid64 = lo + 1;
+            if (mid64 >= hi) mid64 = hi - 1;
         }
-        __syncthreads();
-        const int bin = sh.sel_bin;
-        const int cnt_below_bin = sh.sel_below;
-        const int in_bin = (int)hist[bin];
-        const uint32_t bin_lo = lo + ((uint32_t)bin << shift);
-        const uint32_t bin_hi = (uint32_t)min((uint64_t)bin_lo + (((uint64_t)1 << shift) - 1), (uint64_t)0xFFFFFFFEu);
-        if (below + cnt_below_bin + in_bin <= fit || shift == 0) {
-            thr_key = bin_hi;   // take the whole bin
-            break;
+        const uint32_t mid = (uint32_t)mid64;
+        int c = 0;
+        for_keys<NK>(npt, [&](int e) { c += key_at(e) <= mid ? 1 : 0; });   // own token and padding: 0xFFFFFFFF > mid
+        c = __builtin_amdgcn_readlane(wave_scan_i<OpSum>(c, 0), 63);
+        if (lane == 0) sh.red_c[pass & 1][wave] = c;
+        __syncthreads();         // one barrier per pass: the buffers alternate
+        c = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) c += sh.red_c[pass & 1][w];
+        if (c < want) {
+            lo = mid64;
+            c_lo = c;
+        } else {
+            hi = mid64;
+            c_hi = c;
+            if (c < best) { best = c; thr_key = mid; }
         }
-        // too many keys share the bin: keep what lies below it and split the bin itself
-        below += cnt_below_bin;
-        lo = bin_lo;
-        shift = shift > 11 ? shift - 11 : 0;
+    }
+    if (best > CAP) {            // more (nearly) equal keys around the threshold than the LDS holds
+        if (tid == 0) flags[row] = 1;
+        return;
     }
 
-    // compaction of every j != i with approximate key <= threshold; the largest such key
-    if (tid == 0) { sh.count = 0; sh.thr_max = 0u; }
-    __syncthreads();
+    // compaction of every j != i with approximate key <= threshold, in thread order: every thread
+    // counts its own, a scan over the workgroup gives its first slot; the largest such key
+    int mine = 0;
     uint32_t my_max = 0u;
     for_keys<NK>(npt, [&](int e) {
         const uint32_t key = key_at(e);
         if (key <= thr_key) {   // the row's own token and padding carry 0xFFFFFFFF > thr_key
-            const int slot = atomicAdd(&sh.count, 1);
-            if (slot < CAP) sh.idx[slot] = e * NT + tid;
+            ++mine;
             my_max = max(my_max, key);
         }
     });
-    atomicMax(&sh.thr_max, my_max);
+    const int incl = wave_scan_i<OpSum>(mine, 0);
+    my_max = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMax>((int)(my_max ^ 0x80000000u), INT_MIN), 63) ^ 0x80000000u;
+    __syncthreads();             // the counting passes are done with red_u / red_c
+    if (lane == WAVE - 1) { sh.red_c[0][wave] = incl; sh.red_u[wave] = my_max; }
     __syncthreads();
-    const int count = sh.count;
+    int slot = incl - mine;
+    int count = 0;
+    uint32_t thr_max = 0u;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        if (w < wave) slot += sh.red_c[0][w];
+        count += sh.red_c[0][w];
+        thr_max = max(thr_max, sh.red_u[w]);
+    }
     if (count > CAP) {  // more equal keys at the threshold than the LDS holds
         if (tid == 0) flags[row] = 1;
         return;
     }
-    const float thr = ord_inv(sh.thr_max);   // every discarded token has an approximate key above this
+    for_keys<NK>(npt, [&](int e) {
+        if (key_at(e) <= thr_key) sh.idx[slot++] = token_of(e);
+    });
+    __syncthreads();
+    const float thr = ord_inv(thr_max);   // every discarded token has an approximate key above this
     int P = 1;
     while (P < count) P <<= 1;
     for (int c = tid; c < P; c += NT) {
