@@ -86,6 +86,7 @@ __device__ double exact_key(const CT* cb, int d, int i, int j, int metric, bool 
     if (metric == 0) {
         double acc = 0.0;
         if (vec4) {
+#pragma unroll 4   // the loads of four groups are in flight together; the sum keeps its order
             for (int t = 0; t < d; t += 4) {
                 float x[4], y[4];
                 cb_load4(ci, t, x);
@@ -436,20 +437,10 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     // threshold seen is kept: the one with the fewest keys at or below it that still has `want` and
     // fits the LDS; the search stops as soon as that number fits the aimed-at power of two.
     int64_t lo = (int64_t)kmin - 1, hi = (int64_t)kmax;
-    int c_lo = 0, c_hi = V - 1;  // counts at lo and hi
     uint32_t thr_key = kmax;
     int best = V - 1;            // count(kmax): every other token
-    const int aim = want + ((fit - want) >> 1);
-    for (int pass = 0; pass < 64 && best > fit && hi - lo > 1; ++pass) {
-        // every other step interpolates the count linearly between the ends (the keys are dense and
-        // their distribution smooth, so this lands close); the steps between halve the interval
-        int64_t mid64 = lo + ((hi - lo) >> 1);
-        if ((pass & 1) == 0 && c_hi > c_lo) {
-            const double frac = (double)(aim - c_lo) / (double)(c_hi - c_lo);
-            mid64 = lo + (int64_t)((double)(hi - lo) * frac);
-            if (mid64 <= lo) mid64 = lo + 1;
-            if (mid64 >= hi) mid64 = hi - 1;
-        }
+    for (int pass = 0; pass < 40 && best > fit && hi - lo > 1; ++pass) {
+        const int64_t mid64 = lo + ((hi - lo) >> 1);
         const uint32_t mid = (uint32_t)mid64;
         int c = 0;
         for_keys<NK>(npt, [&](int e) { c += key_at(e) <= mid ? 1 : 0; });   // own token and padding: 0xFFFFFFFF > mid
@@ -461,10 +452,8 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         for (int w = 0; w < NW; ++w) c += sh.red_c[pass & 1][w];
         if (c < want) {
             lo = mid64;
-            c_lo = c;
         } else {
             hi = mid64;
-            c_hi = c;
             if (c < best) { best = c; thr_key = mid; }
         }
     }
@@ -517,10 +506,19 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
             sh.idx[c] = INT_MAX;
         }
     }
-    // bitonic sort ascending by (key, idx)
+    // Bitonic sort ascending by (key, idx).  Pair t of a step works on elements l = 2t - (t mod stride)
+    // and l + stride; a wavefront takes pairs 64w .. 64w+63 (and the same 256, 512 ... further on), so
+    // for strides up to 64 it reads and writes only its own blocks of 128 elements: a step of stride
+    // below 64 follows one that stayed inside those blocks and needs the wavefront's own LDS order,
+    // not a workgroup barrier.
     for (int size = 2; size <= P; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
+            if (stride >= WAVE || size == 2) {   // also the step after a wider one, and the very first
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
             for (int t = tid; t < (P >> 1); t += NT) {
                 const int l = 2 * t - (t & (stride - 1));
                 const int r = l + stride;
