@@ -2,13 +2,25 @@
  * lantern.h - C ABI of the MI355X (gfx950) library for LANTERN's relaxed
  * speculative-decoding verification (arXiv 2410.03355).
  *
- * Two operations:
+ * The two operations of the method:
  *   lantern_build_knn  the latent-space neighbour table B_k of the VQ codebook
  *                      (Section 4.2; Algorithm 2, "Precompute B_k" part)
  *   lantern_verify     one relaxed verification per row: TVD-bounded
  *                      neighbourhood A_{k,delta}, acceptance test, residual
  *                      resampling (Section 4.3; Algorithm 2, inference part;
  *                      Algorithm 1, the accept / resample branch)
+ * and what the paper builds around them:
+ *   lantern_build_knn_metric, lantern_build_random   the cosine and random
+ *                      neighbourhoods of the ablation (Section 5.3.1)
+ *   lantern_verify_divergence   the Jensen-Shannon bound (Section 5.3.2)
+ *   lantern_verify_greedy       greedy decoding (Section 4.3, last sentence)
+ *   lantern_accept_chains, lantern_accept_trees   the loop of Algorithm 1
+ *                      over a drafted chain / along the branches of a tree
+ *   lantern_verify_rows, lantern_verify_greedy_rows   candidates that share
+ *                      logit rows (siblings of a draft tree)
+ *   lantern_decide_rows, lantern_resample_selected, lantern_verify_trees
+ *                      decisions for all candidates, the residual draw only
+ *                      where Algorithm 1 uses it
  *
  * Naming.  The paper writes p for the drafter and q for the target model.
  * Other texts use the letters the other way round, so this header uses
@@ -17,7 +29,8 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller and must stay
  *     valid until the work enqueued on the stream has finished.  The library
- *     allocates nothing, frees nothing and keeps no state between calls.
+ *     allocates nothing, frees nothing and keeps no state between calls that
+ *     a result could depend on.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default
  *     stream).  Calls only enqueue kernels; they do not synchronise.
  *   - The return value is a lantern_status.  Argument errors are found on the
