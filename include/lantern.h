@@ -144,7 +144,11 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
  * Decisions are exact with respect to fp64 evaluation of the rule above: a
  * fast fp32 pass settles every row whose comparisons clear a proven rounding
  * margin, and the remaining rows (and all rejected rows, whose inverse-CDF
- * bucket cannot be settled in fp32) are evaluated in fp64.
+ * bucket cannot be settled in fp32) are evaluated in fp64.  A rejected row
+ * therefore costs many times an accepted one (about 23 us of one compute unit
+ * at V = 16384); callers that walk chains or trees and use one resampled
+ * token per walk should use lantern_decide_rows / lantern_resample_selected or
+ * lantern_verify_trees below.
  *
  * Errors: E_NULL, E_SHAPE (also V > LANTERN_MAX_VOCAB), E_DTYPE, E_DELTA,
  * E_DEVICE.  N = 0 is valid and does nothing.
