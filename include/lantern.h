@@ -350,7 +350,9 @@ int lantern_resample_selected(const void* target_logits, const void* draft_logit
  * looks at.  Two launches: the decisions; then one workgroup per tree walks
  * it and draws the residual.
  *
- *   row_index, draft_tokens, uniforms, parent  [B*M], candidate i of tree b at b*M + i
+ *   row_index, draft_tokens, uniforms, parent  [B*M], candidate i of tree b at b*M + i;
+ *              row_index may be NULL when R == B*M (candidate i reads row i: drafted
+ *              chains, parent[i] = i - 1, have a pair of rows per candidate)
  *   out_accept [B*M], out_len [B], out_path [B*M], out_next [B]  as in
  *              lantern_verify_rows / lantern_accept_trees
  * Errors: those of the three calls; E_SHAPE also when B*M exceeds INT_MAX.

@@ -432,8 +432,6 @@ def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_t
     lib = load()
     R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
     _need_cuda(parent)
-    if row_index is None:
-        raise ValueError("row_index is required")
     if parent.dtype != torch.int32 or not parent.is_contiguous() or parent.numel() != N or M < 1 or N % M:
         raise ValueError("parent must be a contiguous int32 tensor of B*M entries")
     B = N // M
@@ -443,7 +441,8 @@ def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_t
     path = torch.empty((B, M), dtype=torch.int32, device=dev)
     nxt = torch.empty(B, dtype=torch.int32, device=dev)
     rc = lib.lantern_verify_trees(target_logits.data_ptr(), draft_logits.data_ptr(), _dtype_code(target_logits),
-                                  R, V, stride, row_index.data_ptr(), parent.data_ptr(), B, int(M),
+                                  R, V, stride, None if row_index is None else row_index.data_ptr(),
+                                  parent.data_ptr(), B, int(M),
                                   draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
                                   {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence], float(delta), uniforms.data_ptr(),
                                   acc.data_ptr(), n.data_ptr(), path.data_ptr(), nxt.data_ptr(), _stream_ptr(stream))

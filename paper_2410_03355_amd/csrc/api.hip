@@ -258,7 +258,8 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
                          int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream) {
     if (B < 0 || M < 1 || (int64_t)B * M > INT_MAX) return LANTERN_E_SHAPE;
     const int N = B * M;
-    if (B > 0 && (!row_index || !parent || !out_len || !out_path || !out_next)) return LANTERN_E_NULL;
+    if (B > 0 && (!parent || !out_len || !out_path || !out_next)) return LANTERN_E_NULL;
+    if (!row_index && R != N) return LANTERN_E_SHAPE;   // without an index array candidate i reads row i
     // decisions of all candidates; then, one workgroup per tree, the walk and the residual draw of the
     // one candidate it asks for
     const int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index,

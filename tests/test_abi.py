@@ -137,7 +137,7 @@ def test_tree_and_split_argument_errors(lib):
     assert trees(B=-1) == B_.E_SHAPE
     assert trees(B=1 << 20, M=1 << 12) == B_.E_SHAPE   # B*M beyond int
     assert trees(par=nul) == B_.E_NULL
-    assert trees(ri=nul) == B_.E_NULL
+    assert trees(ri=nul) == B_.E_SHAPE               # no index array: one row per candidate (R = 8, B*M = 6)
     assert trees(on=nul) == B_.E_NULL
     assert trees(B=0) == B_.OK
 

@@ -290,3 +290,26 @@ def test_empty_inputs(lantern_gpu):
     un = torch.zeros((3, 2), device=dev)
     assert lantern_gpu.resample_selected(t3, t3, None, tok, knn, 0.1, un, none_i).numel() == 0
     torch.cuda.synchronize()
+
+
+def test_chains_through_the_tree_step(oracle_mod, lantern_gpu):
+    """A drafted chain is a tree with one child per node and a pair of rows per candidate: the
+    fused step without an index array against the oracle's verification and chain walk."""
+    cfg = workloads.CONFIGS["llamagen_step"]
+    B, L = 12, 8
+    st = workloads.make_step(cfg, step=21, rows=B * L, variant="peaked")
+    table = sparse_table_from_oracle(oracle_mod, workloads.make_codebook(cfg).numpy(), cfg.k,
+                                     st.draft_tokens.numpy())
+    delta = 0.05
+    acc_o, res_o, _ = oracle_mod.verify(st.target_logits, st.draft_logits, st.draft_tokens, table, cfg.k, delta,
+                                        st.uniforms, threads=8)
+    kept_o, next_o = oracle_mod.accept_chains(acc_o, res_o, L)
+    parent = torch.arange(-1, L - 1, dtype=torch.int32).repeat(B).cuda()
+    acc, n, path, nxt = lantern_gpu.verify_trees(st.target_logits.cuda(), st.draft_logits.cuda(), None, parent, L,
+                                                 st.draft_tokens.cuda(), torch.from_numpy(table).cuda(), delta,
+                                                 st.uniforms.cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(n.cpu().numpy(), kept_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+    assert 0 < kept_o.mean() < L
