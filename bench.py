@@ -42,7 +42,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=576)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent"])
+    ap.add_argument("--workload", default="stress", choices=["stress", "image_batch", "wide_latent", "llamagen_step", "tiny"],
+                    help="stress is the headline; llamagen_step (one tree's 60 candidates per call) and tiny are "
+                         "in the launch-latency regime: read ms_per_step")
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
     ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree", "decide"],
                     help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only; "
@@ -263,7 +265,22 @@ def main() -> int:
             c1 = time.perf_counter()
             if c1 - c0 >= args.cpu_seconds:
                 break
+        # one thread, one step; and the table build of a sample of query rows on all threads
+        s0 = time.perf_counter()
+        tl, dl, tok, un = host[0]
+        n_single = min(rows, 512)
+        oracle.verify(tl[:n_single], dl[:n_single], tok[:n_single], knn_host, cfg.k, delta, un[:n_single], threads=1,
+                      want_diag=False)
+        s1 = time.perf_counter()
+        cb_host = codebook.float().cpu().numpy()
+        n_knn = min(cfg.V, 256)
+        k0 = time.perf_counter()
+        oracle.build_knn(cb_host, cfg.k, rows=(0, n_knn), threads=threads)
+        k1 = time.perf_counter()
         result["cpu_baseline"] = {
+            "single_thread_value": n_single / (s1 - s0),
+            "knn_build_ms_extrapolated": (k1 - k0) / n_knn * cfg.V * 1e3,
+            "knn_sample": f"{n_knn} of {cfg.V} query rows on {threads} threads, scaled to the whole table",
             "value": n_cpu * rows / (c1 - c0),
             "unit": "verifications/s",
             "cores": threads,
