@@ -189,6 +189,27 @@ def main() -> int:
     # average launch duration: includes the gap between consecutive launches on the stream
     kernel_ms_avg = ev0.elapsed_time(ev1) / args.steps
 
+    # the device's read rate for a plain stream of the same shape (same buffers, same rotation)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_src = [(b.target_logits, None if greedy else b.draft_logits) for b in bufs] if not tree else \
+        [(t_[0].target_logits, t_[0].draft_logits) for t_ in tbufs]
+    probe_bytes = probe_src[0][0].numel() * probe_src[0][0].element_size() // 65536 * 65536
+    probe_total = probe_bytes * (1 if greedy else 2)
+    for i in range(4):
+        pa, pb = probe_src[i % nbuf]
+        lib.lantern_probe_stream_read(pa.data_ptr(), None if pb is None else pb.data_ptr(), probe_bytes,
+                                      sink.data_ptr(), stream.cuda_stream)
+    pv0, pv1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pv0.record(stream)
+    n_probe = 100
+    for i in range(n_probe):
+        pa, pb = probe_src[i % nbuf]
+        lib.lantern_probe_stream_read(pa.data_ptr(), None if pb is None else pb.data_ptr(), probe_bytes,
+                                      sink.data_ptr(), stream.cuda_stream)
+    pv1.record(stream)
+    torch.cuda.synchronize()
+    stream_read_gbs = probe_total * n_probe / (pv0.elapsed_time(pv1) * 1e-3) / 1e9
+
     rows = rows_per_step if tree else cfg.rows
     logit_bytes = 2 if cfg.logit_dtype == "bf16" else 4
     bytes_per_launch = algorithmic_bytes_per_verification(cfg.V, cfg.k, logit_bytes) * rows
@@ -238,6 +259,9 @@ def main() -> int:
                   else MEASURED_TRAFFIC_BYTES.get((args.workload, args.variant, args.mode))),
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "kernel_ms_avg": kernel_ms_avg,
+            "stream_read_gbs": stream_read_gbs,
+            "stream_read_note": f"plain read of {probe_total >> 20} MiB per launch from the same rotating buffers, one "
+                                "workgroup per 64 KiB: what a kernel with this access pattern reaches on this device",
         },
         "knn_build_ms": knn_build_ms,
     }

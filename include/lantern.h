@@ -363,6 +363,19 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
                          int k, int divergence, float delta, const float* uniforms, int32_t* out_accept,
                          int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: reads the first bytes / 65536 whole
+ * 64 KiB chunks of src_a, and of src_b when it is not NULL, once, with the
+ * access pattern of the verification kernel (one workgroup per chunk, 16-byte
+ * loads), and discards them.  Timed by the caller it gives the read rate the
+ * device reaches for such a stream.
+ *   src_a, src_b  device, 16-byte aligned;  sink  device, one uint32
+ *                 (practically never written)
+ * Errors: E_NULL, E_SHAPE (alignment, more than 2^30 - 1 chunks), E_DEVICE.
+ */
+int lantern_probe_stream_read(const void* src_a, const void* src_b, size_t bytes, uint32_t* sink,
+                              void* hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* lantern_status_string(int status);
 

@@ -25,6 +25,7 @@ EXPORTS = (
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
+    "lantern_probe_stream_read",
     "lantern_status_string",
     "lantern_version",
 )
@@ -81,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_trees.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, i32, f32, vp,
                                          vp, vp, vp, vp, vp]
     lib.lantern_verify_trees.restype = i32
+    lib.lantern_probe_stream_read.argtypes = [vp, vp, sz, vp, vp]
+    lib.lantern_probe_stream_read.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
     lib.lantern_build_random.restype = i32
     lib.lantern_status_string.argtypes = [i32]

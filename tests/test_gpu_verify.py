@@ -250,3 +250,18 @@ def test_maximum_vocabulary(oracle_mod, lantern_gpu):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(ga.cpu().numpy(), ga_o)
         np.testing.assert_array_equal(gt.cpu().numpy(), gt_o)
+
+
+def test_stream_read_probe(lantern_gpu):
+    """The measurement aid only reads: it must run, reject bad arguments and leave its source untouched."""
+    lib = lantern_gpu.load()
+    src = torch.arange(3 * 65536 // 4, dtype=torch.int32, device="cuda")
+    keep = src.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert lib.lantern_probe_stream_read(src.data_ptr(), None, src.numel() * 4, sink.data_ptr(), None) == 0
+    assert lib.lantern_probe_stream_read(src.data_ptr(), src.data_ptr(), src.numel() * 4, sink.data_ptr(), None) == 0
+    assert lib.lantern_probe_stream_read(src.data_ptr(), None, 100, sink.data_ptr(), None) == 0      # no whole chunk
+    assert lib.lantern_probe_stream_read(None, None, 65536, sink.data_ptr(), None) == -1
+    assert lib.lantern_probe_stream_read(src.data_ptr() + 4, None, 65536, sink.data_ptr(), None) == -2
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
