@@ -6,15 +6,19 @@
 //               16-byte loads, keeps the raw target row in LDS, gathers the
 //               draft token's k neighbours from LDS, prefix-scans them and
 //               takes the TVD cut and the acceptance test.  Each comparison
-//               carries a rounding margin; a row is settled here only when it
-//               is accepted and every comparison it took cleared its margin.
+//               carries a rounding margin; a row is settled here only when
+//               every comparison it took cleared its margin and it is accepted
+//               (or, when only decisions are asked for, definitely rejected).
 //   exact path  fp64.  The workgroup of a row the fast path did not settle
-//               (ambiguous comparison, unusable input, every rejected row)
-//               re-evaluates it: same rule, then the residual and its
-//               inverse CDF.
+//               (ambiguous comparison, unusable input, a rejected row whose
+//               resampled token is wanted) re-evaluates it: same rule, then
+//               the residual and its inverse CDF.
 // Shapes the fast path does not cover (rows not 16-byte aligned, V not a
 // multiple of the vector width, rows beyond the register budget) run the
 // exact path for every row (kernel verify_exact).
+// Three modes (verify_args.h): decisions and resampled tokens; decisions only;
+// the fp64 path for selected verifications in 1024-thread workgroups
+// (resample_selected, and tree_finish, which first walks its draft tree).
 // Letters: t = target probability (the paper's q), g = drafter probability
 // (the paper's p), xt = draft token.
 #include <hip/hip_runtime.h>
