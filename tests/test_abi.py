@@ -151,3 +151,14 @@ def test_tree_and_split_argument_errors(lib):
     assert lib.lantern_build_random(8192, L.binding.RANDOM_MAX_K + 1, 1, p, nul) == B_.E_SHAPE
     assert lib.lantern_build_random(L.MAX_VOCAB + 1, 2, 1, p, nul) == B_.E_SHAPE
     assert lib.lantern_build_random(8, 4, 1, nul, nul) == B_.E_NULL
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No fallback implementation: without the built library every call raises."""
+    import paper_2410_03355_amd.binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "liblantern.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load()
+    with pytest.raises(FileNotFoundError):
+        B.knn_workspace_bytes(0, 16, 8, 4)
