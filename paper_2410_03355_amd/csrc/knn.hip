@@ -3,7 +3,8 @@
 // Pipeline per block of query rows:
 //   1. approximate keys (fp32) for every pair (query i, token j) into the
 //      workspace: squared l2 distance, or minus cosine similarity
-//   2. per row: radix-select the (k-1+pad) smallest approximate keys, recompute
+//   2. per row: find a threshold with at least k-1+pad approximate keys at or below it
+//      (bisection with counting passes), recompute
 //      the survivors' keys in fp64 exactly as the definition states (coordinate
 //      order, every operation rounded separately), sort them by (key, index)
 //      and emit the first k-1 after the token itself.  A row is emitted only if
