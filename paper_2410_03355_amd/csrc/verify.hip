@@ -17,7 +17,7 @@
 // multiple of the vector width, rows beyond the register budget) run the
 // exact path for every row (kernel verify_exact).
 // Three modes (verify_args.h): decisions and resampled tokens; decisions only;
-// the fp64 path for selected verifications in 1024-thread workgroups
+// the fp64 path for selected verifications in 512-thread workgroups
 // (resample_selected, and tree_finish, which first walks its draft tree).
 // Letters: t = target probability (the paper's q), g = drafter probability
 // (the paper's p), xt = draft token.
@@ -523,10 +523,11 @@ __global__ __launch_bounds__(NT) void verify_exact(VerifyArgs a) {
 }
 
 // VERIFY_SELECTED: workgroup i evaluates verification select[i] and writes out_resample[i].
-// Few rows per launch, so each gets a workgroup of 1024 threads: the fp64 passes of a row are
+// Few rows per launch, so each gets a workgroup of 512 threads (two wavefronts per SIMD, no register
+// spills; 1024 threads measured slower): the fp64 passes of a row are
 // latency-bound at one wavefront per SIMD.
-constexpr int SEL_NT = 1024;
-// Evaluates verification v in fp64 with the 1024 threads of this workgroup (VERIFY_SELECTED: only
+constexpr int SEL_NT = 512;
+// Evaluates verification v in fp64 with all threads of this workgroup (VERIFY_SELECTED: only
 // out_resample[blockIdx.x] is written).  When they fit, both logit rows are first copied into LDS,
 // all loads in flight together, so the fp64 passes read LDS.
 template <typename LT, bool VEC>
