@@ -21,6 +21,7 @@
  *   lantern_decide_rows, lantern_resample_selected, lantern_verify_trees
  *                      decisions for all candidates, the residual draw only
  *                      where Algorithm 1 uses it
+ *   lantern_verify_trees_greedy   the tree step under greedy decoding
  *
  * Naming.  The paper writes p for the drafter and q for the target model.
  * Other texts use the letters the other way round, so this header uses
@@ -362,6 +363,22 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
                          const int32_t* parent, int B, int M, const int32_t* draft_tokens, const int32_t* knn,
                          int k, int divergence, float delta, const float* uniforms, int32_t* out_accept,
                          int32_t* out_len, int32_t* out_path, int32_t* out_next, void* hip_stream);
+
+/*
+ * The tree step under greedy decoding (Section 4.3, last sentence, along the
+ * branches of Algorithm 1): lantern_verify_greedy_rows for all B*M candidates,
+ * then lantern_accept_trees on its outputs.  No drafter logits, no random
+ * draws; the token that follows a branch is the arg-max of the distorted
+ * target of the first child of its last node.
+ *   row_index  may be NULL when R == B*M
+ *   out_accept, out_token [B*M]; out_len [B], out_path [B*M], out_next [B]
+ * Errors: those of the two calls.
+ */
+int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_dtype, int R, int V,
+                                int64_t row_stride_elems, const int32_t* row_index, const int32_t* parent, int B,
+                                int M, const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                                int32_t* out_accept, int32_t* out_token, int32_t* out_len, int32_t* out_path,
+                                int32_t* out_next, void* hip_stream);
 
 /*
  * Measurement aid, not part of the method: reads the first bytes / 65536 whole

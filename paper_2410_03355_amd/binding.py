@@ -25,7 +25,7 @@ EXPORTS = (
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
-    "lantern_probe_stream_read",
+    "lantern_verify_trees_greedy", "lantern_probe_stream_read",
     "lantern_status_string",
     "lantern_version",
 )
@@ -82,6 +82,9 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_trees.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, i32, f32, vp,
                                          vp, vp, vp, vp, vp]
     lib.lantern_verify_trees.restype = i32
+    lib.lantern_verify_trees_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp, vp,
+                                                vp, vp, vp]
+    lib.lantern_verify_trees_greedy.restype = i32
     lib.lantern_probe_stream_read.argtypes = [vp, vp, sz, vp, vp]
     lib.lantern_probe_stream_read.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
@@ -452,3 +455,40 @@ def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_t
     if rc != OK:
         raise LanternError(rc, "lantern_verify_trees")
     return acc, n, path, nxt
+
+
+def verify_trees_greedy(target_logits, row_index, parent, M: int, draft_tokens, knn, delta: float, stream=None):
+    """lantern_verify_trees_greedy; returns (accept int32[B*M], token int32[B*M], len int32[B],
+    path int32[B, M], next int32[B])."""
+    lib = load()
+    given = [t for t in (target_logits, row_index, parent, draft_tokens, knn) if t is not None]
+    _need_cuda(*given)
+    if target_logits.dim() != 2 or target_logits.stride(1) != 1:
+        raise ValueError("logits must be a [R, V] tensor with dense rows")
+    R, V = target_logits.shape
+    N = draft_tokens.numel()
+    if row_index is not None:
+        _check_row_index(row_index, N)
+    elif R != N:
+        raise ValueError("without row_index there must be one logit row per candidate")
+    for t in (parent, draft_tokens, knn):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise TypeError("parent, draft_tokens and knn must be contiguous int32 tensors")
+    if parent.numel() != N or M < 1 or N % M or knn.dim() != 2 or knn.shape[0] != V:
+        raise ValueError("shape mismatch between parent, tokens and the table")
+    B = N // M
+    dev = target_logits.device
+    acc = torch.empty(N, dtype=torch.int32, device=dev)
+    tok = torch.empty(N, dtype=torch.int32, device=dev)
+    n = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, M), dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib.lantern_verify_trees_greedy(target_logits.data_ptr(), _dtype_code(target_logits), R, V,
+                                         target_logits.stride(0) if R > 1 else V,
+                                         None if row_index is None else row_index.data_ptr(), parent.data_ptr(), B,
+                                         int(M), draft_tokens.data_ptr(), knn.data_ptr(), int(knn.shape[1]),
+                                         float(delta), acc.data_ptr(), tok.data_ptr(), n.data_ptr(), path.data_ptr(),
+                                         nxt.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_trees_greedy")
+    return acc, tok, n, path, nxt

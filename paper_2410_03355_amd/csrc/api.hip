@@ -296,6 +296,21 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
+int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_dtype, int R, int V,
+                                int64_t row_stride_elems, const int32_t* row_index, const int32_t* parent, int B,
+                                int M, const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
+                                int32_t* out_accept, int32_t* out_token, int32_t* out_len, int32_t* out_path,
+                                int32_t* out_next, void* hip_stream) {
+    if (B < 0 || M < 1 || (int64_t)B * M > INT_MAX) return LANTERN_E_SHAPE;
+    const int N = B * M;
+    if (B > 0 && (!parent || !out_len || !out_path || !out_next)) return LANTERN_E_NULL;
+    if (!row_index && R != N) return LANTERN_E_SHAPE;
+    const int rc = greedy_impl(target_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems, draft_tokens,
+                               knn, k, delta, out_accept, out_token, nullptr, hip_stream);
+    if (rc != LANTERN_OK || B == 0) return rc;
+    return lantern_accept_trees(out_accept, out_token, parent, B, M, out_len, out_path, out_next, hip_stream);
+}
+
 const char* lantern_status_string(int status) {
     switch (status) {
         case LANTERN_OK: return "ok";

@@ -156,3 +156,30 @@ def test_row_index_errors(lantern_gpu):
     rc = lib.lantern_accept_trees(tok.data_ptr(), tok.data_ptr(), tok.data_ptr(), 1, 0, tok.data_ptr(), tok.data_ptr(),
                                   tok.data_ptr(), None)
     assert rc == -2
+
+
+def test_greedy_tree_step(oracle_mod, lantern_gpu):
+    """lantern_verify_trees_greedy against the oracle's greedy verification over shared rows and its walk."""
+    from parity_utils import level_order
+    cfg = workloads.CONFIGS["llamagen_step"]
+    rng = np.random.default_rng(41)
+    B, M = 6, 60
+    parent = level_order(random_trees(rng, B, M, max_children=5))
+    st, row_index, tokens, un = tree_step(cfg, parent, step=9, variant="peaked")
+    order = torch.argsort(st.target_logits.float(), dim=1, descending=True)[:, :3].numpy()
+    tokens = order[row_index, rng.integers(0, 3, B * M)].astype(np.int32)     # drafts near the top of the target
+    table = random_table(cfg.V, cfg.k, seed=13)
+    for delta in (0.0, 0.02, 0.3):
+        acc_o, tok_o, _ = oracle_mod.verify_greedy_rows(st.target_logits, row_index, tokens, table, cfg.k, delta,
+                                                        threads=8)
+        n_o, path_o, next_o = oracle_mod.accept_trees(acc_o, tok_o, parent, M)
+        acc, tok, n, path, nxt = lantern_gpu.verify_trees_greedy(
+            st.target_logits.cuda(), torch.from_numpy(row_index).cuda(), torch.from_numpy(parent).cuda().reshape(-1), M,
+            torch.from_numpy(tokens).cuda(), torch.from_numpy(table).cuda(), delta)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(tok.cpu().numpy(), tok_o)
+        np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+    assert n_o.max() >= 1
