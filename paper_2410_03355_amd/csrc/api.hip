@@ -12,6 +12,14 @@ namespace {
 
 bool dtype_ok(int dt) { return dt == LANTERN_F32 || dt == LANTERN_BF16; }
 
+// What the second half of a tree step needs besides the verification arguments.
+struct TreeFinish {
+    const int32_t* parent;
+    int M;
+    int32_t* out_len;
+    int32_t* out_path;
+};
+
 // R, row_index: number of logit rows and the row every verification reads; without an index
 // array (row_index null) verification i reads row i and R is N.
 int verify_impl(const void* target_logits, const void* draft_logits, int logits_dtype, int R,
@@ -20,7 +28,7 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
                 int divergence, float delta, const float* uniforms, int32_t* out_accept, int32_t* out_resample,
                 float* out_accept_prob, float* out_mass, float* out_g_tok, int32_t* out_a_size,
                 int32_t* out_path, void* hip_stream, int mode = lantern::VERIFY_FULL,
-                const int32_t* select = nullptr, int n_sel = 0) {
+                const int32_t* select = nullptr, int n_sel = 0, const TreeFinish* tree = nullptr) {
     if (!dtype_ok(logits_dtype)) return LANTERN_E_DTYPE;
     if (N < 0 || R < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V)
         return LANTERN_E_SHAPE;
@@ -32,7 +40,7 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     if (!target_logits || !draft_logits || !draft_tokens || !knn || !uniforms) return LANTERN_E_NULL;
     if (mode != lantern::VERIFY_SELECTED && !out_accept) return LANTERN_E_NULL;
     if (mode != lantern::VERIFY_DECIDE && !out_resample) return LANTERN_E_NULL;
-    if (mode == lantern::VERIFY_SELECTED && !select) return LANTERN_E_NULL;
+    if (mode == lantern::VERIFY_SELECTED && !select && !tree) return LANTERN_E_NULL;
     lantern::VerifyArgs a;
     a.target = target_logits;
     a.draft = draft_logits;
@@ -58,9 +66,14 @@ int verify_impl(const void* target_logits, const void* draft_logits, int logits_
     a.out_gtok = out_g_tok;
     a.out_asize = out_a_size;
     a.out_path = out_path;
-    const hipError_t e = mode == lantern::VERIFY_SELECTED
-                             ? lantern::launch_resample_selected(a, logits_dtype, static_cast<hipStream_t>(hip_stream))
-                             : lantern::launch_verify(a, logits_dtype, static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (tree)   // one workgroup per tree: the walk over out_accept, then the residual draw it asks for
+        e = lantern::launch_tree_finish(a, tree->parent, tree->M, tree->out_len, tree->out_path, logits_dtype, stream);
+    else if (mode == lantern::VERIFY_SELECTED)
+        e = lantern::launch_resample_selected(a, logits_dtype, stream);
+    else
+        e = lantern::launch_verify(a, logits_dtype, stream);
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
@@ -266,34 +279,10 @@ int lantern_verify_trees(const void* target_logits, const void* draft_logits, la
                                        N, draft_tokens, knn, k, divergence, delta, uniforms, out_accept, nullptr,
                                        hip_stream);
     if (rc != LANTERN_OK || B == 0) return rc;
-    lantern::VerifyArgs a;
-    a.target = target_logits;
-    a.draft = draft_logits;
-    a.N = N;
-    a.R = R;
-    a.row_index = row_index;
-    a.V = V;
-    a.stride = row_stride_elems;
-    a.tokens = draft_tokens;
-    a.knn = knn;
-    a.k = k;
-    a.divergence = divergence;
-    a.mode = lantern::VERIFY_SELECTED;
-    a.select = nullptr;
-    a.n_sel = B;
-    a.stage_rows = 0;
-    a.delta = delta;
-    a.uniforms = uniforms;
-    a.out_accept = out_accept;
-    a.out_resample = out_next;
-    a.out_prob = nullptr;
-    a.out_mass = nullptr;
-    a.out_gtok = nullptr;
-    a.out_asize = nullptr;
-    a.out_path = nullptr;
-    const hipError_t e = lantern::launch_tree_finish(a, parent, M, out_len, out_path, (int)logits_dtype,
-                                                     static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+    const TreeFinish tree{parent, M, out_len, out_path};
+    return verify_impl(target_logits, draft_logits, (int)logits_dtype, R, row_index, N, V, row_stride_elems,
+                       draft_tokens, knn, k, divergence, delta, uniforms, out_accept, out_next, nullptr, nullptr,
+                       nullptr, nullptr, nullptr, hip_stream, lantern::VERIFY_SELECTED, nullptr, B, &tree);
 }
 
 int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_dtype, int R, int V,
