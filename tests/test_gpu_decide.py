@@ -313,3 +313,33 @@ def test_chains_through_the_tree_step(oracle_mod, lantern_gpu):
     np.testing.assert_array_equal(n.cpu().numpy(), kept_o)
     np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
     assert 0 < kept_o.mean() < L
+
+
+@pytest.mark.parametrize("V,k,dtype", [(1003, 50, torch.bfloat16), (7, 7, torch.float32), (40000, 64, torch.float32)])
+def test_shared_rows_off_the_fast_path(oracle_mod, lantern_gpu, V, k, dtype):
+    """Shapes that only the fp64 kernels take (odd vocabulary, rows beyond the register budget), with an
+    index array, in all three modes and through the tree step."""
+    rng = np.random.default_rng(V)
+    R, B, M = 5, 3, 6
+    t = torch.from_numpy((rng.standard_normal((R, V)) * 2).astype(np.float32)).to(dtype)
+    g = (t.float() + torch.from_numpy(rng.standard_normal((R, V)).astype(np.float32))).to(dtype)
+    st = workloads.Step(target_logits=t, draft_logits=g, draft_tokens=None, uniforms=None)
+    parent = random_trees(rng, B, M, max_children=3)
+    N = B * M
+    row_index = rng.integers(0, R, N).astype(np.int32)
+    row_index[4] = R
+    tokens = rng.integers(0, V, N).astype(np.int32)
+    un = torch.from_numpy(rng.random((N, 2)).astype(np.float32))
+    table = random_table(V, k, seed=V + 1)
+    for delta in (0.0, 0.2):
+        acc_o, res_o = _rows_all_modes(oracle_mod, lantern_gpu, st, row_index, tokens, un, table, delta)
+        n_o, path_o, next_o, _ = _expected_tree_outputs(oracle_mod, acc_o, res_o, parent, M)
+        acc, n, path, nxt = lantern_gpu.verify_trees(t.cuda(), g.cuda(), torch.from_numpy(row_index).cuda(),
+                                                     torch.from_numpy(parent).cuda().reshape(-1), M,
+                                                     torch.from_numpy(tokens).cuda(), torch.from_numpy(table).cuda(),
+                                                     delta, un.cuda())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
