@@ -33,7 +33,9 @@
  *     allocates nothing, frees nothing and keeps no state between calls that
  *     a result could depend on.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default
- *     stream).  Calls only enqueue kernels; they do not synchronise.
+ *     stream).  Calls only enqueue kernels; they do not synchronise.  The
+ *     current HIP device must be the one that owns the pointers and the
+ *     stream.  Calls may come from several host threads.
  *   - The return value is a lantern_status.  Argument errors are found on the
  *     host before anything is launched; then nothing is written.
  *   - Row-level problems that only the device can see (see lantern_verify) are
