@@ -265,3 +265,41 @@ def test_stream_read_probe(lantern_gpu):
     assert lib.lantern_probe_stream_read(src.data_ptr() + 4, None, 65536, sink.data_ptr(), None) == -2
     torch.cuda.synchronize()
     assert torch.equal(src, keep)
+
+
+def test_concurrent_host_threads(oracle_mod, lantern_gpu):
+    """Several host threads, each on a stream of its own, call the library at once (ctypes drops the
+    interpreter lock during a call); every result must equal the oracle's."""
+    import threading
+    cfg = workloads.CONFIGS["llamagen_step"]
+    table = random_table(cfg.V, cfg.k, seed=77)
+    tb = torch.from_numpy(table).cuda()
+    steps = [workloads.make_step(cfg, step=60 + i, rows=64, variant=("plain", "reject", "peaked")[i % 3])
+             for i in range(4)]
+    deltas = [0.4, 0.0, 0.01, 0.2]
+    want = [oracle_mod.verify(s.target_logits, s.draft_logits, s.draft_tokens, table, cfg.k, d, s.uniforms,
+                              threads=4, want_diag=False)[:2] for s, d in zip(steps, deltas)]
+    dev = [(s.target_logits.cuda(), s.draft_logits.cuda(), s.draft_tokens.cuda(), s.uniforms.cuda()) for s in steps]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            stream = torch.cuda.Stream()
+            t, g, tok, un = dev[i]
+            for _ in range(15):
+                acc, res = lantern_gpu.verify(t, g, tok, tb, deltas[i], un, stream=stream)
+                dacc = lantern_gpu.decide_rows(t, g, None, tok, tb, deltas[i], un, stream=stream)
+                stream.synchronize()
+                if not (np.array_equal(acc.cpu().numpy(), want[i][0]) and np.array_equal(res.cpu().numpy(), want[i][1])
+                        and np.array_equal(dacc.cpu().numpy(), want[i][0])):
+                    errors.append(i)
+        except Exception as exc:   # noqa: BLE001
+            errors.append(repr(exc))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
