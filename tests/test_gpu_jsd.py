@@ -65,3 +65,23 @@ def test_unknown_divergence_is_rejected(lantern_gpu):
     rc = lib.lantern_verify_divergence(p, p, 0, 4, 16, 16, p, p, 4, 7, 0.1, p, p, p, None, None, None, None, None,
                                        None)
     assert rc == lantern_gpu.binding.E_SHAPE
+
+
+@pytest.mark.parametrize("divergence,delta", [("tvd", 0.3), ("jsd", 0.15), ("tvd", 0.9), ("jsd", 0.6)])
+def test_cut_beyond_the_first_1024_slots(oracle_mod, lantern_gpu, divergence, delta):
+    """Long neighbourhoods: the walk passes the 1024 slots the workgroup scans together and ends (or
+    does not end) in the part one wavefront walks alone."""
+    V, k, N = 8192, 4000, 24
+    rng = np.random.default_rng(11)
+    t = torch.from_numpy((rng.standard_normal((N, V)) * 1.0).astype(np.float32)).to(torch.bfloat16)
+    g = (t.float() + torch.from_numpy(rng.standard_normal((N, V)).astype(np.float32) * 0.5)).to(torch.bfloat16)
+    tokens = torch.from_numpy(rng.integers(0, V, N).astype(np.int32))
+    table = random_table(V, k, seed=21)
+    un = torch.from_numpy(philox.uniforms(5, N))
+    acc, res, diag, gout = compare_verify(oracle_mod, lantern_gpu, t, g, tokens, table, delta, un,
+                                          label=f"long walk {divergence}", divergence=divergence)
+    sizes = diag["a_size"]
+    assert (sizes > 1024).any()
+    if delta < 0.5:
+        assert (sizes < k).any()          # the cut itself lies beyond slot 1024
+    assert (gout["path"] == 0).any()      # and the fp32 pass settles such rows
