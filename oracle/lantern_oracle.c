@@ -183,6 +183,21 @@ enum {
 
 int oracle_diag_count(void) { return DIAG_COUNT; }
 
+/* Jensen-Shannon divergence (natural logarithm, Section 5.3.2) between a distorted target ta and
+ * the target t, from the definition over the whole vocabulary:
+ *     1/2 KL(ta || m) + 1/2 KL(t || m),   m = (ta + t) / 2,   0 ln 0 = 0.
+ * Entries where the two agree have m equal to both, so both logarithms are ln 1 = 0 exactly. */
+static double jsd_full(const double* ta, const double* t, int V) {
+    double kl_a = 0.0, kl_t = 0.0;
+    for (int x = 0; x < V; ++x) {
+        if (ta[x] == t[x]) continue;
+        double m = 0.5 * (ta[x] + t[x]);
+        if (ta[x] > 0.0) kl_a = kl_a + ta[x] * log(ta[x] / m);
+        if (t[x] > 0.0) kl_t = kl_t + t[x] * log(t[x] / m);
+    }
+    return 0.5 * kl_a + 0.5 * kl_t;
+}
+
 /*
  * t, g: probability vectors of length V.  nbrs: the k table entries of row xt,
  * nearest first.  scratch: V doubles.
@@ -203,26 +218,6 @@ int oracle_diag_count(void) { return DIAG_COUNT; }
  *     A residual with no mass at all falls back to sampling t_A.
  * optional outputs (may be NULL): rho_out[V] normalised residual, ta_out[V].
  */
-/* Jensen-Shannon divergence (natural logarithm) between the distorted target induced by a set A
- * and the target itself, from the definition 1/2 KL(t_A || m) + 1/2 KL(t || m), m = (t_A + t)/2,
- * restricted to the entries where the two differ: at xt the pair is (mass, t0); at a member x of
- * A other than xt it is (0, t(x)), whose term is 1/2 t(x) ln(t(x) / (t(x)/2)); everywhere else
- * both are equal and the terms vanish.  moved = sum of t over A without xt; 0 ln 0 = 0. */
-static double jsd_of_prefix(double t0, double moved) {
-    double mass = t0 + moved;
-    double mid = 0.5 * (mass + t0);
-    double kl_a = mass > 0.0 ? mass * log(mass / mid) : 0.0;
-    double kl_t = t0 > 0.0 ? t0 * log(t0 / mid) : 0.0;
-    double members = moved * log(2.0);
-    return 0.5 * kl_a + 0.5 * (kl_t + members);
-}
-
-/* divergence 0: total variation distance (Section 4.3); 1: Jensen-Shannon divergence
- * (ablation of Section 5.3.2).  Returns the divergence of the prefix that moves `moved`. */
-static double prefix_divergence(int divergence, double t0, double moved) {
-    return divergence == 0 ? moved : jsd_of_prefix(t0, moved);
-}
-
 static void verify_probs(const double* t, const double* g, int V, int xt,
                          const int32_t* nbrs, int k, int divergence, double delta,
                          double u_acc, double u_res,
@@ -232,6 +227,11 @@ static void verify_probs(const double* t, const double* g, int V, int xt,
     double d_tv = 0.0;
     int a = 0;
     double margin_cut = INFINITY;
+    /* divergence 0: total variation distance (Section 4.3), which for a prefix is the mass it
+     * moves onto xt.  divergence 1: Jensen-Shannon (ablation of Section 5.3.2), evaluated on the
+     * candidate's distorted target itself, kept in `scratch` while walking. */
+    double* cand_ta = scratch;
+    if (divergence != 0) memcpy(cand_ta, t, sizeof(double) * (size_t)V);
     for (int j = 0; j < k; ++j) {
         int x = nbrs[j];
         if (x == xt) {
@@ -240,7 +240,14 @@ static void verify_probs(const double* t, const double* g, int V, int xt,
         }
         double inc = t[x];
         double cand = d_tv + inc;                       /* mass moved onto xt if x is taken */
-        double div = prefix_divergence(divergence, t[xt], cand);
+        double div;
+        if (divergence == 0) {
+            div = cand;
+        } else {
+            cand_ta[x] = 0.0;
+            cand_ta[xt] = t[xt] + cand;
+            div = jsd_full(cand_ta, t, V);
+        }
         double mg = fabs(div - delta);
         if (mg < margin_cut) margin_cut = mg;
         if (div < delta) {
