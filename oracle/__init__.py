@@ -88,6 +88,14 @@ def _as_i32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def _abi_delta(delta) -> float:
+    """The bound as the library's C ABI carries it: a binary32 number.  The logits-level
+    entry points below take their inputs in the ABI's types (fp32 / bf16 logits, fp32
+    uniforms, a binary32 delta) and widen each of them exactly to fp64; the decision rule is
+    then evaluated on that value, so 0.4 means 0.4000000059604645, on both sides."""
+    return float(np.float32(delta))
+
+
 def _p(a: np.ndarray, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct))
 
@@ -173,7 +181,7 @@ def verify(target_logits, draft_logits, draft_tokens, knn, k: int, delta: float,
     diag = np.empty((N, len(DIAG_NAMES)), dtype=np.float64) if want_diag else None
     rc = lib.oracle_verify_div(_p(tl, ctypes.c_float), _p(dl, ctypes.c_float), N, V, V,
                            _p(tok, ctypes.c_int32), _p(tab, ctypes.c_int32), int(k), DIVERGENCES[divergence],
-                           float(delta),
+                           _abi_delta(delta),
                            _p(un, ctypes.c_float), _p(acc, ctypes.c_int32), _p(res, ctypes.c_int32),
                            _p(diag, ctypes.c_double) if want_diag else None, int(threads))
     if rc != 0:
@@ -198,7 +206,7 @@ def verify_greedy(target_logits, draft_tokens, knn, k: int, delta: float, thread
     out = np.empty(N, dtype=np.int32)
     diag = np.empty((N, 3), dtype=np.float64)
     rc = lib.oracle_verify_greedy(_p(tl, ctypes.c_float), N, V, V, _p(tok, ctypes.c_int32),
-                                  _p(tab, ctypes.c_int32), int(k), float(delta), _p(acc, ctypes.c_int32),
+                                  _p(tab, ctypes.c_int32), int(k), _abi_delta(delta), _p(acc, ctypes.c_int32),
                                   _p(out, ctypes.c_int32), _p(diag, ctypes.c_double), int(threads))
     if rc != 0:
         raise ValueError("oracle_verify_greedy: bad arguments")

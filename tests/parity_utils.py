@@ -73,3 +73,18 @@ def compare_verify(oracle, lantern, target, draft, tokens, table, delta, uniform
         np.testing.assert_allclose(g[name][ok], ref[ok], rtol=tol, atol=1e-30, err_msg=f"{label} {name}")
     assert np.all(np.isnan(g["accept_prob"][~ok]))
     return acc_o, res_o, diag, g
+
+
+def delta_window_row():
+    """A two-token row whose only neighbour carries t = 0.40000000285: at or above the double 0.4
+    and below the binary32 number nearest to 0.4 (0.4000000059604645), the value the C ABI's
+    `float delta` carries.  Returns (target logits [1,2] fp32, draft logits, tokens, table, uniforms);
+    with delta = 0.4 the neighbour is taken (|A| = 2) exactly when the bound is read as binary32."""
+    target = torch.tensor([[0.0, -0.40546509623527527]], dtype=torch.float32)
+    p1 = float(np.exp(np.float64(target[0, 1].item())) / (1.0 + np.exp(np.float64(target[0, 1].item()))))
+    assert 0.4 < p1 < float(np.float32(0.4))
+    draft = torch.tensor([[0.0, 0.0]], dtype=torch.float32)
+    tokens = torch.tensor([0], dtype=torch.int32)
+    table = np.array([[0, 1], [1, 0]], dtype=np.int32)
+    uniforms = torch.tensor([[0.75, 0.5]], dtype=torch.float32)
+    return target, draft, tokens, table, uniforms

@@ -283,3 +283,18 @@ def test_philox_known_answers():
     u = philox.uniforms(7, 1000)
     assert u.dtype == np.float32 and u.min() >= 0.0 and u.max() < 1.0
     assert np.all(u * 2.0 ** 24 == np.round(u * 2.0 ** 24))
+
+
+def test_delta_is_the_binary32_value_of_the_abi(oracle_mod):
+    """The logits-level oracle reads the bound as the binary32 number the C ABI carries: a prefix
+    whose TVD lies between the double 0.4 and float32(0.4) is inside the bound; on explicit
+    probabilities (fp64 interface) the same prefix is refused at the double 0.4."""
+    from parity_utils import delta_window_row
+    target, draft, tokens, table, un = delta_window_row()
+    acc, res, diag = oracle_mod.verify(target, draft, tokens, table, 2, 0.4, un)
+    assert diag["a_size"][0] == 2 and diag["mass"][0] == pytest.approx(1.0, abs=1e-15)
+    t = oracle_mod.softmax(target[0])
+    r = oracle_mod.verify_probs(t, [0.5, 0.5], 0, [0, 1], 0.4, 0.75, 0.5)
+    assert r["a_size"] == 1
+    r = oracle_mod.verify_probs(t, [0.5, 0.5], 0, [0, 1], float(np.float32(0.4)), 0.75, 0.5)
+    assert r["a_size"] == 2
