@@ -36,6 +36,11 @@
  *     stream).  Calls only enqueue kernels; they do not synchronise.  The
  *     current HIP device must be the one that owns the pointers and the
  *     stream.  Calls may come from several host threads.
+ *   - One exception to "only enqueue": the first time a kernel needs more
+ *     than 64 KiB of LDS on a device, its limit is raised with a runtime call
+ *     (hipFuncSetAttribute), and the runtime loads a kernel on its first use.
+ *     Neither belongs inside a stream capture: call lantern_prepare for the
+ *     shape beforehand, or make one call of the shape outside the capture.
  *   - The return value is a lantern_status.  Argument errors are found on the
  *     host before anything is launched; then nothing is written.
  *   - Row-level problems that only the device can see (see lantern_verify) are
@@ -87,8 +92,8 @@ typedef enum {
 size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k);
 
 /*
- * Neighbour table of the codebook (Section 4.2: "B_k(x): the k nearest tokens
- * to x in latent space, including x itself"; Algorithm 2, precompute part).
+ * Neighbour table of the codebook: row x lists x and the k-1 codes closest to
+ * it in latent space (B_k of Section 4.2; Algorithm 2, precompute part).
  *
  *   codebook   [V, d] row-major, dtype cb_dtype, device memory, 16-byte aligned
  *   out_knn    [V, k] row-major int32, device memory.  Row i holds i itself in
@@ -134,15 +139,20 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
  *   draft_tokens [N] int32
  *   knn          [V, k] int32 neighbour table (entries of a row distinct)
  *   delta        TVD bound, >= 0.  delta = 0 or k = 1 gives standard
- *                speculative acceptance min(1, t(xt)/g(xt)).
+ *                speculative acceptance min(1, t(xt)/g(xt)).  The bound IS the
+ *                binary32 number passed here, widened exactly where the rule
+ *                is evaluated in fp64: a caller who writes 0.4 gets the bound
+ *                0.4000000059604645 (the float nearest to 0.4), and a prefix
+ *                whose TVD lies between 0.4 and that number is inside it.
  *   uniforms     [N, 2] float32 in [0,1): column 0 acceptance draw, column 1
  *                resampling draw.  The library draws no random numbers.
  *   out_accept   [N] int32: 1 accepted, 0 rejected
  *   out_resample [N] int32: resampled token when rejected, -1 when accepted
  *
- * Rows the device finds unusable - draft token or a table entry outside
- * [0,V), a NaN or +inf logit, or no finite logit - get out_accept = -1 and
- * out_resample = -1; other rows are unaffected.
+ * Rows the device finds unusable - draft token outside [0,V), any of the k
+ * entries of its table row outside [0,V) (all k are checked, also those the
+ * walk never reaches), a NaN or +inf logit, or no finite logit - get
+ * out_accept = -1 and out_resample = -1; other rows are unaffected.
  *
  * Decisions are exact with respect to fp64 evaluation of the rule above: a
  * fast fp32 pass settles every row whose comparisons clear a proven rounding
@@ -394,6 +404,19 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
  */
 int lantern_probe_stream_read(const void* src_a, const void* src_b, size_t bytes, uint32_t* sink,
                               void* hip_stream);
+
+/*
+ * Set-up for callers that record calls into a HIP graph (or want the first
+ * call of a shape to cost what the later ones do): on the current device,
+ * loads the kernels and raises the LDS limit of every kernel that the
+ * verification entry points above (sampling, greedy, rows, decide, selected,
+ * trees, chain and tree walks) can launch for this logit type, vocabulary size
+ * and table width, whatever the alignment of the buffers turns out to be.
+ * Enqueues nothing; must itself be called outside a stream capture; once per
+ * device and shape is enough, repeating it is harmless.
+ * Errors: E_DTYPE, E_SHAPE (V < 1, V > LANTERN_MAX_VOCAB, k < 1, k > V), E_DEVICE.
+ */
+int lantern_prepare(lantern_dtype logits_dtype, int V, int k);
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char* lantern_status_string(int status);

@@ -25,7 +25,7 @@ EXPORTS = (
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
-    "lantern_verify_trees_greedy", "lantern_probe_stream_read",
+    "lantern_verify_trees_greedy", "lantern_probe_stream_read", "lantern_prepare",
     "lantern_status_string",
     "lantern_version",
 )
@@ -89,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_probe_stream_read.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
     lib.lantern_build_random.restype = i32
+    lib.lantern_prepare.argtypes = [i32, i32, i32]
+    lib.lantern_prepare.restype = i32
     lib.lantern_status_string.argtypes = [i32]
     lib.lantern_status_string.restype = ctypes.c_char_p
     lib.lantern_version.argtypes = []
@@ -107,6 +109,16 @@ def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return BF16
     raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16 expected")
+
+
+def prepare(logits_dtype, V: int, k: int) -> None:
+    """lantern_prepare: raises the LDS limits of every verification kernel for this logit dtype
+    (torch.float32 / torch.bfloat16), vocabulary size and table width on the current device, so that
+    later calls make no runtime call besides their launches (needed before stream capture)."""
+    code = {torch.float32: F32, torch.bfloat16: BF16}[logits_dtype]
+    rc = load().lantern_prepare(code, int(V), int(k))
+    if rc != OK:
+        raise LanternError(rc, "lantern_prepare")
 
 
 def _stream_ptr(stream) -> int:

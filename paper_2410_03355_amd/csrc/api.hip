@@ -300,6 +300,15 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
     return lantern_accept_trees(out_accept, out_token, parent, B, M, out_len, out_path, out_next, hip_stream);
 }
 
+int lantern_prepare(lantern_dtype logits_dtype, int V, int k) {
+    if (!dtype_ok((int)logits_dtype)) return LANTERN_E_DTYPE;
+    if (V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V) return LANTERN_E_SHAPE;
+    hipError_t e = lantern::prepare_verify((int)logits_dtype, V, k);
+    if (e == hipSuccess) e = lantern::prepare_greedy((int)logits_dtype, V, k);
+    if (e == hipSuccess) e = lantern::prepare_walks();
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 const char* lantern_status_string(int status) {
     switch (status) {
         case LANTERN_OK: return "ok";
@@ -313,6 +322,6 @@ const char* lantern_status_string(int status) {
     }
 }
 
-int lantern_version(void) { return 100; }
+int lantern_version(void) { return 200; }
 
 }  // extern "C"

@@ -54,6 +54,13 @@ __global__ __launch_bounds__(NT) void accept_trees_kernel(const int32_t* accept,
     }
 }
 
+// Makes the runtime load this file's kernels on the current device (it defers that to a kernel's
+// first use), so that their first launch can be recorded into a graph.
+hipError_t prepare_walks() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&accept_chains_kernel));
+}
+
 hipError_t launch_accept_trees(const int32_t* accept, const int32_t* resample, const int32_t* parent, int B,
                                int M, int32_t* out_len, int32_t* out_path, int32_t* out_next,
                                hipStream_t stream) {

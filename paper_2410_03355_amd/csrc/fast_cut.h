@@ -25,9 +25,12 @@ struct ScanLds {
     int* wbad;
 };
 
-// All threads, before the barrier.  nb: table slots 4*tid .. 4*tid+3 (0 beyond k).
+// All threads, before the barrier.  nb: table slots 4*tid .. 4*tid+3 (0 beyond k); nrow: the
+// token's table row.  Every one of the k entries is range-checked here, also those beyond the
+// first 1024 slots that the walk may never reach: a row with an entry outside [0, V) is unusable
+// wherever its cut falls.
 template <typename LT>
-__device__ __forceinline__ void scan_publish(const int (&nb)[4], int xt, int k, int V,
+__device__ __forceinline__ void scan_publish(const int (&nb)[4], int xt, int k, int V, const int32_t* nrow,
                                              const unsigned char* s_row, float ct, const ScanLds& lds) {
     using L = Lane<LT>;
     const int tid = threadIdx.x;
@@ -49,6 +52,8 @@ __device__ __forceinline__ void scan_publish(const int (&nb)[4], int xt, int k, 
         run += e;
         p[q] = run;
     }
+    for (int j = NT * 4 + tid; j < k; j += NT)
+        if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
     const float incl = wave_scan_incl(run);
     const float excl = wave_prev(incl, 0.f);
     reinterpret_cast<float4*>(lds.gs)[tid] = make_float4(excl + p[0], excl + p[1], excl + p[2], excl + p[3]);
@@ -89,8 +94,11 @@ struct SlotTest {
         } else {
             const float mass = e_tx + I;
             const float mid = 0.5f * (mass + e_tx);
+            // a ratio below the smallest normal number is flushed to zero and its logarithm is
+            // -inf; the term x ln(x / mid) it stands for is below 1e-36 * mid: taken as zero
+            const float ratio = e_tx / mid;
             const float kl_a = mass > 0.f ? mass * __logf(mass / mid) : 0.f;
-            const float kl_t = e_tx > 0.f ? e_tx * __logf(e_tx / mid) : 0.f;
+            const float kl_t = ratio >= 1.1754944e-38f ? e_tx * __logf(ratio) : 0.f;
             const float J = 0.5f * kl_a + 0.5f * (kl_t + I * 0.69314718f);
             const float err = 0.7f * (8.0e-6f * I + 3.0e-6f * e_tx) + 1.0e-6f * (e_tx + I);
             *passes = J + err < lo;

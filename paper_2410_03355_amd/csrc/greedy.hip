@@ -257,7 +257,7 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     st = wave_sum(st);
     emax = wave_max(emax);
     const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
-    scan_publish<LT>(nb, xt, k, V, s_row, ct, scan);
+    scan_publish<LT>(nb, xt, k, V, nrow, s_row, ct, scan);
     if (lane == 0) { sh.wsum[wave] = st; sh.wemax[wave] = emax; }
     __syncthreads();
 
@@ -347,14 +347,15 @@ __global__ __launch_bounds__(NT) void greedy_exact(GreedyArgs a) {
     greedy_exact_row<LT, false>(a, verification_of_block(blockIdx.x, a.N, a.row_index != nullptr), smem, nullptr);
 }
 
+// launch == false: only the LDS limit is raised (lantern_prepare), nothing is enqueued.
 template <typename LT, int NV>
-static hipError_t launch_greedy_nv(const GreedyArgs& a, hipStream_t stream) {
+static hipError_t launch_greedy_nv(const GreedyArgs& a, hipStream_t stream, bool launch) {
     const size_t row_bytes = ((size_t)a.V * sizeof(LT) + 15) & ~size_t(15);
     const size_t tail = greedy_exact_lds_bytes(a.V) > GREEDY_SHARED_TAIL ? greedy_exact_lds_bytes(a.V) : GREEDY_SHARED_TAIL;
     const size_t lds = row_bytes + GREEDY_SHARED_HEAD + tail;
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    const hipError_t e = full ? allow_lds(&greedy_fast<LT, NV, true>, lds) : allow_lds(&greedy_fast<LT, NV, false>, lds);
-    if (e != hipSuccess) return e;
+    const hipError_t e = full ? allow_lds<&greedy_fast<LT, NV, true>>(lds) : allow_lds<&greedy_fast<LT, NV, false>>(lds);
+    if (e != hipSuccess || !launch) return e;
     if (full)
         hipLaunchKernelGGL((greedy_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
     else
@@ -363,23 +364,50 @@ static hipError_t launch_greedy_nv(const GreedyArgs& a, hipStream_t stream) {
 }
 
 template <typename LT>
-static hipError_t launch_greedy_typed(const GreedyArgs& a, hipStream_t stream) {
+static hipError_t launch_greedy_fast(const GreedyArgs& a, hipStream_t stream, bool launch) {
+    const int nvec = a.V / Lane<LT>::EPV;
+    const int nv = (nvec + NT - 1) / NT;
+    if (nv <= 1) return launch_greedy_nv<LT, 1>(a, stream, launch);
+    if (nv <= 2) return launch_greedy_nv<LT, 2>(a, stream, launch);
+    if (nv <= 4) return launch_greedy_nv<LT, 4>(a, stream, launch);
+    if (nv <= 8) return launch_greedy_nv<LT, 8>(a, stream, launch);
+    return launch_greedy_nv<LT, 16>(a, stream, launch);
+}
+
+template <typename LT>
+static bool greedy_fast_shape(int V, int k) {
     constexpr int EPV = Lane<LT>::EPV;
+    return (V % EPV) == 0 && (V / EPV + NT - 1) / NT <= 16 && k <= FAST_MAX_K;
+}
+
+template <typename LT>
+static hipError_t launch_greedy_typed(const GreedyArgs& a, hipStream_t stream) {
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | (uintptr_t)(a.stride * (int64_t)sizeof(LT));
-    if ((align & 15) == 0 && (a.V % EPV) == 0 && a.k <= FAST_MAX_K) {
-        const int nvec = a.V / EPV;
-        const int nv = (nvec + NT - 1) / NT;
-        if (nv <= 1) return launch_greedy_nv<LT, 1>(a, stream);
-        if (nv <= 2) return launch_greedy_nv<LT, 2>(a, stream);
-        if (nv <= 4) return launch_greedy_nv<LT, 4>(a, stream);
-        if (nv <= 8) return launch_greedy_nv<LT, 8>(a, stream);
-        if (nv <= 16) return launch_greedy_nv<LT, 16>(a, stream);
-    }
+    if ((align & 15) == 0 && greedy_fast_shape<LT>(a.V, a.k)) return launch_greedy_fast<LT>(a, stream, true);
     const size_t lds = greedy_exact_lds_bytes(a.V);
-    const hipError_t e = allow_lds(&greedy_exact<LT>, lds);
+    const hipError_t e = allow_lds<&greedy_exact<LT>>(lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((greedy_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
+}
+
+template <typename LT>
+static hipError_t prepare_greedy_typed(int V, int k) {
+    hipFuncAttributes attr;   // loads this file's kernels on the current device
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&greedy_exact<LT>));
+    if (e != hipSuccess) return e;
+    if (greedy_fast_shape<LT>(V, k)) {
+        GreedyArgs a{};
+        a.V = V;
+        a.k = k;
+        e = launch_greedy_fast<LT>(a, nullptr, false);
+    }
+    if (e == hipSuccess) e = allow_lds<&greedy_exact<LT>>(greedy_exact_lds_bytes(V));
+    return e;
+}
+
+hipError_t prepare_greedy(int logits_dtype, int V, int k) {
+    return logits_dtype == 0 ? prepare_greedy_typed<float>(V, k) : prepare_greedy_typed<uint16_t>(V, k);
 }
 
 hipError_t launch_verify_greedy(const GreedyArgs& a, int logits_dtype, hipStream_t stream) {

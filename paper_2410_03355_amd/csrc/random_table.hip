@@ -139,7 +139,7 @@ __global__ __launch_bounds__(NT) void random_rows_kernel(int V, int k, uint32_t 
 
 hipError_t launch_build_random(int V, int k, uint64_t seed, uint64_t t0, int32_t* out, hipStream_t stream) {
     const size_t lds = sizeof(RandomShared) + (size_t)CAP * sizeof(uint64_t);
-    const hipError_t e = allow_lds(&random_rows_kernel, lds);
+    const hipError_t e = allow_lds<&random_rows_kernel>(lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(random_rows_kernel, dim3(V), dim3(NT), lds, stream, V, k, (uint32_t)(seed & 0xFFFFFFFFu),
                        (uint32_t)(seed >> 32), t0, out);

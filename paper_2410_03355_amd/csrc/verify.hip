@@ -187,7 +187,7 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
 
         // ---- neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront ----
         const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
-        scan_publish<LT>(m.nb, xt, k, V, s_row, ct, scan);
+        scan_publish<LT>(m.nb, xt, k, V, a.knn + (int64_t)xs * k, s_row, ct, scan);
         if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; }
         __syncthreads();  // sums and neighbour partial sums are published
 
@@ -209,9 +209,10 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             const float MA = e_tx + S;                // mass * Zt
             const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
             const float rhs = MA * Zg;                // mass  * Zt * Zg
-            const bool accept = (lhs + ACC_SLACK) < rhs * (1.f - TAU_ACC);
+            const float slack = acc_slack(k);
+            const bool accept = (lhs + slack) < rhs * (1.f - TAU_ACC);
             // a definite rejection settles the row only when no resampled token is asked for
-            const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + ACC_SLACK);
+            const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + slack);
             // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
             const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
             const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
@@ -609,12 +610,13 @@ static size_t fast_lds_bytes(int V) {
     return row_bytes + FAST_SHARED_HEAD + tail;
 }
 
+// launch == false: only the LDS limits are raised (lantern_prepare), nothing is enqueued.
 template <typename LT, int NV>
-static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
+static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream, bool launch) {
     const size_t lds = fast_lds_bytes<LT>(a.V);
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    const hipError_t e = full ? allow_lds(&verify_fast<LT, NV, true>, lds) : allow_lds(&verify_fast<LT, NV, false>, lds);
-    if (e != hipSuccess) return e;
+    const hipError_t e = full ? allow_lds<&verify_fast<LT, NV, true>>(lds) : allow_lds<&verify_fast<LT, NV, false>>(lds);
+    if (e != hipSuccess || !launch) return e;
     if (full)
         hipLaunchKernelGGL((verify_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
     else
@@ -623,39 +625,54 @@ static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream) {
 }
 
 template <typename LT>
-static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
+static hipError_t launch_fast(const VerifyArgs& a, hipStream_t stream, bool launch) {
+    const int nvec = a.V / Lane<LT>::EPV;
+    const int nv = (nvec + NT - 1) / NT;
+    if (nv <= 1) return launch_fast_nv<LT, 1>(a, stream, launch);
+    if (nv <= 2) return launch_fast_nv<LT, 2>(a, stream, launch);
+    if (nv <= 4) return launch_fast_nv<LT, 4>(a, stream, launch);
+    if (nv <= 8) return launch_fast_nv<LT, 8>(a, stream, launch);
+    return launch_fast_nv<LT, 16>(a, stream, launch);
+}
+
+// Rows the fp32 pass covers: whole 16-byte vectors, at most 16 per thread, k within the scan's depth.
+template <typename LT>
+static bool fast_shape(int V, int k) {
     constexpr int EPV = Lane<LT>::EPV;
+    return (V % EPV) == 0 && (V / EPV + NT - 1) / NT <= 16 && k <= FAST_MAX_K;
+}
+
+template <typename LT>
+static hipError_t launch_typed(const VerifyArgs& a, hipStream_t stream) {
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
                             (uintptr_t)(a.stride * (int64_t)sizeof(LT));
-    if ((align & 15) == 0 && (a.V % EPV) == 0 && a.k <= FAST_MAX_K) {
-        const int nvec = a.V / EPV;
-        const int nv = (nvec + NT - 1) / NT;
-        if (nv <= 1) return launch_fast_nv<LT, 1>(a, stream);
-        if (nv <= 2) return launch_fast_nv<LT, 2>(a, stream);
-        if (nv <= 4) return launch_fast_nv<LT, 4>(a, stream);
-        if (nv <= 8) return launch_fast_nv<LT, 8>(a, stream);
-        if (nv <= 16) return launch_fast_nv<LT, 16>(a, stream);
-    }
+    if ((align & 15) == 0 && fast_shape<LT>(a.V, a.k)) return launch_fast<LT>(a, stream, true);
     const size_t lds = exact_lds_bytes(a.V);
-    const hipError_t e = allow_lds(&verify_exact<LT>, lds);
+    const hipError_t e = allow_lds<&verify_exact<LT>>(lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((verify_exact<LT>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
+}
+
+// LDS of the 512-thread kernels; *stage: both logit rows fit beside the exact path's data.
+template <typename LT>
+static size_t selected_lds_bytes(int V, bool vec, int* stage) {
+    const size_t lds = exact_lds_bytes(V, SEL_NT);
+    const size_t staged = ((lds + 15) & ~size_t(15)) + 2 * (((size_t)V * sizeof(LT) + 15) & ~size_t(15));
+    *stage = (vec && staged <= 150 * 1024) ? 1 : 0;
+    return *stage ? staged : lds;
 }
 
 template <typename LT>
 static hipError_t launch_selected_typed(const VerifyArgs& a_in, const int32_t* parent, int M, int32_t* out_len,
                                         int32_t* out_path, hipStream_t stream) {
     VerifyArgs a = a_in;
-    size_t lds = exact_lds_bytes(a.V, SEL_NT);
     const uintptr_t align = reinterpret_cast<uintptr_t>(a.target) | reinterpret_cast<uintptr_t>(a.draft) |
                             (uintptr_t)(a.stride * (int64_t)sizeof(LT));
     const bool vec = (align & 15) == 0 && (a.V % EXV) == 0;   // rows 16-byte aligned, whole vectors
-    const size_t staged = ((lds + 15) & ~size_t(15)) + 2 * (((size_t)a.V * sizeof(LT) + 15) & ~size_t(15));
-    a.stage_rows = (vec && staged <= 150 * 1024) ? 1 : 0;      // both rows beside the exact path's data
-    if (a.stage_rows) lds = staged;
+    const size_t lds = selected_lds_bytes<LT>(a.V, vec, &a.stage_rows);
     if (parent) {   // walk and draw in one launch, one workgroup per tree
-        const hipError_t e = vec ? allow_lds(&tree_finish<LT, true>, lds) : allow_lds(&tree_finish<LT, false>, lds);
+        const hipError_t e = vec ? allow_lds<&tree_finish<LT, true>>(lds) : allow_lds<&tree_finish<LT, false>>(lds);
         if (e != hipSuccess) return e;
         if (vec)
             hipLaunchKernelGGL((tree_finish<LT, true>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a, parent, M, out_len,
@@ -665,13 +682,47 @@ static hipError_t launch_selected_typed(const VerifyArgs& a_in, const int32_t* p
                                out_path);
         return hipGetLastError();
     }
-    const hipError_t e = vec ? allow_lds(&resample_selected<LT, true>, lds) : allow_lds(&resample_selected<LT, false>, lds);
+    const hipError_t e = vec ? allow_lds<&resample_selected<LT, true>>(lds) : allow_lds<&resample_selected<LT, false>>(lds);
     if (e != hipSuccess) return e;
     if (vec)
         hipLaunchKernelGGL((resample_selected<LT, true>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a);
     else
         hipLaunchKernelGGL((resample_selected<LT, false>), dim3(a.n_sel), dim3(SEL_NT), lds, stream, a);
     return hipGetLastError();
+}
+
+// Raises, on the current device, the LDS limit of every kernel a verification of this vocabulary
+// size and logit type can launch, whatever the alignment of the caller's buffers turns out to be.
+template <typename LT>
+static hipError_t prepare_typed(int V, int k) {
+    // the runtime defers loading a file's kernels to their first use: make that happen now
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&verify_exact<LT>));
+    if (e != hipSuccess) return e;
+    if (fast_shape<LT>(V, k)) {
+        VerifyArgs a{};
+        a.V = V;
+        a.k = k;
+        e = launch_fast<LT>(a, nullptr, false);
+    }
+    if (e == hipSuccess) e = allow_lds<&verify_exact<LT>>(exact_lds_bytes(V));
+    for (int vec = 0; vec < 2 && e == hipSuccess; ++vec) {
+        if (vec && (V % EXV) != 0) break;
+        int stage;
+        const size_t lds = selected_lds_bytes<LT>(V, vec != 0, &stage);
+        if (vec) {
+            e = allow_lds<&tree_finish<LT, true>>(lds);
+            if (e == hipSuccess) e = allow_lds<&resample_selected<LT, true>>(lds);
+        } else {
+            e = allow_lds<&tree_finish<LT, false>>(lds);
+            if (e == hipSuccess) e = allow_lds<&resample_selected<LT, false>>(lds);
+        }
+    }
+    return e;
+}
+
+hipError_t prepare_verify(int logits_dtype, int V, int k) {
+    return logits_dtype == 0 ? prepare_typed<float>(V, k) : prepare_typed<uint16_t>(V, k);
 }
 
 hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipStream_t stream) {

@@ -51,6 +51,10 @@ hipError_t launch_resample_selected(const VerifyArgs& a, int logits_dtype, hipSt
 hipError_t launch_tree_finish(const VerifyArgs& a, const int32_t* parent, int M, int32_t* out_len, int32_t* out_path,
                               int logits_dtype, hipStream_t stream);
 
+// Raises the dynamic-LDS limits of every kernel the calls above can launch for this logit type,
+// vocabulary size and table width on the current device; enqueues nothing.
+hipError_t prepare_verify(int logits_dtype, int V, int k);
+
 }  // namespace lantern
 
 namespace lantern {
@@ -73,10 +77,13 @@ struct GreedyArgs {
 };
 
 hipError_t launch_verify_greedy(const GreedyArgs& a, int logits_dtype, hipStream_t stream);
+hipError_t prepare_greedy(int logits_dtype, int V, int k);
 
 }  // namespace lantern
 
 namespace lantern {
+
+hipError_t prepare_walks();   // loads the walk kernels on the current device
 
 hipError_t launch_accept_chains(const int32_t* accept, const int32_t* resample, int B, int L,
                                 int32_t* out_len, int32_t* out_next, hipStream_t stream);

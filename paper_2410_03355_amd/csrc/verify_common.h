@@ -54,9 +54,10 @@ constexpr float TAU_ACC = 3.0e-5f;
 // v_exp_f32 flushes results below 2^-126; absolute slack for products of such
 // terms with sums bounded by V.
 constexpr float ABS_SLACK = 1.0e-30f;
-// The acceptance test multiplies such terms by a row sum (up to 2^46): a flushed term of the
-// token (below 1.2e-38) or of A (below k * 1.2e-38) then moves a side by at most 1e-21.
-constexpr float ACC_SLACK = 1.0e-21f;
+// The acceptance test multiplies such terms by a row sum (up to 2^46 = 7e13): every flushed term
+// (below 1.18e-38: the token's own on either side, up to k - 1 of them in the sum over A) moves a
+// side by less than 8.3e-25, so the absolute slack of that test grows with k.
+__device__ __forceinline__ float acc_slack(int k) { return (float)(k + 2) * 8.3e-25f; }
 constexpr float Z_MAX = 7.0e13f;  // just below 2^46 = e^31.9
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -111,3 +111,14 @@ def test_capture_tree_step(oracle_mod, lantern_gpu):
         np.testing.assert_array_equal(n.cpu().numpy(), n_o)
         np.testing.assert_array_equal(path.cpu().numpy(), path_o)
         np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+
+
+def test_first_call_inside_a_capture_after_prepare(lantern_gpu):
+    """lantern_prepare raises the LDS limits ahead of time, so the first call of a shape in a process
+    may be recorded into a graph: checked in a fresh process (tests/graph_prepare_child.py)."""
+    import os
+    import subprocess
+    import sys
+    child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "graph_prepare_child.py")
+    r = subprocess.run([sys.executable, "-u", child], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout[-2000:] + r.stderr[-4000:]

@@ -82,6 +82,38 @@ def test_wide_latent_rows(oracle_mod, lantern_gpu):
                        table, delta, st.uniforms, label=f"wide_latent {variant}")
 
 
+def test_image_batch_full_step(oracle_mod, lantern_gpu):
+    """image_batch at its own launch size: all 960 rows of a step in one call."""
+    cfg = workloads.CONFIGS["image_batch"]
+    st, table = _step_and_table(oracle_mod, cfg, cfg.rows, step=101)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                                       table, cfg.delta, st.uniforms, threads=16, label="image_batch full step")
+    assert len(acc) == 960
+
+
+@pytest.mark.parametrize("variant,delta", [("plain", None), ("peaked", 0.01), ("reject", 0.0)])
+def test_wide_latent_full_step(oracle_mod, lantern_gpu, variant, delta):
+    """wide_latent at its own launch size: 3840 rows of fp32 logits (V=8192, k=100) in one call."""
+    cfg = workloads.CONFIGS["wide_latent"]
+    st = workloads.make_step(cfg, step=9, variant=variant)
+    table = random_table(cfg.V, cfg.k, seed=31)
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, st.target_logits, st.draft_logits, st.draft_tokens,
+                                       table, cfg.delta if delta is None else delta, st.uniforms, threads=16,
+                                       label=f"wide_latent full step {variant}")
+    assert len(acc) == 3840
+    if variant == "reject":
+        assert (acc == 0).mean() > 0.3
+
+
+def test_delta_is_the_binary32_value(oracle_mod, lantern_gpu):
+    """A prefix whose TVD lies between the double 0.4 and float32(0.4): inside the bound on both sides."""
+    from parity_utils import delta_window_row
+    target, draft, tokens, table, un = delta_window_row()
+    acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, target, draft, tokens, table, 0.4, un,
+                                       label="delta window")
+    assert g["a_size"][0] == 2 and g["path"][0] == 1
+
+
 def test_stress_full_step(oracle_mod, lantern_gpu):
     """One full 3840-row step of the stress configuration, in the bench's launch
     configuration (V=16384, k=1000, bf16, all rows in one call), every row compared."""
@@ -179,6 +211,34 @@ def test_filtered_and_unusable_rows(oracle_mod, lantern_gpu):
     assert list(acc[2:8]) == [-1] * 6 and list(res[2:8]) == [-1] * 6
     assert acc[0] in (0, 1) and acc[1] in (0, 1)
     assert acc[9] == 1
+
+
+def test_bad_table_entry_beyond_the_cut(oracle_mod, lantern_gpu):
+    """All k entries of a table row are range-checked, also those after the cut and beyond the
+    first 1024 slots: such rows are unusable on every path (sampling, decisions only, greedy)."""
+    V, k, N = 8192, 4000, 12
+    rng = np.random.default_rng(21)
+    t = torch.from_numpy((rng.standard_normal((N, V)) * 6.0).astype(np.float32)).to(torch.bfloat16)   # peaked: early cut
+    g = (t.float() + torch.from_numpy(rng.standard_normal((N, V)).astype(np.float32))).to(torch.bfloat16)
+    tokens = torch.from_numpy(rng.permutation(V)[:N].astype(np.int32))
+    table = random_table(V, k, seed=22)
+    bad_rows = [1, 4, 7]
+    for i, slot in zip(bad_rows, (1030, 2999, 3999)):
+        table[int(tokens[i]), slot] = V + i
+    un = torch.from_numpy(philox.uniforms(23, N))
+    acc, res, diag, gg = compare_verify(oracle_mod, lantern_gpu, t, g, tokens, table, 0.02, un, label="late bad entry")
+    assert all(acc[i] == -1 for i in bad_rows) and (acc >= 0).sum() == N - len(bad_rows)
+    assert (diag["a_size"][acc >= 0] < 1024).all()          # the walk itself ends long before the bad entries
+    tb = torch.from_numpy(table).cuda()
+    dec = lantern_gpu.decide_rows(t.cuda(), g.cuda(), None, tokens.cuda(), tb, 0.02, un.cuda())
+    ga, gt = lantern_gpu.verify_greedy(t.cuda(), tokens.cuda(), tb, 0.02)
+    torch.cuda.synchronize()
+    dec = dec[0] if isinstance(dec, tuple) else dec
+    np.testing.assert_array_equal(dec.cpu().numpy(), acc)
+    ga_o, gt_o, _ = oracle_mod.verify_greedy(t, tokens, table, k, 0.02, threads=8)
+    np.testing.assert_array_equal(ga.cpu().numpy(), ga_o)
+    np.testing.assert_array_equal(gt.cpu().numpy(), gt_o)
+    assert all(ga_o[i] == -1 for i in bad_rows)
 
 
 def test_empty_batch_and_determinism(oracle_mod, lantern_gpu):
