@@ -123,6 +123,30 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
                              void* hip_stream);
 
 /*
+ * lantern_build_knn_metric for callers that cannot allocate device memory and
+ * so cannot bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The workspace is a static device
+ * array inside the library (LANTERN_STATIC_SCRATCH_BYTES, held on every GPU
+ * the library runs on until the process ends); the call allocates and frees
+ * nothing.  Same table, bit for bit, as lantern_build_knn_metric.
+ *
+ *   out_exact_rows  device int32 or NULL: receives the number of rows ranked
+ *                   by the all-pairs pass (what lantern_build_knn leaves in the
+ *                   first word of its workspace)
+ * Limits: V <= LANTERN_STATIC_MAX_V; beyond that E_WORKSPACE, nothing launched.
+ * All calls on one GPU share that GPU's scratch (the library clears what must
+ * start at zero): calls that overlap in time on one GPU - from several streams
+ * or threads - race and give undefined tables; serialise them.  The first call
+ * on a device looks the array's address up (a runtime call, no allocation):
+ * make it outside a stream capture.
+ * Errors: E_NULL, E_SHAPE, E_DTYPE, E_WORKSPACE (V over the limit), E_DEVICE.
+ */
+#define LANTERN_STATIC_MAX_V 32768
+#define LANTERN_STATIC_SCRATCH_BYTES (40u << 20)
+int lantern_build_knn_static(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k, int metric,
+                             int32_t* out_knn, int32_t* out_exact_rows, void* hip_stream);
+
+/*
  * N independent relaxed verifications (Section 4.3, final rule):
  *   t = softmax(target row), g = softmax(draft row), xt = draft token
  *   walk knn[xt, 0..k) nearest first; a neighbour x != xt is taken while the

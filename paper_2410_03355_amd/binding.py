@@ -25,7 +25,7 @@ EXPORTS = (
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
-    "lantern_verify_trees_greedy", "lantern_probe_stream_read", "lantern_prepare",
+    "lantern_verify_trees_greedy", "lantern_probe_stream_read", "lantern_prepare", "lantern_build_knn_static",
     "lantern_status_string",
     "lantern_version",
 )
@@ -89,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.lantern_probe_stream_read.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
     lib.lantern_build_random.restype = i32
+    lib.lantern_build_knn_static.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.lantern_build_knn_static.restype = i32
     lib.lantern_prepare.argtypes = [i32, i32, i32]
     lib.lantern_prepare.restype = i32
     lib.lantern_status_string.argtypes = [i32]
@@ -159,6 +161,28 @@ def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None, r
     if return_stats:
         return out, ws[:4].view(torch.int32)[0]
     return out
+
+
+STATIC_MAX_V = 32768
+
+
+def build_knn_static(codebook: torch.Tensor, k: int, out: torch.Tensor, metric: str = "l2", exact_rows=None,
+                     stream=None) -> None:
+    """lantern_build_knn_static: the table into the caller's `out` ([V, k] int32, device) using the
+    library's static scratch; this wrapper allocates nothing either.  exact_rows: device int32
+    tensor of one element, or None."""
+    lib = load()
+    _need_cuda(codebook, out, exact_rows)
+    if codebook.dim() != 2 or not codebook.is_contiguous():
+        raise ValueError("codebook must be a contiguous [V, d] tensor")
+    V, d = codebook.shape
+    if out.dtype != torch.int32 or tuple(out.shape) != (V, k) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous int32 [V, k] tensor")
+    rc = lib.lantern_build_knn_static(codebook.data_ptr(), _dtype_code(codebook), V, d, k,
+                                      {"l2": METRIC_L2, "cosine": METRIC_COSINE}[metric], out.data_ptr(),
+                                      None if exact_rows is None else exact_rows.data_ptr(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_build_knn_static")
 
 
 def _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms):

@@ -241,6 +241,26 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
+int lantern_build_knn_static(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k, int metric,
+                             int32_t* out_knn, int32_t* out_exact_rows, void* hip_stream) {
+    if (!dtype_ok((int)cb_dtype)) return LANTERN_E_DTYPE;
+    if (V < 1 || d < 1 || k < 1 || k > V) return LANTERN_E_SHAPE;
+    if (metric != LANTERN_METRIC_L2 && metric != LANTERN_METRIC_COSINE) return LANTERN_E_SHAPE;
+    if (!codebook || !out_knn) return LANTERN_E_NULL;
+    if (V > LANTERN_STATIC_MAX_V || !lantern::knn_static_fits(V)) return LANTERN_E_WORKSPACE;
+    lantern::KnnArgs a;
+    a.codebook = codebook;
+    a.cb_dtype = (int)cb_dtype;
+    a.V = V;
+    a.d = d;
+    a.k = k;
+    a.metric = metric;
+    a.out = out_knn;
+    a.workspace = nullptr;
+    const hipError_t e = lantern::launch_build_knn_static(a, out_exact_rows, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 int lantern_build_knn(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
                       int32_t* out_knn, void* workspace, size_t workspace_bytes, void* hip_stream) {
     return lantern_build_knn_metric(codebook, cb_dtype, V, d, k, LANTERN_METRIC_L2, out_knn,

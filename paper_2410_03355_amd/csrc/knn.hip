@@ -17,8 +17,11 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "device_utils.h"
 #include "knn_args.h"
+#include "lantern.h"
 
 namespace lantern {
 
@@ -30,24 +33,70 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 
 struct KnnLayout {
     size_t stats, norms, nmax, dist, flags, slow, total;
-    int row_block;
+    int row_block;   // query rows per pass through the key block
+    int slow_wgs;    // workgroups (and fp64 row buffers) of the exact pass
 };
 
-static KnnLayout knn_layout(int V) {
+static KnnLayout knn_layout(int V, int row_block, int slow_wgs) {
     KnnLayout L;
-    L.row_block = V < ROW_BLOCK ? V : ROW_BLOCK;
+    L.row_block = V < row_block ? V : row_block;
+    L.slow_wgs = slow_wgs;
     size_t off = 0;
     L.stats = off; off = align_up(off + 256, 256);   // int32[0]: rows that took the exact all-pairs pass
     L.norms = off; off = align_up(off + sizeof(float) * (size_t)V, 256);
     L.nmax = off;  off = align_up(off + 256, 256);
     L.dist = off;  off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
     L.flags = off; off = align_up(off + sizeof(int) * (size_t)L.row_block, 256);
-    L.slow = off;  off = align_up(off + sizeof(double) * (size_t)SLOW_WGS * V, 256);
+    L.slow = off;  off = align_up(off + sizeof(double) * (size_t)L.slow_wgs * V, 256);
     L.total = off;
     return L;
 }
 
-size_t knn_workspace_bytes(int V, int, int) { return knn_layout(V).total; }
+size_t knn_workspace_bytes(int V, int, int) { return knn_layout(V, ROW_BLOCK, SLOW_WGS).total; }
+
+// ---- scratch of the entry point that allocates nothing ----
+// Device memory that lives as long as the process, one copy per GPU.  Host code never uses the
+// array's name as an address: it asks the runtime for the array's device address once per device
+// and passes that pointer on.
+constexpr size_t STATIC_SCRATCH_BYTES = LANTERN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// The largest layout that fits the static scratch: fewer exact-pass buffers, and as many query
+// rows per pass as the rest holds (a multiple of 128, the contraction's tile).  row_block 0: V is
+// beyond what the scratch can serve.
+static KnnLayout knn_layout_static(int V) {
+    const int slow_wgs = 32;
+    for (int rb = ROW_BLOCK; rb >= 128; rb -= 128) {
+        const KnnLayout L = knn_layout(V, rb, slow_wgs);
+        if (L.total <= STATIC_SCRATCH_BYTES) return L;
+    }
+    KnnLayout none = knn_layout(V, 128, slow_wgs);
+    none.row_block = 0;
+    return none;
+}
+
+bool knn_static_fits(int V) { return knn_layout_static(V).row_block > 0; }
+
+// Device address of the static scratch on the current device (looked up once per device).
+static hipError_t static_scratch_ptr(void** out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void* ptrs[MAX_DEVICES];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
+}
 
 template <typename CT> __device__ __forceinline__ float cb_f32(const CT* p, int64_t i);
 template <> __device__ __forceinline__ float cb_f32<float>(const float* p, int64_t i) { return p[i]; }
@@ -586,10 +635,10 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
 }
 
 __global__ void knn_clear_stats(int* stats) { stats[threadIdx.x] = 0; }
+__global__ void knn_copy_stats(const int* stats, int32_t* out) { *out = stats[0]; }
 
 template <typename CT>
-static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
-    const KnnLayout L = knn_layout(a.V);
+static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t stream) {
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
     float* dist = reinterpret_cast<float*>(ws + L.dist);
     int* flags = reinterpret_cast<int*>(ws + L.flags);
@@ -648,7 +697,7 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
         else LANTERN_LAUNCH_SELECT_NK(0);
 #undef LANTERN_LAUNCH_SELECT_NK
 #undef LANTERN_LAUNCH_SELECT
-        const int wgs = rows < SLOW_WGS ? rows : SLOW_WGS;
+        const int wgs = rows < L.slow_wgs ? rows : L.slow_wgs;
         hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
                            a.metric, r0, rows, flags, slow, a.out, stats);
         const hipError_t e = hipGetLastError();
@@ -658,8 +707,27 @@ static hipError_t build_typed(const KnnArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream) {
-    if (a.cb_dtype == 0) return build_typed<float>(a, stream);
-    return build_typed<uint16_t>(a, stream);
+    const KnnLayout L = knn_layout(a.V, ROW_BLOCK, SLOW_WGS);
+    if (a.cb_dtype == 0) return build_typed<float>(a, L, stream);
+    return build_typed<uint16_t>(a, L, stream);
+}
+
+// The same build with the library's static scratch as workspace; a.workspace is ignored.
+// exact_rows: device int32 that receives the number of rows ranked by the all-pairs pass, or null.
+hipError_t launch_build_knn_static(const KnnArgs& a_in, int32_t* exact_rows, hipStream_t stream) {
+    const KnnLayout L = knn_layout_static(a_in.V);
+    if (L.row_block == 0) return hipErrorInvalidValue;   // the host entry has checked this
+    KnnArgs a = a_in;
+    hipError_t e = static_scratch_ptr(&a.workspace);
+    if (e != hipSuccess) return e;
+    e = a.cb_dtype == 0 ? build_typed<float>(a, L, stream) : build_typed<uint16_t>(a, L, stream);
+    if (e != hipSuccess) return e;
+    if (exact_rows) {
+        hipLaunchKernelGGL(knn_copy_stats, dim3(1), dim3(1), 0, stream,
+                           reinterpret_cast<const int*>(static_cast<unsigned char*>(a.workspace) + L.stats), exact_rows);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace lantern

@@ -21,6 +21,11 @@ struct KnnArgs {
 size_t knn_workspace_bytes(int V, int d, int k);
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream);
 
+// The build on the library's static device scratch (no workspace from the caller, nothing
+// allocated).  knn_static_fits: whether a codebook of V codes is within what that scratch serves.
+bool knn_static_fits(int V);
+hipError_t launch_build_knn_static(const KnnArgs& a, int32_t* exact_rows, hipStream_t stream);
+
 // Random table of k <= RANDOM_MAX_K entries per row; t0: first threshold on the 32-bit keys, in [1, 2^32].
 constexpr int RANDOM_MAX_K = 4096;
 hipError_t launch_build_random(int V, int k, uint64_t seed, uint64_t t0, int32_t* out, hipStream_t stream);

@@ -162,3 +162,21 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         B.load()
     with pytest.raises(FileNotFoundError):
         B.knn_workspace_bytes(0, 16, 8, 4)
+
+
+def test_static_build_and_prepare_argument_errors(lib):
+    """The entry point that allocates nothing refuses sizes beyond its scratch on the host."""
+    import paper_2410_03355_amd as L
+    p = ctypes.c_void_p(4096)
+    nul = ctypes.c_void_p(0)
+    call = lib.lantern_build_knn_static
+    assert call(p, 9, 16, 8, 4, 0, p, nul, nul) == L.binding.E_DTYPE
+    assert call(p, L.F32, 16, 8, 17, 0, p, nul, nul) == L.binding.E_SHAPE
+    assert call(p, L.F32, 16, 8, 4, 5, p, nul, nul) == L.binding.E_SHAPE
+    assert call(nul, L.F32, 16, 8, 4, 0, p, nul, nul) == L.binding.E_NULL
+    assert call(p, L.F32, 16, 8, 4, 0, nul, nul, nul) == L.binding.E_NULL
+    assert call(p, L.F32, L.binding.STATIC_MAX_V + 1, 8, 4, 0, p, nul, nul) == L.binding.E_WORKSPACE
+    assert lib.lantern_prepare(7, 16, 4) == L.binding.E_DTYPE
+    assert lib.lantern_prepare(L.F32, 0, 1) == L.binding.E_SHAPE
+    assert lib.lantern_prepare(L.F32, 16, 17) == L.binding.E_SHAPE
+    assert lib.lantern_prepare(L.BF16, L.MAX_VOCAB + 1, 4) == L.binding.E_SHAPE
