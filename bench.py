@@ -57,6 +57,8 @@ def main() -> int:
                     help="tree mode: candidates listed level by level with siblings next to each other (as a "
                          "drafter that expands one level at a time lists them), or in random drafting order")
     ap.add_argument("--buffers", type=int, default=6, help="distinct step inputs rotated through")
+    ap.add_argument("--rows", type=int, default=None,
+                    help="verifications per step, when not the workload's own (a sweep aid: the headline uses the default)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="the CPU oracle is timed on whole steps of the workload until this much time has passed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -83,6 +85,8 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = workloads.CONFIGS[args.workload]
+    if args.rows is not None:
+        cfg = workloads.with_overrides(cfg, rows=args.rows)
     delta = 0.0 if args.variant == "reject" else cfg.delta
     stream = torch.cuda.current_stream()
 

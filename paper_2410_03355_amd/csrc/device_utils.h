@@ -86,6 +86,28 @@ __device__ __forceinline__ float wave_prev(float v, float identity) {
     return dpp_f<DPP_WAVE_SHR1, 0xF>(identity, v);
 }
 
+// fp64 sum over the wavefront with DPP on the two halves of the value (six steps of two moves
+// and one add, no LDS traffic); the result is uniform.  Lanes without a source add +0.0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_d(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)b, CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+__device__ __forceinline__ double wave_sum_dpp(double v) {
+    v += dpp_d<DPP_ROW_SHR1, 0xF>(v);
+    v += dpp_d<DPP_ROW_SHR2, 0xF>(v);
+    v += dpp_d<DPP_ROW_SHR4, 0xF>(v);
+    v += dpp_d<DPP_ROW_SHR8, 0xF>(v);
+    v += dpp_d<DPP_ROW_BCAST15, 0xA>(v);
+    v += dpp_d<DPP_ROW_BCAST31, 0xC>(v);
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, 63);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 63);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 // fp64 versions go through the LDS crossbar (ds_bpermute); they are used only
 // by the exact path.
 __device__ __forceinline__ double wave_sum(double v) {

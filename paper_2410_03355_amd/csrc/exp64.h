@@ -54,4 +54,69 @@ LANTERN_HD double exp_nonpos(double d) {
     return ldexp(p, (int)n);
 }
 
+// exp(d) for d in [-1000, 700] from a table of 2^(j/128): d = (128 n + j) ln2/128 + r with
+// |r| <= ln2/256, exp(d) = 2^n * T[j] * e^r.  The reduction multiplies the integer 128 n + j
+// (below 2^18 in magnitude) by a 32-bit piece of ln2/128, which is exact, and by the remainder;
+// e^r - 1 is the degree-5 Taylor polynomial (truncation below 6e-19); the table entry is a pair
+// hi + lo, so the result is within 0.6 ulp of the exact value: within one ulp of libm.  Half the
+// arithmetic of exp_nonpos.  tab: EXP_TABLE_HILO, on the device a copy of it in LDS.
+// Arguments below -1000, and NaN, give 0.  Branch-free.
+LANTERN_HD double exp_poly5(double r) {                     // e^r - 1 for |r| <= ln2/256
+    double q = __builtin_fma(r, 8.3333333333333332177e-03, 4.1666666666666664354e-02);   // 1/5!, 1/4!
+    q = __builtin_fma(q, r, 1.6666666666666665741e-01);                                  // 1/3!
+    q = __builtin_fma(q, r, 0.5);
+    q = __builtin_fma(q, r, 1.0);
+    return q * r;
+}
+
+LANTERN_HD double exp_tab(double d, const double* tab) {
+    const double INV_STEP = 184.6649652337873;             // 128 / ln 2
+    const double STEP_HI = 0x1.62e42fee00000p-8;           // ln2/128 with the low 21 mantissa bits zero
+    const double STEP_LO = 0x1.a39ef35793c76p-40;          // ln2/128 - STEP_HI
+    d = fmin(fmax(d, -1000.0), 700.0);
+    const double m = __builtin_rint(d * INV_STEP);
+    double r = __builtin_fma(-m, STEP_HI, d);
+    r = __builtin_fma(-m, STEP_LO, r);
+    const int mi = (int)m;
+    const int j = mi & 127;
+    const int n = mi >> 7;                                  // floor division: j >= 0
+    const double hi = tab[2 * j], lo = tab[2 * j + 1];
+    const double p = exp_poly5(r);                          // e^r - 1
+    const double res = hi + __builtin_fma(hi, p, lo);
+    return ldexp(res, n);
+}
+
+// exp_tab for arguments known to lie in [-700, 700], with fewer instructions: the rounding to an
+// integer is one fused multiply-add onto 1.5 * 2^52 (the integer then sits in the low word of
+// the sum), and the scaling by 2^n is an integer addition to the exponent field (the result
+// stays a normal number on this range).  Same reduction, table and polynomial as exp_tab: the
+// same value.  The caller clamps; outside the range the result is meaningless.
+// tab_bytes: the table as bytes (on the device an LDS address: placed at offset 0 of the
+// workgroup's LDS, the lookup's address is the masked integer itself).
+LANTERN_HD double exp_tab_core(double d, const unsigned char* tab_bytes) {
+    const double INV_STEP = 184.6649652337873;
+    const double STEP_HI = 0x1.62e42fee00000p-8;
+    const double STEP_LO = 0x1.a39ef35793c76p-40;
+    const double MAGIC = 6755399441055744.0;               // 1.5 * 2^52
+    const double t = __builtin_fma(d, INV_STEP, MAGIC);
+    unsigned long long tb;
+    __builtin_memcpy(&tb, &t, 8);
+    const unsigned mi = (unsigned)tb;                       // low word: the rounded integer, two's complement
+    const double m = t - MAGIC;
+    double r = __builtin_fma(-m, STEP_HI, d);
+    r = __builtin_fma(-m, STEP_LO, r);
+    const double* entry = reinterpret_cast<const double*>(tab_bytes + ((mi & 127u) << 4));
+    const double hi = entry[0], lo = entry[1];
+    const double p = exp_poly5(r);
+    const double res = hi + __builtin_fma(hi, p, lo);
+    unsigned long long rb;
+    __builtin_memcpy(&rb, &res, 8);
+    // n = mi >> 7 (arithmetic) into the exponent field: bits 52.. of the double, 20.. of its high word
+    const unsigned hi_word = (unsigned)(rb >> 32) + ((mi & ~127u) << 13);
+    rb = ((unsigned long long)hi_word << 32) | (unsigned)rb;
+    double out;
+    __builtin_memcpy(&out, &rb, 8);
+    return out;
+}
+
 }  // namespace lantern

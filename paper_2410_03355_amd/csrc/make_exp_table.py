@@ -14,7 +14,12 @@ print("")
 print("namespace lantern {")
 print("")
 print("constexpr int EXP_TABLE_N = %d;" % N)
-print("static const __device__ double EXP_TABLE_HILO[2 * EXP_TABLE_N] = {")
+print("#if defined(__HIPCC__)")
+print("#define LANTERN_EXP_TABLE_QUAL __device__")
+print("#else")
+print("#define LANTERN_EXP_TABLE_QUAL")
+print("#endif")
+print("static const LANTERN_EXP_TABLE_QUAL double EXP_TABLE_HILO[2 * EXP_TABLE_N] = {")
 for j in range(N):
     v = (LN2 * Decimal(j) / Decimal(N)).exp()
     hi = float(v)

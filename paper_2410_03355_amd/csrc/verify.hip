@@ -27,6 +27,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include "exp_table.h"
 #include "fast_cut.h"
 #include "lds_limit.h"
 #include "tree_walk.h"
@@ -42,7 +43,9 @@ struct FastShared {
     float wtot[NW];                 // per-wave totals of the neighbour terms (first 1024 slots)
     int wbad[NW];                   // a table entry outside [0,V)
     int settled;                    // row settled by the fp32 path
-    int pad[3];
+    int regs_ok;                    // not settled, but usable, sums in range and the cut definite
+    int a_size;                     // slots taken into A (valid when regs_ok)
+    int pad;
     // from here on the memory is reused by the exact path once the fp32 decision is taken
     float gs[NT * 4];               // inclusive sums of the neighbour terms within their wavefront
     unsigned gskip[NT];             // bit q: slot 4*tid+q is the token itself or beyond k
@@ -54,6 +57,336 @@ static_assert(FAST_SHARED_HEAD % 16 == 0, "the exact path's LDS region must be 1
 template <typename LT, bool VEC, int TNT = NT>
 __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const unsigned char* lds_row,
                           bool have_max, float max_t, float max_g, const unsigned char* lds_grow = nullptr);
+
+// ---------------------------------------------------------------------------
+// fp64 evaluation of a row in one pass, with what the fp32 pass already knows
+// ---------------------------------------------------------------------------
+// For a row the fp32 pass could not settle but found usable, with both sums in range and a
+// definite cut: the decision and, on rejection, the resampled token, in fp64, in ONE pass over the
+// two rows (2V exponentials instead of the 4V of the general path, no pass for the maxima).
+// What makes one pass enough: the residual max(0, t_A - g) needs, token by token, the SIGN of
+// t_A(x) - g(x), and the fp32 terms and sums decide that sign for all but the few tokens where
+// the two probabilities agree to within the fp32 error bound.  So while the pass adds up the
+// fp64 normalisers it also adds, per (vector chunk, wavefront) segment and in token order, the
+// target and drafter terms of the tokens whose residual is certainly positive; tokens whose sign
+// fp32 cannot tell go on a short list with their fp64 terms.  Once the normalisers are known a
+// segment's residual mass is  P_t / Z_t - P_g / Z_g  plus its listed tokens, a scan over the
+// (at most 64) segment masses finds the segment that holds the draw, and that segment alone is
+// re-evaluated token by token.
+// No global load sits inside the pass (under a saturated memory system each costs microseconds):
+// the drafter's row is still in the registers of the fp32 pass, the target row in LDS, the first
+// 1024 table slots in registers, and the table of the exponential was fetched with the row.
+constexpr int AMB_CAP = 40;          // tokens whose residual sign fp32 leaves open (about one per row)
+constexpr double TAU_SIGN = 2.0e-5;  // covers the errors of the two fp32 sums in the sign test (<= 8.8e-6 together)
+
+struct AmbEntry {
+    double et, eg;   // unnormalised fp64 terms
+    int x;           // token
+    int pad;
+};
+
+// LDS of this path, in the region the neighbour scan no longer needs.
+struct OnePassLayout {
+    size_t mask, seg, amb_count, amb, total;
+};
+// The exponential's table sits at the very start of the workgroup's LDS (before the row): the
+// address of a lookup is then the masked integer itself, with no base to add.
+constexpr int EXP_TABLE_BYTES = 2 * EXP_TABLE_N * (int)sizeof(double);
+__host__ __device__ inline OnePassLayout one_pass_layout(int V) {
+    OnePassLayout L;
+    size_t off = (sizeof(ExactShared) + 15) & ~size_t(15);
+    L.mask = off;      off += (((size_t)V + 31) / 32) * 4;  off = (off + 15) & ~size_t(15);
+    L.seg = off;       off += 16 * NW * 2 * sizeof(double);           // up to 16 vector chunks per thread
+    L.amb = off;       off += AMB_CAP * sizeof(AmbEntry);
+    L.amb_count = off; off += 16;
+    L.total = off;
+    return L;
+}
+
+// One residual term of the token-by-token evaluation: max(0, t_A(x) - g(x)), zero on A and at xt
+// (the token's own residual is zero in a rejected row: u g >= mass with u < 1).
+__device__ __forceinline__ double one_pass_term(float lt, float lg, bool zero, double rt, double rg, double inv_zt,
+                                                double inv_zg, const double* tab) {
+    const double d = exp_tab((double)lt - rt, tab) * inv_zt - exp_tab((double)lg - rg, tab) * inv_zg;
+    return (!zero && d > 0.0) ? d : 0.0;
+}
+
+// What the pass does for one token: its fp64 terms into the normalisers; into the segment's sums
+// when the residual is certainly positive; onto the list when that cannot be told.
+// The sign test compares the fp64 terms across the fp32 sums: t(x) > g(x) <=> e_t Z_g > e_g Z_t,
+// where only Z_t32 and Z_g32 carry an error (at most 4.4e-6 relative each: terms 2.5e-6, tree
+// sums 1.9e-6), so a margin of TAU_SIGN = 2e-5 on either side makes "positive" and "not positive"
+// certain.  floor_t, floor_g: the row's reference logit minus 700; logits below it (filtered
+// tokens at -inf among them) are evaluated there: a term of 1e-304 of the sum either way.
+// max of two floats as the one hardware instruction (fmaxf first quiets both operands, two more
+// instructions per call; no NaN reaches this path).
+__device__ __forceinline__ float max_f32_1(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+struct OnePassAcc {
+    double zt, zg, pt, pg;
+};
+__device__ __forceinline__ void one_pass_token(OnePassAcc& acc, float lt, float lg, bool zero, int x, double rt,
+                                               double rg, float floor_t, float floor_g, double Zt, double Zg,
+                                               const unsigned char* tab, AmbEntry* amb, int* amb_count) {
+    const double et = exp_tab_core((double)max_f32_1(lt, floor_t) - rt, tab);
+    const double eg = exp_tab_core((double)max_f32_1(lg, floor_g) - rg, tab);
+    acc.zt += et;
+    acc.zg += eg;
+    const double lhs = et * Zg, rhs = eg * Zt;              // t(x) > g(x)  <=>  lhs > rhs
+    const bool pos = !zero && (rhs < lhs * (1.0 - TAU_SIGN));
+    const bool neg = zero || (lhs < rhs * (1.0 - TAU_SIGN));
+    const double m = pos ? 1.0 : 0.0;
+    acc.pt = __builtin_fma(et, m, acc.pt);
+    acc.pg = __builtin_fma(eg, m, acc.pg);
+    if (!pos && !neg) {
+        const int slot = atomicAdd(amb_count, 1);
+        if (slot < AMB_CAP) {
+            amb[slot].et = et;
+            amb[slot].eg = eg;
+            amb[slot].x = x;
+        }
+    }
+}
+
+// s_row: raw target row in LDS.  G: the drafter's row as the fp32 pass loaded it (consumed here).
+// nb: table slots 4*tid .. 4*tid+3.  ref_t, ref_g: the fp32 pass's reference logits; Zt32, Zg32:
+// its sums; a_size: its (definite) cut.
+// tab_elem: entry tid of EXP_TABLE_HILO; tab_lds: where the table goes in LDS.
+template <typename LT, int NV, bool FULL>
+__device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int lrow, uint4 (&G)[NV],
+                                               const int (&nb)[4], float ref_t, float ref_g,
+                                               float Zt32, float Zg32, int a_size, int xt, float lg_tok, float u_acc32,
+                                               double tab_elem, unsigned char* tab_lds, unsigned char* ex,
+                                               const unsigned char* s_row) {
+    using L = Lane<LT>;
+    constexpr int EPV = L::EPV;
+    constexpr int NSEG = NV * NW;                            // at most 64: one wavefront scans them
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
+    const int V = a.V;
+    const int k = a.k;
+    const int nvec = V / EPV;
+    const OnePassLayout lay = one_pass_layout(V);
+    ExactShared& sh = *reinterpret_cast<ExactShared*>(ex);
+    uint32_t* mask = reinterpret_cast<uint32_t*>(ex + lay.mask);
+    double* seg = reinterpret_cast<double*>(ex + lay.seg);
+    double* tab = reinterpret_cast<double*>(tab_lds);
+    AmbEntry* amb = reinterpret_cast<AmbEntry*>(ex + lay.amb);
+    int* amb_count = reinterpret_cast<int*>(ex + lay.amb_count);
+    const int nwords = (V + 31) >> 5;
+    const double rt = (double)ref_t, rg = (double)ref_g;
+    const float u_res32 = a.uniforms[2 * (int64_t)row + 1];  // in flight during the pass
+
+    // ---- table of the exponential, empty mask, empty list ----
+    tab[tid] = tab_elem;                                     // 2 * 128 doubles, one per thread
+    for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
+    if (tid == 0) *amb_count = 0;
+    __syncthreads();
+
+    // ---- A as a bitmask, and its mass (unnormalised) ----
+    double s_loc = 0.0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int n = nb[q];                                 // in range: the fp32 pass has checked all k entries
+        if (tid * 4 + q < a_size && n != xt) {
+            s_loc += exp_tab((double)L::lds(s_row, n) - rt, tab);
+            atomicOr(&mask[n >> 5], 1u << (n & 31));
+        }
+    }
+    if (a_size > NT * 4) {
+        const int32_t* nrow = a.knn + (int64_t)xt * k;
+        for (int j = NT * 4 + tid; j < a_size; j += NT) {
+            const int n = nrow[j];
+            if (n != xt) {
+                s_loc += exp_tab((double)L::lds(s_row, n) - rt, tab);
+                atomicOr(&mask[n >> 5], 1u << (n & 31));
+            }
+        }
+    }
+    const double S = block_sum<NW>(s_loc, sh.red, tid);      // its barriers also publish the mask
+    const double e_tx = exp_tab((double)L::lds(s_row, xt) - rt, tab);
+    const double e_gx = exp_tab((double)lg_tok - rg, tab);
+
+    // ---- the pass: normalisers, and per segment the terms of the certainly positive residuals ----
+    // Rolled loops with the vectors shifted down by one chunk / two elements per turn, so that
+    // registers are indexed statically and the code stays small.
+    OnePassAcc acc;
+    acc.zt = 0.0;
+    acc.zg = 0.0;
+    const float floor_t = ref_t - 700.f, floor_g = ref_g - 700.f;
+    const double Zt64 = (double)Zt32, Zg64 = (double)Zg32;
+#pragma unroll 1
+    for (int c = 0; c < NV; ++c) {
+        uint4 gv = G[0];
+#pragma unroll
+        for (int i = 0; i + 1 < NV; ++i) G[i] = G[i + 1];
+        const int vi = c * NT + tid;
+        const bool live = FULL || vi < nvec;
+        uint4 tv = live ? reinterpret_cast<const uint4*>(s_row)[vi]
+                        : make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+        const int x0 = vi * EPV;
+        unsigned in_a = live ? (mask[x0 >> 5] >> (x0 & 31)) & ((1u << EPV) - 1u) : 0u;   // EPV divides 32
+        acc.pt = 0.0;
+        acc.pg = 0.0;
+#pragma unroll 1
+        for (int e = 0; e < EPV; e += 2) {
+            const float lt0 = L::get(tv, 0), lt1 = L::get(tv, 1), lg0 = L::get(gv, 0), lg1 = L::get(gv, 1);
+            // t_A is zero on A without the token, the token's own residual is zero in a rejected row,
+            // and a filtered target token has t = 0
+            const bool zero0 = (in_a & 1u) || (x0 + e == xt) || lt0 == neg_inf_f();
+            const bool zero1 = (in_a & 2u) || (x0 + e + 1 == xt) || lt1 == neg_inf_f();
+            one_pass_token(acc, lt0, lg0, zero0, x0 + e, rt, rg, floor_t, floor_g, Zt64, Zg64, tab_lds, amb, amb_count);
+            one_pass_token(acc, lt1, lg1, zero1, x0 + e + 1, rt, rg, floor_t, floor_g, Zt64, Zg64, tab_lds, amb, amb_count);
+            tv = L::drop2(tv);
+            gv = L::drop2(gv);
+            in_a >>= 2;
+        }
+        const double pt = wave_sum_dpp(acc.pt);
+        const double pg = wave_sum_dpp(acc.pg);
+        if (lane == 0) {
+            seg[2 * (c * NW + wave)] = pt;
+            seg[2 * (c * NW + wave) + 1] = pg;
+        }
+    }
+    const double zt = block_sum<NW>(acc.zt, sh.red, tid);
+    const double zg = block_sum<NW>(acc.zg, sh.red2, tid);  // its barriers publish seg and the list
+
+    // ---- decision ----
+    const double mass = (e_tx + S) / zt;
+    const double g_tok = e_gx / zg;
+    const bool accepted = ((double)u_acc32 * g_tok < mass);
+    if (tid == 0) {
+        double ap;
+        if (g_tok > 0.0) ap = fmin(1.0, mass / g_tok);
+        else ap = mass > 0.0 ? 1.0 : 0.0;
+        if (a.out_prob) a.out_prob[row] = (float)ap;
+        if (a.out_mass) a.out_mass[row] = (float)mass;
+        if (a.out_gtok) a.out_gtok[row] = (float)g_tok;
+        if (a.out_asize) a.out_asize[row] = a_size;
+        if (a.out_path) a.out_path[row] = 1;
+        if (accepted) {
+            a.out_accept[row] = 1;
+            a.out_resample[row] = -1;
+        }
+    }
+    if (accepted) return;
+
+    // ---- rejected: residual mass per segment (segments in token order), the one that holds the draw ----
+    const int n_amb = *amb_count;
+    const double inv_zt = 1.0 / zt, inv_zg = 1.0 / zg;
+    if (wave == 0) {
+        double r = 0.0;
+        if (lane < NSEG) {
+            r = seg[2 * lane] * inv_zt - seg[2 * lane + 1] * inv_zg;
+            r = r > 0.0 ? r : 0.0;
+            for (int i = 0; i < n_amb && i < AMB_CAP; ++i) {
+                const int v = amb[i].x / EPV;               // vector of the token: chunk v / NT, thread v % NT
+                if ((v / NT) * NW + ((v % NT) >> 6) == lane) {
+                    const double d = amb[i].et * inv_zt - amb[i].eg * inv_zg;
+                    r += d > 0.0 ? d : 0.0;
+                }
+            }
+        }
+        const double incl = wave_scan_incl(r);
+        const double Z = __shfl(incl, WAVE - 1, WAVE);
+        const double cthr = (double)u_res32 * Z;
+        const unsigned long long cross = __ballot(lane < NSEG && incl > cthr);
+        const unsigned long long has = __ballot(r > 0.0);
+        // rounding can leave no crossing: the last segment that holds mass takes the draw
+        const int s = cross ? (__ffsll((long long)cross) - 1) : (has ? 63 - __clzll((long long)has) : 0);
+        const double before = s ? __shfl(incl, s - 1, WAVE) : 0.0;
+        if (lane == 0) {
+            sh.bcast[0] = before;
+            sh.bcast[1] = cthr;
+            sh.bcast[2] = Z;
+            sh.ibcast[0] = s;
+        }
+    }
+    __syncthreads();
+    // a list that overflowed, or a residual without mass (by rounding): the general path
+    // (uniform over the workgroup)
+    if (n_amb > AMB_CAP || !(sh.bcast[2] > 0.0)) {
+        __syncthreads();
+        exact_row<LT, true>(a, row, ex, s_row, false, 0.f, 0.f);
+        return;
+    }
+    const int ent = sh.ibcast[0];
+    if (wave == (ent % NW)) {
+        const double P = sh.bcast[0], cthr = sh.bcast[1];
+        const int vi = (ent / NW) * NT + tid;
+        const int x0 = vi * EPV;
+        const bool live = FULL || vi < nvec;
+        const uint4 ninf = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+        const uint4* gsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride);
+        const uint4 gv = live ? gsrc[vi] : ninf;             // the one reload: this segment of the drafter's row
+        const uint4 tv = live ? reinterpret_cast<const uint4*>(s_row)[vi] : ninf;
+        const unsigned in_a = live ? (mask[x0 >> 5] >> (x0 & 31)) & ((1u << EPV) - 1u) : 0u;
+        double r[EPV];
+        double sum = 0.0;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            r[e] = one_pass_term(L::get(tv, e), L::get(gv, e), ((in_a >> e) & 1u) || (x0 + e == xt), rt, rg, inv_zt,
+                                 inv_zg, tab);
+            sum += r[e];
+        }
+        const double incl = wave_scan_incl(sum);
+        double excl = __shfl_up(incl, 1, WAVE);
+        if (lane == 0) excl = 0.0;
+        const unsigned long long cross = __ballot(P + incl > cthr);
+        const unsigned long long haspos = __ballot(sum > 0.0);
+        // rounding between the segment's mass and its token-by-token evaluation can leave no
+        // crossing lane: then the last lane that holds mass takes the draw
+        const int owner = cross ? (__ffsll((long long)cross) - 1) : (haspos ? 63 - __clzll((long long)haspos) : 0);
+        int found = -1;
+        if (lane == owner) {
+            double cum = P + excl;
+            int lastpos = -1;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                cum += r[e];
+                if (r[e] > 0.0) lastpos = x0 + e;
+                if (found < 0 && cum > cthr && r[e] > 0.0) found = x0 + e;
+            }
+            if (found < 0) found = lastpos;
+        }
+        found = __shfl(found, owner, WAVE);
+        if (found < 0) {
+            // no token of the segment holds mass: its mass was rounding noise of the sums (it takes a
+            // draw within ~1e-16 of a segment edge).  The first token after it that holds mass is
+            // the one the cumulative sum reaches next; failing that, the last one before it.
+            const int seg_x0 = ((ent / NW) * NT + (ent % NW) * WAVE) * EPV;   // first token of the segment
+            int before = -1, after = INT_MAX;
+            for (int v0 = 0; v0 < nvec; v0 += WAVE) {
+                const int v = v0 + lane;
+                const bool lv = v < nvec;
+                const uint4 gq = lv ? gsrc[v] : ninf;
+                const uint4 tq = lv ? reinterpret_cast<const uint4*>(s_row)[v] : ninf;
+                const unsigned ia = lv ? (mask[(v * EPV) >> 5] >> ((v * EPV) & 31)) & ((1u << EPV) - 1u) : 0u;
+                int first = INT_MAX, last = -1;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int x = v * EPV + e;
+                    const bool has = one_pass_term(L::get(tq, e), L::get(gq, e), ((ia >> e) & 1u) || x == xt, rt, rg,
+                                                   inv_zt, inv_zg, tab) > 0.0;
+                    if (has && x >= seg_x0 && x < first) first = x;
+                    if (has && x < seg_x0) last = x;
+                }
+                after = min(after, wave_min(first));
+                before = max(before, -wave_min(-last));
+            }
+            found = after != INT_MAX ? after : before;
+        }
+        if (lane == 0) {
+            a.out_accept[row] = 0;
+            a.out_resample[row] = found;
+        }
+    }
+}
 
 // Per-row scalars and table slots, fetched together with the row.
 struct RowMeta {
@@ -73,13 +406,13 @@ struct RowMeta {
 // a term equal to one (Z >= 1) and every term is at most Z; rows whose sum exceeds 2^46
 // (an element more than 32 above the reference) are left to the exact path.
 template <typename LT, int NV, bool FULL>
-__global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
+__global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* s_row = smem;
+    unsigned char* s_row = smem + EXP_TABLE_BYTES;           // the fp64 path's table goes in front
     const int row_bytes = (a.V * (int)sizeof(LT) + 15) & ~15;
-    FastShared& sh = *reinterpret_cast<FastShared*>(smem + row_bytes);
+    FastShared& sh = *reinterpret_cast<FastShared*>(s_row + row_bytes);
     unsigned char* ex_lds = reinterpret_cast<unsigned char*>(sh.gs);
 
     const int tid = threadIdx.x;
@@ -127,6 +460,8 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
         m.u_acc = a.uniforms[2 * (int64_t)row];
         m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
     }
+    // this thread's entry of the exponential's table, for the fp64 path (cache-resident, 2 KB in all)
+    const double tab_elem = EXP_TABLE_HILO[tid];
 
     {
         const int xt = m.xt;
@@ -217,6 +552,10 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
             const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
             const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
             if (lane == 0) {
+                // with the resampled token wanted, a usable row with a definite cut is finished in
+                // fp64 from the registers
+                sh.regs_ok = (!settled && !bad && sums_ok && cut_definite && a.mode == VERIFY_FULL) ? 1 : 0;
+                sh.a_size = a_size;
                 if (settled) {
                     a.out_accept[row] = accept ? 1 : 0;
                     if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
@@ -234,7 +573,20 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
         __syncthreads();  // the decision is published; wavefront 0 is done with the LDS row
         if (!sh.settled) {
             // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
-            exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
+            if (sh.regs_ok) {
+                float Zt = 0.f, Zg = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    Zt += sh.wsum_t[w];
+                    Zg += sh.wsum_g[w];
+                }
+                const int a_size = sh.a_size;
+                __syncthreads();   // every thread has read the head before the region behind it is reused
+                exact_one_pass<LT, NV, FULL>(a, row, lrow, G, m.nb, rt, rg, Zt, Zg, a_size, xt, m.lg_tok, m.u_acc,
+                                             tab_elem, smem, ex_lds, s_row);
+            } else {
+                exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
+            }
         }
     }
 }
@@ -245,24 +597,29 @@ __global__ __launch_bounds__(NT) void verify_fast(VerifyArgs a) {
 
 // LDS the exact path needs beyond whatever precedes it: reductions, a bitmask
 // of A over the vocabulary, one fp64 partial sum per (vector chunk, wavefront).
-__host__ __device__ inline size_t exact_lds_bytes(int V, int threads = NT) {
+__host__ __device__ inline size_t exact_table_offset(int V, int threads = NT) {
     const size_t nvec = ((size_t)V + EXV - 1) / EXV;
     const size_t nchunk = (nvec + threads - 1) / threads;
-    return ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 +
-           nchunk * (threads / WAVE) * sizeof(double);
+    const size_t off = ((sizeof(ExactShared) + 15) & ~size_t(15)) + (((size_t)V + 31) / 32) * 4 + 8 +
+                       nchunk * (threads / WAVE) * sizeof(double);
+    return (off + 15) & ~size_t(15);
+}
+// ... and, last, the table of the exponential.
+__host__ __device__ inline size_t exact_lds_bytes(int V, int threads = NT) {
+    return exact_table_offset(V, threads) + EXP_TABLE_BYTES;
 }
 
 // One residual term: max(0, t_A(x) - g(x)) (or t_A(x) when the residual has no mass).
 __device__ __forceinline__ double resid_term(int x, int xt, int V, float lt, float lg, const uint32_t* mask,
                                              double mt, double mg, double inv_zt, double inv_zg,
-                                             double mass, int zero_resid) {
+                                             double mass, int zero_resid, const double* tab) {
     // branch-free: both exponentials are always evaluated, then selected
     const int xm = x < V ? x : V - 1;
     const bool in_a = (x < V) && ((mask[xm >> 5] >> (xm & 31)) & 1u);
-    double ta = exp_nonpos((double)lt - mt) * inv_zt;
+    double ta = exp_tab((double)lt - mt, tab) * inv_zt;
     ta = in_a ? 0.0 : ta;
     ta = (x == xt) ? mass : ta;
-    const double gv = exp_nonpos((double)lg - mg) * inv_zg;
+    const double gv = exp_tab((double)lg - mg, tab) * inv_zg;
     const double r = zero_resid ? ta : ta - gv;
     return r > 0.0 ? r : 0.0;
 }
@@ -290,6 +647,8 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     const int V = a.V;
     const int k = a.k;
     const int nwords = (V + 31) >> 5;
+    double* tab = reinterpret_cast<double*>(ex + exact_table_offset(V, TNT));
+    for (int i = tid; i < 2 * EXP_TABLE_N; i += TNT) tab[i] = EXP_TABLE_HILO[i];   // published by the first barrier below
     double* wtot = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(mask) + (((size_t)nwords * 4 + 7) & ~size_t(7)));
     const int nvec = (V + EPV - 1) / EPV;
     const int nchunk = (nvec + TNT - 1) / TNT;
@@ -371,8 +730,8 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
             double st = 0.0, sg = 0.0;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                st += exp_nonpos((double)tf[e] - mt);
-                sg += exp_nonpos((double)gf[e] - mg);
+                st += exp_tab((double)tf[e] - mt, tab);
+                sg += exp_tab((double)gf[e] - mg, tab);
             }
             zt += st;
             zg += sg;
@@ -382,12 +741,12 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
     zg = block_sum<TNW>(zg, sh.red2, tid);
 
     // ---- nearest-first walk over the table row ----
-    const double t_tok = exp_nonpos((double)L::glob(trow, xt) - mt) / zt;
+    const double t_tok = exp_tab((double)L::glob(trow, xt) - mt, tab) / zt;
     int a_size;
     double S;
-    exact_walk<LT, TNT>(trow, lds_row, nrow, k, xt, mt, zt, a.divergence, t_tok, delta, sh, tid, &a_size, &S);
+    exact_walk<LT, TNT>(trow, lds_row, nrow, k, xt, mt, zt, a.divergence, t_tok, delta, sh, tid, &a_size, &S, tab);
 
-    const double g_tok = exp_nonpos((double)L::glob(grow, xt) - mg) / zg;
+    const double g_tok = exp_tab((double)L::glob(grow, xt) - mg, tab) / zg;
     const double mass = t_tok + S;
     const bool accepted = (u_acc * g_tok < mass);
     if (tid == 0 && !selected) {
@@ -442,7 +801,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
 #pragma unroll
                 for (int e = 0; e < EPV; ++e)
                     s += resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass,
-                                    zero_resid);
+                                    zero_resid, tab);
                 s = wave_sum(s);
                 if (lane == 0) wtot[c * TNW + wave] = s;
             }
@@ -486,7 +845,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
             double s = 0.0;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                r[e] = resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass, zero_resid);
+                r[e] = resid_term(vi * EPV + e, xt, V, tf[e], gf[e], mask, mt, mg, inv_zt, inv_zg, mass, zero_resid, tab);
                 s += r[e];
             }
             const double incl = wave_scan_incl(s);
@@ -606,8 +965,10 @@ __global__ __launch_bounds__(SEL_NT) void tree_finish(VerifyArgs a, const int32_
 template <typename LT>
 static size_t fast_lds_bytes(int V) {
     const size_t row_bytes = ((size_t)V * sizeof(LT) + 15) & ~size_t(15);
-    const size_t tail = exact_lds_bytes(V) > FAST_SHARED_TAIL ? exact_lds_bytes(V) : FAST_SHARED_TAIL;
-    return row_bytes + FAST_SHARED_HEAD + tail;
+    size_t tail = exact_lds_bytes(V) > FAST_SHARED_TAIL ? exact_lds_bytes(V) : FAST_SHARED_TAIL;
+    const size_t one_pass = one_pass_layout(V).total;
+    if (one_pass > tail) tail = one_pass;
+    return EXP_TABLE_BYTES + row_bytes + FAST_SHARED_HEAD + tail;
 }
 
 // launch == false: only the LDS limits are raised (lantern_prepare), nothing is enqueued.

@@ -80,6 +80,10 @@ struct Lane<float> {
         const uint32_t w = e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
         return __uint_as_float(w);
     }
+    // the vector without its first two elements (the freed places read -inf)
+    __device__ static __forceinline__ uint4 drop2(const uint4& v) {
+        return make_uint4(v.z, v.w, NEG_INF_WORD, NEG_INF_WORD);
+    }
     __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
         return reinterpret_cast<const float*>(row)[x];
     }
@@ -99,6 +103,9 @@ struct Lane<uint16_t> {  // bfloat16 storage
         const int wi = e >> 1;
         const uint32_t w = wi == 0 ? v.x : wi == 1 ? v.y : wi == 2 ? v.z : v.w;
         return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+    __device__ static __forceinline__ uint4 drop2(const uint4& v) {
+        return make_uint4(v.y, v.z, v.w, NEG_INF_WORD);
     }
     __device__ static __forceinline__ float lds(const unsigned char* row, int x) {
         return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[x]) << 16);
@@ -268,10 +275,12 @@ __device__ __forceinline__ double prefix_divergence64(int divergence, double t0,
 // (a function of t_tok = t(xt) and of the inclusive sum) is not below delta.
 // *a_size: slots taken; *S: sum of t over the taken slots other than the token.
 // trow: the target row in global memory; lds_row: the same raw row in LDS, or null.
+// tab: the exponential's table in LDS (exp_tab), or null for the table-free routine.
 template <typename LT, int TNT = NT>
 __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* lds_row, const int32_t* nrow,
                                            int k, int xt, double mt, double zt, int divergence, double t_tok,
-                                           double delta, ExactShared& sh, int tid, int* a_size, double* S) {
+                                           double delta, ExactShared& sh, int tid, int* a_size, double* S,
+                                           const double* tab = nullptr) {
     using L = Lane<LT>;
     double carry = 0.0;
     *a_size = k;
@@ -283,7 +292,8 @@ __device__ __forceinline__ void exact_walk(const LT* trow, const unsigned char* 
         const int n = valid ? nrow[j] : xt;
         const bool self = (n == xt);
         const float ln = lds_row ? L::lds(lds_row, n) : L::glob(trow, n);
-        const double tj = self ? 0.0 : exp_nonpos((double)ln - mt) / zt;
+        const double dj = (double)ln - mt;
+        const double tj = self ? 0.0 : (tab ? exp_tab(dj, tab) : exp_nonpos(dj)) / zt;
         double ctot;
         const double incl = carry + block_scan_incl<TNT / WAVE>(tj, sh.red, tid, &ctot);
         const int fail_j = (valid && !self && !(prefix_divergence64(divergence, t_tok, incl) < delta)) ? j : INT_MAX;

@@ -185,5 +185,5 @@ def test_exp64_host_build_under_sanitizers(tmp_path):
                     os.path.join(ROOT, "tests", "exp64_check.cpp"), "-o", exe, "-lm"], check=True)
     r = subprocess.run([exe], env=ENV, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
-    worst, n_diff, n, specials = (int(x) for x in r.stdout.split())
-    assert worst <= 1 and specials == 1
+    worst, n_diff, n, specials, worst_tab, n_diff_tab, specials_tab = (int(x) for x in r.stdout.split())
+    assert worst <= 1 and specials == 1 and worst_tab <= 1 and specials_tab == 1
