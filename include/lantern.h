@@ -322,7 +322,11 @@ int lantern_verify_greedy_rows(const void* target_logits, lantern_dtype logits_d
  * parent[i] < i.  The paper leaves the rule for siblings to its drafter; the
  * rule here: standing at a node (first the prefix), its children are tried in
  * index order, the first accepted one is taken and the walk goes on from it.
- * With one child per node this is lantern_accept_chains.
+ * With one child per node this is lantern_accept_chains.  With more than one
+ * child per node the walk does NOT preserve the target's law, not even at
+ * delta = 0 or k = 1 where a chain does: every sibling is tested on its own
+ * against the undistorted rows, while law-preserving multi-candidate sampling
+ * would test sibling j against the residual left by siblings 1 .. j-1.
  *
  *   accept, resample  [B*M] int32, as written by lantern_verify_rows;
  *             resample may be NULL: out_next then holds, where it would hold a

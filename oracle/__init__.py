@@ -310,3 +310,78 @@ def build_random(V: int, k: int, seed: int, rows=None, threads: int = 8) -> np.n
                                     _p(out, ctypes.c_int32), int(threads)) != 0:
         raise ValueError("oracle_build_random_rows: bad arguments")
     return out
+
+
+def sibling_group_probs(t, g, tokens, knn_rows, delta: float, u_acc, u_res, divergence: str = "tvd",
+                        want_final: bool = True) -> dict:
+    """One sibling group under the sequential-residual rule, on explicit probabilities (fp64
+    interface: delta is taken as given).  tokens: the siblings' tokens in the order they are tried;
+    knn_rows: [m, k] their table rows.  Returns taken (index or -1), next (token or -1),
+    accept_prob [m] (NaN where not reached) and, with want_final, final_dist [V] = the
+    distribution the following token is drawn from when every sibling is rejected."""
+    lib = _load()
+    D = ctypes.POINTER(ctypes.c_double)
+    I = ctypes.POINTER(ctypes.c_int32)
+    lib.oracle_sibling_group_probs.argtypes = [D, D, ctypes.c_int, ctypes.c_int, I, I, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_double, D, D, I, I, D, D]
+    lib.oracle_sibling_group_probs.restype = ctypes.c_int
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    xs = _as_i32(tokens).reshape(-1)
+    rows = _as_i32(knn_rows)
+    m = xs.shape[0]
+    if rows.ndim != 2 or rows.shape[0] != m:
+        raise ValueError("knn_rows must be [m, k]")
+    ua = np.ascontiguousarray(u_acc, dtype=np.float64).reshape(-1)
+    ur = np.ascontiguousarray(u_res, dtype=np.float64).reshape(-1)
+    taken = np.zeros(1, dtype=np.int32)
+    nxt = np.zeros(1, dtype=np.int32)
+    ap = np.empty(m, dtype=np.float64)
+    fin = np.empty(t.shape[0], dtype=np.float64) if want_final else None
+    rc = lib.oracle_sibling_group_probs(_p(t, ctypes.c_double), _p(g, ctypes.c_double), t.shape[0], m,
+                                        _p(xs, ctypes.c_int32), _p(rows, ctypes.c_int32), rows.shape[1],
+                                        DIVERGENCES[divergence], float(delta), _p(ua, ctypes.c_double),
+                                        _p(ur, ctypes.c_double), _p(taken, ctypes.c_int32), _p(nxt, ctypes.c_int32),
+                                        _p(ap, ctypes.c_double), _p(fin, ctypes.c_double) if want_final else None)
+    if rc != 0:
+        raise ValueError("oracle_sibling_group_probs: bad arguments")
+    return {"taken": int(taken[0]), "next": int(nxt[0]), "accept_prob": ap, "final_dist": fin}
+
+
+def verify_trees_sequential(target_logits, draft_logits, row_index, parent, M: int, draft_tokens, knn, k: int,
+                            delta: float, uniforms, threads: int = 1, divergence: str = "tvd"):
+    """Walk of B draft trees of M candidates under the sequential-residual sibling rule, from logits.
+    Returns (len int32[B], path int32[B, M], next int32[B])."""
+    lib = _load()
+    F = ctypes.POINTER(ctypes.c_float)
+    I = ctypes.POINTER(ctypes.c_int32)
+    lib.oracle_verify_trees_sequential.argtypes = [F, F, ctypes.c_int, ctypes.c_int, ctypes.c_int64, I, I,
+                                                   ctypes.c_int, ctypes.c_int, I, I, ctypes.c_int, ctypes.c_int,
+                                                   ctypes.c_double, F, I, I, I, ctypes.c_int]
+    lib.oracle_verify_trees_sequential.restype = ctypes.c_int
+    tl = _as_f32(target_logits)
+    dl = _as_f32(draft_logits)
+    if tl.ndim != 2 or tl.shape != dl.shape:
+        raise ValueError("logits must be two [R, V] arrays of equal shape")
+    R, V = tl.shape
+    ri = _as_i32(row_index).reshape(-1)
+    par = _as_i32(parent).reshape(-1)
+    tok = _as_i32(draft_tokens).reshape(-1)
+    tab = _as_i32(knn)
+    un = _as_f32(uniforms).reshape(-1)
+    N = ri.shape[0]
+    if N % M or par.shape[0] != N or tok.shape[0] != N or un.shape[0] != 2 * N or tab.size != V * k:
+        raise ValueError("shape mismatch")
+    B = N // M
+    n = np.empty(B, dtype=np.int32)
+    path = np.empty((B, M), dtype=np.int32)
+    nxt = np.empty(B, dtype=np.int32)
+    rc = lib.oracle_verify_trees_sequential(_p(tl, ctypes.c_float), _p(dl, ctypes.c_float), R, V, V,
+                                            _p(ri, ctypes.c_int32), _p(par, ctypes.c_int32), B, M,
+                                            _p(tok, ctypes.c_int32), _p(tab, ctypes.c_int32), int(k),
+                                            DIVERGENCES[divergence], _abi_delta(delta), _p(un, ctypes.c_float),
+                                            _p(n, ctypes.c_int32), _p(path, ctypes.c_int32), _p(nxt, ctypes.c_int32),
+                                            int(threads))
+    if rc != 0:
+        raise ValueError("oracle_verify_trees_sequential: bad arguments")
+    return n, path, nxt

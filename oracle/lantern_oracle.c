@@ -654,6 +654,190 @@ int oracle_accept_trees(const int32_t* accept, const int32_t* resample, const in
 }
 
 /* ------------------------------------------------------------------------- */
+/* Siblings verified one after the other against the residual of the ones     */
+/* before (a second rule for draft trees; Section 2, Algorithm 1)             */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Algorithm 1 tries one drafted token per position and, when it rejects it,
+ * goes on with the residual distribution.  A draft tree offers several tokens
+ * for one position.  The rule of oracle_accept_trees tests each of them
+ * against the same undistorted target, which does not keep the target law even
+ * at k = 1.  The rule here applies Algorithm 1's own step repeatedly: the
+ * siblings x_1 .. x_m share the context's target t and drafter g;
+ *     t_1 = t
+ *     for j = 1 .. m:  verify x_j as Section 4.3 states it, with t_j in place of
+ *                      the target (neighbourhood, mass and acceptance all on t_j);
+ *                      accepted: x_j is taken;
+ *                      rejected: t_{j+1} = the normalised residual of that
+ *                                verification, max(0, t_{j,A} - g) / Z
+ *     all rejected: the token that follows is drawn from t_{m+1}, i.e. it is the
+ *                   resampled token of the last sibling's verification.
+ * With tokens drawn independently from g and k = 1 (or delta = 0) this is
+ * recursive rejection sampling and the emitted token follows t exactly.
+ *
+ * One sibling group on explicit probabilities.  xs[m]: the siblings' tokens in
+ * the order they are tried; nbrs[j*k .. j*k+k): the table row of xs[j];
+ * u_acc[m], u_res[m]: each sibling's own draws.  out_taken: index of the accepted
+ * sibling or -1; out_next: the resampled token when all were rejected, else -1;
+ * accept_prob[m] (optional): the probability of accepting sibling j given that
+ * all before it were rejected (NaN for siblings not reached); final_dist[V]
+ * (optional): t_{m+1}, computed even when a sibling was accepted (as if none were).
+ * Returns 0, or -1 on bad arguments.
+ */
+int oracle_sibling_group_probs(const double* t, const double* g, int V, int m, const int32_t* xs,
+                               const int32_t* nbrs, int k, int divergence, double delta,
+                               const double* u_acc, const double* u_res, int32_t* out_taken,
+                               int32_t* out_next, double* accept_prob, double* final_dist) {
+    if (!t || !g || !xs || !nbrs || !u_acc || !u_res || !out_taken || !out_next) return -1;
+    if (V < 1 || m < 1 || k < 1 || k > V || !(delta >= 0.0)) return -1;
+    if (divergence != 0 && divergence != 1) return -1;
+    for (int j = 0; j < m; ++j)
+        if (!row_args_ok(V, xs[j], nbrs + (size_t)j * k, k)) return -1;
+    double* buf = (double*)malloc(sizeof(double) * 3 * (size_t)V);
+    if (!buf) return -1;
+    double* cur = buf;
+    double* rho = buf + V;
+    double* scratch = buf + 2 * (size_t)V;
+    memcpy(cur, t, sizeof(double) * (size_t)V);
+    int taken = -1;
+    int next = -1;
+    for (int j = 0; j < m; ++j) {
+        if (accept_prob) accept_prob[j] = NAN;
+    }
+    for (int j = 0; j < m; ++j) {
+        int32_t acc, res;
+        double diag[DIAG_COUNT];
+        verify_probs(cur, g, V, xs[j], nbrs + (size_t)j * k, k, divergence, delta, u_acc[j], u_res[j],
+                     &acc, &res, diag, scratch, rho, NULL);
+        if (accept_prob) accept_prob[j] = diag[DIAG_ACCEPT_PROB];
+        if (acc && taken < 0) {
+            taken = j;
+            if (!final_dist) break;
+        }
+        if (!acc && taken < 0) next = res;
+        memcpy(cur, rho, sizeof(double) * (size_t)V);     /* the next sibling's target */
+    }
+    if (final_dist) memcpy(final_dist, cur, sizeof(double) * (size_t)V);
+    *out_taken = taken;
+    *out_next = taken >= 0 ? -1 : next;
+    free(buf);
+    return 0;
+}
+
+/*
+ * Walk of B draft trees of M candidates under the rule above, from logits.
+ * Candidate i of tree b (at b*M + i) reads logit row row_index[b*M+i] of both
+ * matrices, drafts tokens[b*M+i] and owns uniforms[2*(b*M+i) .. +2); parent as
+ * in oracle_accept_trees.  Standing at a node, its children are tried in index
+ * order as one sibling group on the logit rows of the first child; the accepted
+ * child is taken and the walk goes on from it.  out_len, out_path as in
+ * oracle_accept_trees; out_next: the resampled token of the last child when
+ * every child was rejected; -1 when the last node has no child; -2 when a child
+ * that had to be tried is unusable (token, table entry or row index out of
+ * range, unusable logits, or a row index other than the first child's); -3 for
+ * a malformed parent array.  Returns 0, or -1 on bad arguments.
+ */
+int oracle_verify_trees_sequential(const float* target_logits, const float* draft_logits, int R, int V,
+                                   int64_t row_stride, const int32_t* row_index, const int32_t* parent,
+                                   int B, int M, const int32_t* tokens, const int32_t* knn, int k,
+                                   int divergence, double delta, const float* uniforms, int32_t* out_len,
+                                   int32_t* out_path, int32_t* out_next, int threads) {
+    if (divergence != 0 && divergence != 1) return -1;
+    if (B < 0 || M < 1 || R < 0 || V < 1 || k < 1 || k > V || row_stride < V || !(delta >= 0.0)) return -1;
+    if (B == 0) return 0;
+    if (R < 1) return -1;
+    if (!target_logits || !draft_logits || !row_index || !parent || !tokens || !knn || !uniforms ||
+        !out_len || !out_path || !out_next)
+        return -1;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads > 0 ? threads : 1)
+#endif
+    {
+        double* buf = (double*)malloc(sizeof(double) * 4 * (size_t)V);
+        if (!buf) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+            double* cur = buf;
+            double* g = buf + V;
+            double* rho = buf + 2 * (size_t)V;
+            double* scratch = buf + 3 * (size_t)V;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (int b = 0; b < B; ++b) {
+                const int32_t* par = parent + (size_t)b * M;
+                int32_t* path = out_path + (size_t)b * M;
+                for (int j = 0; j < M; ++j) path[j] = -1;
+                int well_formed = 1;
+                for (int i = 0; i < M; ++i)
+                    if (par[i] < -1 || par[i] >= i) well_formed = 0;
+                if (!well_formed) {
+                    out_len[b] = 0;
+                    out_next[b] = -3;
+                    continue;
+                }
+                int node = -1;
+                int len = 0;
+                int next = -1;
+                for (;;) {
+                    int taken = -1;
+                    int group_row = -1;
+                    int have_rows = 0;
+                    int stop = 0;
+                    next = -1;
+                    for (int i = node + 1; i < M && !stop; ++i) {
+                        if (par[i] != node) continue;
+                        size_t c = (size_t)b * M + i;
+                        int r = row_index[c];
+                        int xt = tokens[c];
+                        if (!have_rows) {             /* first child: the group's context */
+                            group_row = r;
+                            have_rows = 1;
+                            int ok = (r >= 0 && r < R);
+                            if (ok) ok = softmax_row(target_logits + (size_t)r * row_stride, V, cur) == 0;
+                            if (ok) ok = softmax_row(draft_logits + (size_t)r * row_stride, V, g) == 0;
+                            if (!ok) { next = -2; stop = 1; break; }
+                        }
+                        if (r != group_row || xt < 0 || xt >= V || !row_args_ok(V, xt, knn + (size_t)xt * k, k)) {
+                            next = -2;
+                            stop = 1;
+                            break;
+                        }
+                        int32_t acc, res;
+                        verify_probs(cur, g, V, xt, knn + (size_t)xt * k, k, divergence, delta,
+                                     (double)uniforms[2 * c], (double)uniforms[2 * c + 1], &acc, &res, NULL,
+                                     scratch, rho, NULL);
+                        if (acc) {
+                            taken = i;
+                            stop = 1;
+                        } else {
+                            next = res;                                  /* so far the last rejected child */
+                            memcpy(cur, rho, sizeof(double) * (size_t)V);  /* the next sibling's target */
+                        }
+                    }
+                    if (taken >= 0) {
+                        path[len] = taken;
+                        len = len + 1;
+                        node = taken;
+                        continue;
+                    }
+                    break;     /* next: -1 no child, -2 unusable, else the last child's resampled token */
+                }
+                out_len[b] = len;
+                out_next[b] = next;
+            }
+        }
+        free(buf);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Random neighbourhoods (Section 5.3.1 and Table 3, the "random selection"   */
 /* row of the ablation on latent proximity measures)                          */
 /* ------------------------------------------------------------------------- */

@@ -115,6 +115,25 @@ int main(int argc, char** argv) {
             wr_i32(rc);
             if (rc == 0) wr(out, 4 * (size_t)(r1 - r0) * k);
             free(out);
+        } else if (op == 8) {   /* tree walk under the sequential-residual sibling rule, from logits */
+            int R = rd_i32(), V = rd_i32(), B = rd_i32(), M = rd_i32(), k = rd_i32(), divergence = rd_i32(),
+                threads = rd_i32();
+            double delta = rd_f64();
+            float* tl = rd(4 * (size_t)R * V);
+            float* dl = rd(4 * (size_t)R * V);
+            int32_t* ri = rd(4 * (size_t)B * M);
+            int32_t* par = rd(4 * (size_t)B * M);
+            int32_t* tok = rd(4 * (size_t)B * M);
+            int32_t* knn = rd(4 * (size_t)V * k);
+            float* un = rd(4 * 2 * (size_t)B * M);
+            int32_t* len = malloc(4 * (size_t)B + 4);
+            int32_t* path = malloc(4 * (size_t)B * M + 4);
+            int32_t* next = malloc(4 * (size_t)B + 4);
+            int rc = oracle_verify_trees_sequential(tl, dl, R, V, V, ri, par, B, M, tok, knn, k, divergence, delta, un,
+                                                    len, path, next, threads);
+            wr_i32(rc);
+            if (rc == 0) { wr(len, 4 * (size_t)B); wr(path, 4 * (size_t)B * M); wr(next, 4 * (size_t)B); }
+            free(tl); free(dl); free(ri); free(par); free(tok); free(knn); free(un); free(len); free(path); free(next);
         } else {
             fprintf(stderr, "unknown opcode %d\n", op);
             return 5;

@@ -179,6 +179,29 @@ def test_rows_from_logits_under_sanitizers(driver, oracle_mod, tmp_path):
     np.testing.assert_array_equal(o[0].reshape(97, 13), oracle_mod.build_random(97, 13, 0xDEADBEEF12345678, threads=2))
 
 
+def test_sequential_sibling_walk_under_sanitizers(driver, oracle_mod, tmp_path):
+    from test_oracle_sibling_pins import _random_tree_inputs
+    rng = np.random.default_rng(21)
+    B, M, V, k = 6, 9, 25, 4
+    parent, tl, dl, row_index, tokens, table, un = _random_tree_inputs(rng, B, M, V, k)
+    tokens[3] = V + 2                                 # an unusable candidate
+    tl[row_index[2 * M], 1] = np.inf
+    s = Stream()
+    for divergence, delta in ((0, 0.1), (1, 0.02)):
+        s.i32(8, B * (M + 1), V, B, M, k, divergence, 3)
+        s.f64(float(np.float32(delta)))
+        s.arr(tl, np.float32); s.arr(dl, np.float32); s.arr(row_index, np.int32); s.arr(parent, np.int32)
+        s.arr(tokens, np.int32); s.arr(table, np.int32); s.arr(un, np.float32)
+        s.readers.append([(np.int32, B), (np.int32, B * M), (np.int32, B)])
+    for (rc, o), (divergence, delta) in zip(s.run(driver, tmp_path), (("tvd", 0.1), ("jsd", 0.02))):
+        assert rc == 0
+        n, path, nxt = oracle_mod.verify_trees_sequential(tl, dl, row_index, parent, M, tokens, table, k, delta, un,
+                                                          threads=2, divergence=divergence)
+        np.testing.assert_array_equal(o[0], n)
+        np.testing.assert_array_equal(o[1].reshape(B, M), path)
+        np.testing.assert_array_equal(o[2], nxt)
+
+
 def test_exp64_host_build_under_sanitizers(tmp_path):
     exe = str(tmp_path / "exp64_check_san")
     subprocess.run(["g++", *SAN, "-ffp-contract=off", "-I", os.path.join(ROOT, "paper_2410_03355_amd", "csrc"),
