@@ -172,8 +172,10 @@ __device__ void greedy_exact_row(const GreedyArgs& a, int row, unsigned char* ex
     }
 }
 
-// fp32 path.  FULL: the row fills all NV vector slots of every thread.
-template <typename LT, int NV, bool FULL>
+// fp32 path.  FULL: the row fills all NV vector slots of every thread.  VT: the token's table row
+// can be read with 16-byte loads (a kernel of its own for the other case: a load that only one of
+// two paths issues makes the statically placed wait counters wait for every load).
+template <typename LT, int NV, bool FULL, bool VT>
 __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
@@ -189,12 +191,14 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     const int V = a.V;
     const int k = a.k;
     const int nvec = V / EPV;
-    const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
     const int row = verification_of_block(blockIdx.x, a.N, a.row_index != nullptr);
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
-    // ---- stream the target row: NV 16-byte loads per thread, coalesced ----
+    // ---- loads, the token first: its table row's address depends on it, and that dependent load
+    // should be in flight together with the streamed row ----
+    const int xt = a.tokens[row];
+    // stream the target row: NV 16-byte loads per thread, coalesced
     uint4 T[NV];
     {
         const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride);
@@ -205,21 +209,21 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
             else T[c] = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
         }
     }
-    const int xt = a.tokens[row];
     const bool tok_ok = (unsigned)xt < (unsigned)V;
     const int xs = tok_ok ? xt : 0;
     const int32_t* nrow = a.knn + (int64_t)xs * k;
-    int nb[4];
+    int nb[4];   // table slots 4*tid .. 4*tid+3 (unspecified where the slot is beyond k: every use checks)
     {
         const int j0 = tid * 4;
-        if (nvec_ok && j0 + 3 < k) {
-            const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
+        if (VT) {   // k a multiple of four: loaded unconditionally from a clamped slot, no branch around the load
+            const int4 q = *reinterpret_cast<const int4*>(nrow + min(j0, k - 4));
             nb[0] = q.x; nb[1] = q.y; nb[2] = q.z; nb[3] = q.w;
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
         }
     }
+    __builtin_amdgcn_sched_barrier(0);   // every load of the row is issued before anything waits for one
 
     // ---- raw row to LDS; reference = maximum over vector slot 0 of every thread ----
 #pragma unroll
@@ -354,12 +358,23 @@ static hipError_t launch_greedy_nv(const GreedyArgs& a, hipStream_t stream, bool
     const size_t tail = greedy_exact_lds_bytes(a.V) > GREEDY_SHARED_TAIL ? greedy_exact_lds_bytes(a.V) : GREEDY_SHARED_TAIL;
     const size_t lds = row_bytes + GREEDY_SHARED_HEAD + tail;
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    const hipError_t e = full ? allow_lds<&greedy_fast<LT, NV, true>>(lds) : allow_lds<&greedy_fast<LT, NV, false>>(lds);
-    if (e != hipSuccess || !launch) return e;
-    if (full)
-        hipLaunchKernelGGL((greedy_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
+    const bool vt = ((a.k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
+    if (!launch) {   // every instantiation may be needed later
+        hipError_t e = allow_lds<&greedy_fast<LT, NV, true, true>>(lds);
+        if (e == hipSuccess) e = allow_lds<&greedy_fast<LT, NV, false, true>>(lds);
+        if (e == hipSuccess) e = allow_lds<&greedy_fast<LT, NV, false, false>>(lds);
+        return e;
+    }
+    const hipError_t e = (full && vt) ? allow_lds<&greedy_fast<LT, NV, true, true>>(lds)
+                         : vt         ? allow_lds<&greedy_fast<LT, NV, false, true>>(lds)
+                                      : allow_lds<&greedy_fast<LT, NV, false, false>>(lds);
+    if (e != hipSuccess) return e;
+    if (full && vt)
+        hipLaunchKernelGGL((greedy_fast<LT, NV, true, true>), dim3(a.N), dim3(NT), lds, stream, a);
+    else if (vt)
+        hipLaunchKernelGGL((greedy_fast<LT, NV, false, true>), dim3(a.N), dim3(NT), lds, stream, a);
     else
-        hipLaunchKernelGGL((greedy_fast<LT, NV, false>), dim3(a.N), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((greedy_fast<LT, NV, false, false>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
 }
 

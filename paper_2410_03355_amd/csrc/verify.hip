@@ -393,11 +393,14 @@ struct RowMeta {
     int xt;        // draft token
     float u_acc;   // acceptance draw
     float lg_tok;  // draft logit of the token
-    int nb[4];     // table slots 4*tid .. 4*tid+3
+    int nb[4];     // table slots 4*tid .. 4*tid+3 (unspecified where the slot is beyond k)
 };
 
 // fp32 path, one workgroup per row.
 // FULL: the row fills all NV vector slots of every thread (no bounds checks).
+// VT: the token's table row can be read with 16-byte loads (k a multiple of four, table 16-byte
+// aligned); the other case is a kernel of its own because a load that only one of two paths
+// issues makes the hardware wait counters, which are placed statically, wait for every load.
 //
 // Exponentials are taken as 2^(l*log2e - c) with one reference c per row, common to all
 // terms of that row, so its own rounding cancels in every comparison.  The reference is
@@ -405,7 +408,7 @@ struct RowMeta {
 // rather than the row maximum: any element of the row works, because the sum then holds
 // a term equal to one (Z >= 1) and every term is at most Z; rows whose sum exceeds 2^46
 // (an element more than 32 above the reference) are left to the exact path.
-template <typename LT, int NV, bool FULL>
+template <typename LT, int NV, bool FULL, bool VT>
 __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs a) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
@@ -421,12 +424,18 @@ __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs 
     const int V = a.V;
     const int k = a.k;
     const int nvec = V / EPV;
-    const bool nvec_ok = ((k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
     const int row = verification_of_block(blockIdx.x, a.N, a.row_index != nullptr);
     bool row_ok;
     const int lrow = logit_row(a.row_index, a.R, row, &row_ok);
 
-    // ---- stream both rows: NV 16-byte loads per thread and row, coalesced ----
+    // ---- loads, in the order their results are needed to issue further loads ----
+    // Vector loads return in order.  The token comes first: the address of its table row depends on
+    // it, and that second, dependent load should be in flight together with the streamed rows, not
+    // start after the last of them has arrived.
+    RowMeta m;
+    m.xt = a.tokens[row];
+    m.u_acc = a.uniforms[2 * (int64_t)row];
+    // stream both rows: NV 16-byte loads per thread and row, coalesced
     uint4 T[NV], G[NV];
     {
         const uint4* tv = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.target) + (int64_t)lrow * a.stride);
@@ -443,25 +452,27 @@ __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs 
             }
         }
     }
-    // token, its table slots 4*tid .. 4*tid+3, acceptance draw, draft logit of the token
-    RowMeta m;
+    // the token's table slots 4*tid .. 4*tid+3 and its draft logit
     {
-        m.xt = a.tokens[row];
         const int xs0 = ((unsigned)m.xt < (unsigned)V) ? m.xt : 0;
         const int32_t* nrow = a.knn + (int64_t)xs0 * k;
         const int j0 = tid * 4;
-        if (nvec_ok && j0 + 3 < k) {
-            const int4 q = *reinterpret_cast<const int4*>(nrow + j0);
+        if (VT) {        // k a multiple of four, so a thread's four slots are all inside k or all beyond
+            // loaded unconditionally from a clamped slot (no branch around the load, so nothing waits
+            // for it here); what threads beyond k read is never looked at (every use checks the slot
+            // number against k)
+            const int4 q = *reinterpret_cast<const int4*>(nrow + min(j0, k - 4));
             m.nb[0] = q.x; m.nb[1] = q.y; m.nb[2] = q.z; m.nb[3] = q.w;
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) m.nb[q] = (j0 + q < k) ? nrow[j0 + q] : 0;
         }
-        m.u_acc = a.uniforms[2 * (int64_t)row];
         m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
     }
     // this thread's entry of the exponential's table, for the fp64 path (cache-resident, 2 KB in all)
     const double tab_elem = EXP_TABLE_HILO[tid];
+    // every load of the row is issued before anything waits for one of them
+    __builtin_amdgcn_sched_barrier(0);
 
     {
         const int xt = m.xt;
@@ -976,12 +987,24 @@ template <typename LT, int NV>
 static hipError_t launch_fast_nv(const VerifyArgs& a, hipStream_t stream, bool launch) {
     const size_t lds = fast_lds_bytes<LT>(a.V);
     const bool full = a.V == NV * NT * Lane<LT>::EPV;
-    const hipError_t e = full ? allow_lds<&verify_fast<LT, NV, true>>(lds) : allow_lds<&verify_fast<LT, NV, false>>(lds);
-    if (e != hipSuccess || !launch) return e;
-    if (full)
-        hipLaunchKernelGGL((verify_fast<LT, NV, true>), dim3(a.N), dim3(NT), lds, stream, a);
+    // three instantiations: whole rows with a vector-readable table, ragged rows with one, and the rest
+    const bool vt = ((a.k & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.knn) & 15) == 0);
+    if (!launch) {   // every one of them may be needed later
+        hipError_t e = allow_lds<&verify_fast<LT, NV, true, true>>(lds);
+        if (e == hipSuccess) e = allow_lds<&verify_fast<LT, NV, false, true>>(lds);
+        if (e == hipSuccess) e = allow_lds<&verify_fast<LT, NV, false, false>>(lds);
+        return e;
+    }
+    const hipError_t e = (full && vt) ? allow_lds<&verify_fast<LT, NV, true, true>>(lds)
+                         : vt         ? allow_lds<&verify_fast<LT, NV, false, true>>(lds)
+                                      : allow_lds<&verify_fast<LT, NV, false, false>>(lds);
+    if (e != hipSuccess) return e;
+    if (full && vt)
+        hipLaunchKernelGGL((verify_fast<LT, NV, true, true>), dim3(a.N), dim3(NT), lds, stream, a);
+    else if (vt)
+        hipLaunchKernelGGL((verify_fast<LT, NV, false, true>), dim3(a.N), dim3(NT), lds, stream, a);
     else
-        hipLaunchKernelGGL((verify_fast<LT, NV, false>), dim3(a.N), dim3(NT), lds, stream, a);
+        hipLaunchKernelGGL((verify_fast<LT, NV, false, false>), dim3(a.N), dim3(NT), lds, stream, a);
     return hipGetLastError();
 }
 
