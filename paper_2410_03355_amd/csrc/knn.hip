@@ -684,13 +684,21 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
                                cb, a.V, a.d, r0, a.metric, dist);
         }
         const float* nsel = mfma && a.metric == 0 ? norms : nullptr;
-        // candidate capacity: 2048 slots (24 KB of LDS) when k allows, else 4096
-        const bool small_cap = (a.k - 1) + 8 + (a.k - 1) / 128 <= 2048;
+        // candidate capacity: the smallest of 256 / 1024 / 2048 / 4096 slots that holds k-1+pad.  The
+        // selection is bound by the latency of its many short phases, so its throughput is the number
+        // of workgroups a compute unit holds at once, and that number is set by this LDS footprint
+        // (12 bytes a slot).
+        const int want_slots = (a.k - 1) + 8 + (a.k - 1) / 128;
 #define LANTERN_LAUNCH_SELECT(NKV, CAPV)                                                                    \
         hipLaunchKernelGGL((knn_select<CT, NKV, CAPV>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k,  \
                            a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
 #define LANTERN_LAUNCH_SELECT_NK(NKV)                                                                       \
-        do { if (small_cap) LANTERN_LAUNCH_SELECT(NKV, 2048); else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP); } while (0)
+        do {                                                                                                \
+            if (want_slots <= 256) LANTERN_LAUNCH_SELECT(NKV, 256);                                         \
+            else if (want_slots <= 1024) LANTERN_LAUNCH_SELECT(NKV, 1024);                                  \
+            else if (want_slots <= 2048) LANTERN_LAUNCH_SELECT(NKV, 2048);                                  \
+            else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP);                                                      \
+        } while (0)
         if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8);
         else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32);
         else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64);
