@@ -107,6 +107,159 @@ struct SlotTest {
     }
 };
 
+// ---- the walk with every wavefront classifying its own slots ----
+// The same walk split differently: between the barrier that publishes the wavefront totals and the
+// one that publishes the per-wavefront results, every wavefront compares the four slots each of its
+// threads holds in registers; afterwards every thread combines the four results.  No wavefront
+// waits while another one scans all 1024 slots, and the serial work no longer lands on the one
+// SIMD that hosts wavefront 0 of every resident workgroup.
+
+// What a thread keeps of its slots 4*tid .. 4*tid+3 between the halves of the walk.
+struct SlotTerms {
+    float incl[4];   // inclusive sums within the wavefront, lane order
+    float excl;      // the sum before the thread's first slot, within the wavefront
+    unsigned skip;   // bit q: slot 4*tid+q is the token itself or beyond k
+};
+
+// All threads, before the barrier that publishes wtot / wbad.
+template <typename LT>
+__device__ __forceinline__ SlotTerms slot_terms(const int (&nb)[4], int xt, int k, int V, const int32_t* nrow,
+                                                const unsigned char* s_row, float ct, float* wtot, int* wbad) {
+    using L = Lane<LT>;
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
+    SlotTerms st;
+    float run = 0.f;
+    st.skip = 0;
+    int bad = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bool valid = tid * 4 + q < k;
+        const int n = nb[q];
+        const bool inr = (unsigned)n < (unsigned)V;
+        if (valid && !inr) bad = 1;
+        float e = 0.f;
+        if (n == xt || !valid) st.skip |= 1u << q;
+        else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
+        run += e;
+        st.incl[q] = run;
+    }
+    for (int j = NT * 4 + tid; j < k; j += NT)     // entries the walk may never reach are range-checked too
+        if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
+    const float incl = wave_scan_incl(run);
+    st.excl = wave_prev(incl, 0.f);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) st.incl[q] += st.excl;
+    bad = wave_or(bad);
+    if (lane == WAVE - 1) wtot[wave] = incl;
+    if (lane == 0) wbad[wave] = bad;
+    return st;
+}
+
+// Per-wavefront results of the classification: first slot not definitely passing (and the sum
+// before it), first slot definitely failing; INT_MAX when there is none.
+struct WaveCut {
+    int* np;
+    int* df;
+    float* s;
+};
+
+// All threads, after the barrier.  woff: sum of the totals of the wavefronts before this one.
+__device__ __forceinline__ void classify_slots(const SlotTerms& st, const SlotTest& test, float woff,
+                                               const WaveCut& out) {
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
+    int my_np = INT_MAX, my_df = INT_MAX;
+    float my_s = 0.f;
+    float before = woff + st.excl;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float I = woff + st.incl[q];
+        if (!((st.skip >> q) & 1u)) {
+            bool passes, fails;
+            test.classify(I, &passes, &fails);
+            if (my_np == INT_MAX && !passes) { my_np = tid * 4 + q; my_s = before; }
+            if (my_df == INT_MAX && fails) my_df = tid * 4 + q;
+        }
+        before = I;
+    }
+    const int w_np = wave_min(my_np);
+    const int w_df = wave_min(my_df);
+    float s_cut = 0.f;
+    if (w_np != INT_MAX) {
+        const unsigned long long owner = __ballot(my_np == w_np);
+        s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s), __ffsll((long long)owner) - 1));
+    }
+    if (lane == 0) {
+        out.np[wave] = w_np;
+        out.df[wave] = w_df;
+        out.s[wave] = s_cut;
+    }
+}
+
+// Slots beyond the first 1024, walked by one wavefront 1024 at a time (k > 1024 and no cut among
+// the first 1024).  carry: the sum over the first 1024 slots.  Returns like scan_cut.
+template <typename LT>
+__device__ __forceinline__ CutResult walk_tail(const SlotTest& test, float carry, int xt, int xs, int k, int V,
+                                               const int32_t* knn, const unsigned char* s_row, float ct) {
+    using L = Lane<LT>;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int32_t* nrow = knn + (int64_t)xs * k;
+    int first_np = INT_MAX, first_df = INT_MAX, bad = 0;
+    float s_cut = 0.f;
+    for (int base = NT * 4; base < k; base += WAVE * SPL) {
+        const int j0 = base + lane * SPL;
+        float ev[SPL];
+        float run = 0.f;
+        unsigned skip = 0;
+#pragma unroll
+        for (int q = 0; q < SPL; ++q) {
+            const bool valid = j0 + q < k;
+            const int n = valid ? nrow[j0 + q] : 0;
+            const bool inr = (unsigned)n < (unsigned)V;
+            if (valid && !inr) bad = 1;
+            float e = 0.f;
+            if (n == xt || !valid) skip |= 1u << q;
+            else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
+            ev[q] = e;
+            run += e;
+        }
+        const float incl = wave_scan_incl(run);
+        const float ctot = lane63_f(incl);
+        float I = carry + wave_prev(incl, 0.f);
+        int my_np = INT_MAX, my_df = INT_MAX;
+        float my_s = 0.f;
+#pragma unroll
+        for (int q = 0; q < SPL; ++q) {
+            const float bef = I;
+            I += ev[q];
+            if (!((skip >> q) & 1u)) {
+                bool passes, fails;
+                test.classify(I, &passes, &fails);
+                if (my_np == INT_MAX && !passes) { my_np = j0 + q; my_s = bef; }
+                if (my_df == INT_MAX && fails) my_df = j0 + q;
+            }
+        }
+        const int w_np = wave_min(my_np);
+        if (w_np != INT_MAX) {
+            const unsigned long long owner = __ballot(my_np == w_np);
+            first_np = w_np;
+            first_df = wave_min(my_df);
+            s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s), __ffsll((long long)owner) - 1));
+            break;
+        }
+        carry += ctot;
+    }
+    CutResult r;
+    r.definite = (first_np == INT_MAX) || (first_np == first_df);
+    r.a_size = (first_np == INT_MAX) ? k : first_np;
+    r.S = (first_np == INT_MAX) ? carry : s_cut;
+    r.bad = wave_or(bad);
+    return r;
+}
+
 // Wavefront 0, after the barrier.  Zt: sum of the unnormalised target terms; e_tx: the
 // unnormalised term of the token itself (used by the Jensen-Shannon bound only).
 template <typename LT>

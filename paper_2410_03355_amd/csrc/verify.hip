@@ -42,10 +42,10 @@ struct FastShared {
     float wsum_t[NW], wsum_g[NW];   // per-wave sums of exponentials
     float wtot[NW];                 // per-wave totals of the neighbour terms (first 1024 slots)
     int wbad[NW];                   // a table entry outside [0,V)
-    int settled;                    // row settled by the fp32 path
-    int regs_ok;                    // not settled, but usable, sums in range and the cut definite
-    int a_size;                     // slots taken into A (valid when regs_ok)
-    int pad;
+    int cut_np[NW];                 // per wavefront: first slot not definitely inside the bound,
+    int cut_df[NW];                 //   first slot definitely outside it,
+    float cut_s[NW];                //   sum before the former
+    int tail[4];                    // k > 1024: the result of the walk beyond slot 1024 (a_size, S, definite, bad)
     // from here on the memory is reused by the exact path once the fp32 decision is taken
     float gs[NT * 4];               // inclusive sums of the neighbour terms within their wavefront
     unsigned gskip[NT];             // bit q: slot 4*tid+q is the token itself or beyond k
@@ -74,8 +74,9 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
 // (at most 64) segment masses finds the segment that holds the draw, and that segment alone is
 // re-evaluated token by token.
 // No global load sits inside the pass (under a saturated memory system each costs microseconds):
-// the drafter's row is still in the registers of the fp32 pass, the target row in LDS, the first
-// 1024 table slots in registers, and the table of the exponential was fetched with the row.
+// the drafter's row is fetched again, all of it at once, before the pass starts (keeping it in
+// registers from the fp32 pass on would cost that pass registers it does not have), the target row
+// is in LDS, the first 1024 table slots in registers.
 constexpr int AMB_CAP = 40;          // tokens whose residual sign fp32 leaves open (about one per row)
 constexpr double TAU_SIGN = 2.0e-5;  // covers the errors of the two fp32 sums in the sign test (<= 8.8e-6 together)
 
@@ -152,15 +153,15 @@ __device__ __forceinline__ void one_pass_token(OnePassAcc& acc, float lt, float 
     }
 }
 
-// s_row: raw target row in LDS.  G: the drafter's row as the fp32 pass loaded it (consumed here).
+// s_row: raw target row in LDS.
 // nb: table slots 4*tid .. 4*tid+3.  ref_t, ref_g: the fp32 pass's reference logits; Zt32, Zg32:
 // its sums; a_size: its (definite) cut.
-// tab_elem: entry tid of EXP_TABLE_HILO; tab_lds: where the table goes in LDS.
+// tab_lds: where the exponential's table goes in LDS.
 template <typename LT, int NV, bool FULL>
-__device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int lrow, uint4 (&G)[NV],
+__device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int lrow,
                                                const int (&nb)[4], float ref_t, float ref_g,
                                                float Zt32, float Zg32, int a_size, int xt, float lg_tok, float u_acc32,
-                                               double tab_elem, unsigned char* tab_lds, unsigned char* ex,
+                                               unsigned char* tab_lds, unsigned char* ex,
                                                const unsigned char* s_row) {
     using L = Lane<LT>;
     constexpr int EPV = L::EPV;
@@ -181,9 +182,18 @@ __device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int
     const int nwords = (V + 31) >> 5;
     const double rt = (double)ref_t, rg = (double)ref_g;
     const float u_res32 = a.uniforms[2 * (int64_t)row + 1];  // in flight during the pass
+    // the drafter's row, every load issued now; it arrives while the table and the mask are set up
+    const uint4* gsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride);
+    uint4 G[NV];
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int vi = c * NT + tid;
+        G[c] = (FULL || vi < nvec) ? gsrc[vi]
+                                   : make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
+    }
 
     // ---- table of the exponential, empty mask, empty list ----
-    tab[tid] = tab_elem;                                     // 2 * 128 doubles, one per thread
+    tab[tid] = EXP_TABLE_HILO[tid];                          // 2 * 128 doubles, one per thread (cache-resident)
     for (int w = tid; w < nwords; w += NT) mask[w] = 0u;
     if (tid == 0) *amb_count = 0;
     __syncthreads();
@@ -322,8 +332,7 @@ __device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int
         const int x0 = vi * EPV;
         const bool live = FULL || vi < nvec;
         const uint4 ninf = make_uint4(L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD, L::NEG_INF_WORD);
-        const uint4* gsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride);
-        const uint4 gv = live ? gsrc[vi] : ninf;             // the one reload: this segment of the drafter's row
+        const uint4 gv = live ? gsrc[vi] : ninf;             // this segment of the drafter's row, once more
         const uint4 tv = live ? reinterpret_cast<const uint4*>(s_row)[vi] : ninf;
         const unsigned in_a = live ? (mask[x0 >> 5] >> (x0 & 31)) & ((1u << EPV) - 1u) : 0u;
         double r[EPV];
@@ -469,8 +478,6 @@ __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs 
         }
         m.lg_tok = L::glob(reinterpret_cast<const LT*>(a.draft) + (int64_t)lrow * a.stride, xs0);
     }
-    // this thread's entry of the exponential's table, for the fp64 path (cache-resident, 2 KB in all)
-    const double tab_elem = EXP_TABLE_HILO[tid];
     // every load of the row is issued before anything waits for one of them
     __builtin_amdgcn_sched_barrier(0);
 
@@ -532,69 +539,90 @@ __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs 
         sg = wave_sum(sg);
 
         // ---- neighbour terms of slots 4*tid .. 4*tid+3, scanned within the wavefront ----
-        const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
-        scan_publish<LT>(m.nb, xt, k, V, a.knn + (int64_t)xs * k, s_row, ct, scan);
+        const SlotTerms slots = slot_terms<LT>(m.nb, xt, k, V, a.knn + (int64_t)xs * k, s_row, ct, sh.wtot, sh.wbad);
         if (lane == 0) { sh.wsum_t[wave] = st; sh.wsum_g[wave] = sg; }
-        __syncthreads();  // sums and neighbour partial sums are published
+        __syncthreads();  // sums and wavefront totals of the neighbour terms are published
 
-        // ---- wavefront 0: cut, mass, acceptance ----
-        if (wave == 0) {
-            float Zt = 0.f, Zg = 0.f;
+        // ---- every wavefront: the bound on its own slots ----
+        float Zt = 0.f, Zg = 0.f, woff = 0.f, run_off = 0.f;
+        int bad = (tok_ok && row_ok) ? 0 : 1;
 #pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                Zt += sh.wsum_t[w];
-                Zg += sh.wsum_g[w];
-            }
-            const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
-            const CutResult cut = scan_cut<LT>(Zt, a.divergence, a.delta, e_tx, xt, xs, k, V, a.knn, s_row, ct, scan);
-            const int bad = cut.bad | ((tok_ok && row_ok) ? 0 : 1);
-            const bool cut_definite = cut.definite;
-            const int a_size = cut.a_size;
-            const float S = cut.S;
-            const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
-            const float MA = e_tx + S;                // mass * Zt
-            const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
-            const float rhs = MA * Zg;                // mass  * Zt * Zg
-            const float slack = acc_slack(k);
-            const bool accept = (lhs + slack) < rhs * (1.f - TAU_ACC);
-            // a definite rejection settles the row only when no resampled token is asked for
-            const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + slack);
-            // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
-            const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
-            const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
-            if (lane == 0) {
-                // with the resampled token wanted, a usable row with a definite cut is finished in
-                // fp64 from the registers
-                sh.regs_ok = (!settled && !bad && sums_ok && cut_definite && a.mode == VERIFY_FULL) ? 1 : 0;
-                sh.a_size = a_size;
-                if (settled) {
-                    a.out_accept[row] = accept ? 1 : 0;
-                    if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
-                    const float mass = MA / Zt;
-                    const float gx = e_gx / Zg;
-                    if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
-                    if (a.out_mass) a.out_mass[row] = mass;
-                    if (a.out_gtok) a.out_gtok[row] = gx;
-                    if (a.out_asize) a.out_asize[row] = a_size;
-                    if (a.out_path) a.out_path[row] = 0;
-                }
-                sh.settled = settled ? 1 : 0;
-            }
+        for (int w = 0; w < NW; ++w) {
+            Zt += sh.wsum_t[w];
+            Zg += sh.wsum_g[w];
+            if (w < wave) woff += sh.wtot[w];
+            run_off += sh.wtot[w];
+            bad |= sh.wbad[w];
         }
-        __syncthreads();  // the decision is published; wavefront 0 is done with the LDS row
-        if (!sh.settled) {
-            // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in LDS
-            if (sh.regs_ok) {
-                float Zt = 0.f, Zg = 0.f;
+        const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
+        SlotTest test;
+        {
+            const float R = a.delta * Zt;             // divergence of the prefix, times Zt, < delta * Zt
+            test.divergence = a.divergence;
+            test.e_tx = e_tx;
+            test.lo = R * (1.f - TAU_CUT) - ABS_SLACK;
+            test.hi = R * (1.f + TAU_CUT) + ABS_SLACK;
+        }
+        classify_slots(slots, test, woff, WaveCut{sh.cut_np, sh.cut_df, sh.cut_s});
+        __syncthreads();  // the wavefronts' results are published
+
+        // ---- every thread: the cut, the mass, the acceptance test (same inputs, same result) ----
+        int first_np = INT_MAX, first_df = INT_MAX;
+        float s_cut = 0.f;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    Zt += sh.wsum_t[w];
-                    Zg += sh.wsum_g[w];
+        for (int w = NW - 1; w >= 0; --w) {
+            if (sh.cut_np[w] != INT_MAX) { first_np = sh.cut_np[w]; s_cut = sh.cut_s[w]; }
+            first_df = min(first_df, sh.cut_df[w]);
+        }
+        bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
+        int a_size = (first_np == INT_MAX) ? k : first_np;
+        float S = (first_np == INT_MAX) ? run_off : s_cut;
+        if (first_np == INT_MAX && k > NT * 4) {      // uniform: the walk goes on beyond slot 1024
+            if (wave == 0) {
+                const CutResult tail = walk_tail<LT>(test, run_off, xt, xs, k, V, a.knn, s_row, ct);
+                if (lane == 0) {
+                    sh.tail[0] = tail.a_size;
+                    sh.tail[1] = __float_as_int(tail.S);
+                    sh.tail[2] = tail.definite ? 1 : 0;
+                    sh.tail[3] = tail.bad;
                 }
-                const int a_size = sh.a_size;
-                __syncthreads();   // every thread has read the head before the region behind it is reused
-                exact_one_pass<LT, NV, FULL>(a, row, lrow, G, m.nb, rt, rg, Zt, Zg, a_size, xt, m.lg_tok, m.u_acc,
-                                             tab_elem, smem, ex_lds, s_row);
+            }
+            __syncthreads();
+            a_size = sh.tail[0];
+            S = __int_as_float(sh.tail[1]);
+            cut_definite = sh.tail[2] != 0;
+            bad |= sh.tail[3];
+        }
+        const float e_gx = hw_exp2(__builtin_fmaf(m.lg_tok, LOG2E_F, -cg));
+        const float MA = e_tx + S;                // mass * Zt
+        const float lhs = m.u_acc * e_gx * Zt;    // u * g(xt) * Zt * Zg
+        const float rhs = MA * Zg;                // mass  * Zt * Zg
+        const float slack = acc_slack(k);
+        const bool accept = (lhs + slack) < rhs * (1.f - TAU_ACC);
+        // a definite rejection settles the row only when no resampled token is asked for
+        const bool reject = (a.mode == VERIFY_DECIDE) && (lhs * (1.f - TAU_ACC) > rhs + slack);
+        // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
+        const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
+        const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
+        if (settled) {
+            if (tid == 0) {
+                a.out_accept[row] = accept ? 1 : 0;
+                if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
+                const float mass = MA / Zt;
+                const float gx = e_gx / Zg;
+                if (a.out_prob) a.out_prob[row] = fminf(1.f, mass / gx);
+                if (a.out_mass) a.out_mass[row] = mass;
+                if (a.out_gtok) a.out_gtok[row] = gx;
+                if (a.out_asize) a.out_asize[row] = a_size;
+                if (a.out_path) a.out_path[row] = 0;
+            }
+        } else {
+            // not settled in fp32: this workgroup evaluates the row in fp64; the raw target row stays in
+            // LDS.  With the resampled token wanted, a usable row with a definite cut is finished in one
+            // pass from the registers.
+            if (!bad && sums_ok && cut_definite && a.mode == VERIFY_FULL) {
+                exact_one_pass<LT, NV, FULL>(a, row, lrow, m.nb, rt, rg, Zt, Zg, a_size, xt, m.lg_tok, m.u_acc,
+                                             smem, ex_lds, s_row);
             } else {
                 exact_row<LT, true>(a, row, ex_lds, s_row, false, 0.f, 0.f);
             }
