@@ -604,7 +604,7 @@ __global__ __launch_bounds__(NT, (NV <= 8 ? 4 : 2)) void verify_fast(VerifyArgs 
         // sums in [1, 2^46]: every term is within 32 of the reference (NaN fails both tests)
         const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX) && (Zg >= 1.f) && (Zg <= Z_MAX);
         const bool settled = !bad && sums_ok && cut_definite && (accept || reject);
-        if (settled) {
+        if (__builtin_expect(settled, 1)) {
             if (tid == 0) {
                 a.out_accept[row] = accept ? 1 : 0;
                 if (a.mode == VERIFY_FULL) a.out_resample[row] = -1;
