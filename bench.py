@@ -62,7 +62,7 @@ class Runner:
         self.out_res = [torch.empty(cfg.rows, dtype=torch.int32, device=dev) for _ in range(nbuf)]
         out_acc, out_res = self.out_acc, self.out_res
         self.tree_info = {}
-        if mode == "tree":
+        if mode in ("tree", "tree_seq"):
             import numpy as np
             from synth import trees
             M = 60
@@ -85,6 +85,22 @@ class Runner:
                               "distinct_logit_rows": self.distinct_rows}
             self.probe_src = [(t_[0].target_logits, t_[0].draft_logits) for t_ in tb]
             self.keep = (tb, parent)
+
+            if mode == "tree_seq":
+                need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, cfg.V))
+                work = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+                self.keep = (tb, parent, work)
+
+                def step_seq(i):
+                    st_, ri, tok, un = tb[i % nbuf]
+                    rc = lib.lantern_verify_trees_sequential(
+                        st_.target_logits.data_ptr(), st_.draft_logits.data_ptr(), dcode, B * (M + 1), cfg.V, cfg.V,
+                        ri.data_ptr(), parent.data_ptr(), B, M, tok.data_ptr(), knn.data_ptr(), cfg.k, div, delta,
+                        un.data_ptr(), t_len.data_ptr(), t_path.data_ptr(), t_next.data_ptr(), work.data_ptr(),
+                        work.numel(), stream.cuda_stream)
+                    assert rc == 0, rc
+                self.step = step_seq
+                return
 
             def step(i):
                 st_, ri, tok, un = tb[i % nbuf]
@@ -135,7 +151,7 @@ class Runner:
     def algorithmic_bytes(self) -> int:
         cfg = self.cfg
         lb = 2 if cfg.logit_dtype == "bf16" else 4
-        if self.mode == "tree":   # every distinct pair of logit rows once; per verification the table row and the small items
+        if self.mode in ("tree", "tree_seq"):   # every distinct pair of logit rows once; per verification the table row and the small items
             return 2 * cfg.V * lb * self.distinct_rows + (4 * cfg.k + 24) * self.rows
         if self.mode == "greedy":  # one logit row, the table row, token, two outputs
             return (cfg.V * lb + 4 * cfg.k + 12) * self.rows
@@ -143,6 +159,8 @@ class Runner:
 
     def accepted_fraction(self, steps: int) -> float:
         import torch
+        if self.mode == "tree_seq":   # no per-candidate decisions: the accepted nodes over all candidates
+            return float(self.t_len.float().sum().item()) / self.rows
         acc_all = torch.stack(self.out_acc[: min(self.nbuf, steps)])[:, : self.rows]
         return float((acc_all == 1).float().mean().item())
 
@@ -204,11 +222,12 @@ def main() -> int:
                     help="stress is the headline; llamagen_step (one tree's 60 candidates per call) and tiny are "
                          "in the launch-latency regime: read ms_per_step")
     ap.add_argument("--variant", default="plain", choices=["plain", "reject", "peaked"])
-    ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree", "decide"],
+    ap.add_argument("--mode", default="sample", choices=["sample", "greedy", "tree", "tree_seq", "decide"],
                     help="sample: lantern_verify (the headline); greedy: lantern_verify_greedy, target rows only; "
                          "decide: lantern_decide_rows, the decisions without resampled tokens (rejections settle in "
                          "the fp32 pass too); tree: rows_per_step/60 random draft trees of 60 candidates, siblings sharing logit rows "
-                         "(lantern_verify_trees: decisions, walk, one residual draw per tree)")
+                         "(lantern_verify_trees: decisions, walk, one residual draw per tree); tree_seq: the same trees "
+                         "under the sequential-residual sibling rule (lantern_verify_trees_sequential)")
     ap.add_argument("--divergence", default="tvd", choices=["tvd", "jsd"],
                     help="bound on the neighbourhood: total variation (the headline) or Jensen-Shannon")
     ap.add_argument("--tree-order", default="level", choices=["level", "random"],
@@ -262,7 +281,7 @@ def main() -> int:
     nbuf = max(1, args.buffers)
     run = Runner(lantern, lib, cfg, knn, args.variant, args.mode, args.divergence, args.tree_order, nbuf, dev, stream)
     torch.cuda.synchronize()
-    greedy, tree = args.mode == "greedy", args.mode == "tree"
+    greedy, tree = args.mode == "greedy", args.mode in ("tree", "tree_seq")
 
     for i in range(args.warmup):
         run.step(i)
@@ -339,9 +358,11 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "greedy_fast" if greedy else "verify_fast",
+            "kernel": "greedy_fast" if greedy else ("trees_sequential" if args.mode == "tree_seq" else "verify_fast"),
             **({"note": "per step: verify_fast over shared rows, the tree walk, one fp64 residual draw per tree"}
-               if tree else {}),
+               if args.mode == "tree" else {}),
+            **({"note": "one workgroup per tree walks it in fp64, sibling after sibling: latency bound, 64 of 256 "
+                        "compute units busy"} if args.mode == "tree_seq" else {}),
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -362,7 +383,8 @@ def main() -> int:
         # ---- the other mixes and entry points on the same configuration (the headline's mix accepts
         # nearly every row; the paper's acceptance rates are far lower, and rejections cost time) ----
         variants = {}
-        for variant, modes in (("reject", ("sample", "decide", "tree")), ("peaked", ("sample", "decide", "tree"))):
+        for variant, modes in (("reject", ("sample", "decide", "tree", "tree_seq")),
+                               ("peaked", ("sample", "decide", "tree", "tree_seq"))):
             variants[variant] = {}
             for mode in modes:
                 r = Runner(lantern, lib, cfg, knn, variant, mode, "tvd", args.tree_order, min(nbuf, 4), dev, stream)
@@ -371,13 +393,14 @@ def main() -> int:
                 b = r.algorithmic_bytes()
                 variants[variant][mode] = {
                     "entry_point": {"sample": "lantern_verify", "decide": "lantern_decide_rows",
-                                    "tree": "lantern_verify_trees"}[mode],
+                                    "tree": "lantern_verify_trees",
+                                    "tree_seq": "lantern_verify_trees_sequential"}[mode],
                     "delta": r.delta, "rows_per_step": r.rows, "steps": args.extra_steps,
                     "ms_per_step": w / args.extra_steps * 1e3, "kernel_ms_avg": kms,
                     "value": r.rows * args.extra_steps / w,
                     "accepted_fraction": r.accepted_fraction(args.extra_steps),
                     "frac": b / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                    **({"mean_accepted_length": float(r.t_len.float().mean().item())} if mode == "tree" else {}),
+                    **({"mean_accepted_length": float(r.t_len.float().mean().item())} if mode in ("tree", "tree_seq") else {}),
                 }
                 del r
                 torch.cuda.empty_cache()
@@ -386,7 +409,8 @@ def main() -> int:
                                    "(about 60 % of the rows rejected); peaked: logits x5 (about 45 % rejected, the bound "
                                    "cuts the neighbourhoods); sample resamples every rejected row in fp64, decide "
                                    "returns decisions only, tree walks 64 trees of 60 candidates and resamples one "
-                                   "token per tree; frac = algorithmic bytes / kernel time / 8 TB/s")
+                                   "token per tree, tree_seq walks the same trees under the sequential-residual "
+                                   "sibling rule (its accepted_fraction is accepted nodes / candidates); frac = algorithmic bytes / kernel time / 8 TB/s")
         wl = workloads.CONFIGS["wide_latent"]
         _, wl_ms = time_knn_build(lantern, workloads.make_codebook(wl, device=dev), wl.k)
         result["knn"][wl.name] = knn_report(wl, wl_ms)

@@ -22,6 +22,8 @@
  *                      decisions for all candidates, the residual draw only
  *                      where Algorithm 1 uses it
  *   lantern_verify_trees_greedy   the tree step under greedy decoding
+ *   lantern_verify_trees_sequential   the tree step with siblings verified one
+ *                      after the other against the residual of those before
  *
  * Naming.  The paper writes p for the drafter and q for the target model.
  * Other texts use the letters the other way round, so this header uses
@@ -419,6 +421,51 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
                                 int M, const int32_t* draft_tokens, const int32_t* knn, int k, float delta,
                                 int32_t* out_accept, int32_t* out_token, int32_t* out_len, int32_t* out_path,
                                 int32_t* out_next, void* hip_stream);
+
+/*
+ * The tree step under the sequential-residual sibling rule (Section 2 and
+ * Algorithm 1: a rejected draft is followed by the residual distribution;
+ * Section 4.3 for each candidate).  lantern_verify_trees tests every child of
+ * a node against the same target, which with more than one child per node
+ * does not keep the target law even at k = 1.  Here the children of a node are
+ * tried one after the other, in index order, on the logit rows of the first
+ * child: the first against t_1 = the target distribution of those rows; child
+ * j + 1, reached when child j was rejected, against t_{j+1} = the normalised
+ * residual max(0, t_{j,A} - g) / Z of child j's verification, with the
+ * neighbourhood, the mass and the acceptance test of Section 4.3 all taken on
+ * t_{j+1}.  The first accepted child is taken and the walk goes on from it.
+ * With k = 1 or delta = 0 and tokens drawn independently from g this is
+ * recursive rejection sampling, and the emitted token follows the target.
+ * Everything is evaluated in fp64; one launch, one workgroup per tree.
+ *
+ *   row_index, draft_tokens, uniforms, parent  [B*M] as in lantern_verify_trees
+ *              (row_index may be NULL when R == B*M); each candidate owns its
+ *              two draws, uniforms[2i] for the acceptance test and
+ *              uniforms[2i+1] for the residual draw
+ *   out_len    [B], out_path [B*M] as in lantern_accept_trees
+ *   out_next   [B] int32: when every child of the last node was rejected, the
+ *              token drawn from the residual of its last child; -1 when the
+ *              last node has no child; -2 when a child that had to be tried is
+ *              unusable (row index, token or a table entry out of range, logit
+ *              rows with a NaN, a +inf or no finite entry, or a row index other
+ *              than the first child's); -3, with len 0, for a malformed parent
+ *              array
+ *   workspace  device memory, 256-byte aligned, of at least
+ *              lantern_verify_trees_sequential_workspace_bytes(B, V) bytes
+ *              (2 V doubles per tree; 0 for invalid arguments); owned by the
+ *              caller, contents unspecified afterwards, must not be shared by
+ *              calls that may overlap
+ * Errors: E_DTYPE, E_SHAPE (as lantern_verify_trees, and an unknown
+ * divergence), E_DELTA, E_NULL, E_WORKSPACE, E_DEVICE.  B = 0 does nothing.
+ */
+size_t lantern_verify_trees_sequential_workspace_bytes(int B, int V);
+
+int lantern_verify_trees_sequential(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                                    int R, int V, int64_t row_stride_elems, const int32_t* row_index,
+                                    const int32_t* parent, int B, int M, const int32_t* draft_tokens,
+                                    const int32_t* knn, int k, int divergence, float delta, const float* uniforms,
+                                    int32_t* out_len, int32_t* out_path, int32_t* out_next, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream);
 
 /*
  * Measurement aid, not part of the method: reads the first bytes / 65536 whole

@@ -25,7 +25,8 @@ EXPORTS = (
     "lantern_verify", "lantern_verify_ex", "lantern_verify_divergence", "lantern_verify_greedy",
     "lantern_accept_chains", "lantern_verify_rows", "lantern_verify_greedy_rows", "lantern_accept_trees",
     "lantern_build_random", "lantern_decide_rows", "lantern_resample_selected", "lantern_verify_trees",
-    "lantern_verify_trees_greedy", "lantern_probe_stream_read", "lantern_prepare", "lantern_build_knn_static",
+    "lantern_verify_trees_greedy", "lantern_verify_trees_sequential_workspace_bytes",
+    "lantern_verify_trees_sequential", "lantern_probe_stream_read", "lantern_prepare", "lantern_build_knn_static",
     "lantern_status_string",
     "lantern_version",
 )
@@ -85,6 +86,11 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_trees_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp, vp,
                                                 vp, vp, vp]
     lib.lantern_verify_trees_greedy.restype = i32
+    lib.lantern_verify_trees_sequential_workspace_bytes.argtypes = [i32, i32]
+    lib.lantern_verify_trees_sequential_workspace_bytes.restype = sz
+    lib.lantern_verify_trees_sequential.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, i32, f32,
+                                                    vp, vp, vp, vp, vp, sz, vp]
+    lib.lantern_verify_trees_sequential.restype = i32
     lib.lantern_probe_stream_read.argtypes = [vp, vp, sz, vp, vp]
     lib.lantern_probe_stream_read.restype = i32
     lib.lantern_build_random.argtypes = [i32, i32, ctypes.c_uint64, vp, vp]
@@ -491,6 +497,42 @@ def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_t
     if rc != OK:
         raise LanternError(rc, "lantern_verify_trees")
     return acc, n, path, nxt
+
+
+def verify_trees_sequential(target_logits, draft_logits, row_index, parent, M: int, draft_tokens, knn, delta: float,
+                            uniforms, divergence: str = "tvd", workspace=None, stream=None):
+    """lantern_verify_trees_sequential; returns (len int32[B], path int32[B, M], next int32[B]).
+    workspace: a uint8 device tensor of at least trees_sequential_workspace_bytes(B, V) bytes, or None
+    to allocate one."""
+    lib = load()
+    R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
+    _need_cuda(parent)
+    if parent.dtype != torch.int32 or not parent.is_contiguous() or parent.numel() != N or M < 1 or N % M:
+        raise ValueError("parent must be a contiguous int32 tensor of B*M entries")
+    B = N // M
+    dev = target_logits.device
+    need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, V))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _need_cuda(workspace)
+    n = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, M), dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib.lantern_verify_trees_sequential(target_logits.data_ptr(), draft_logits.data_ptr(),
+                                             _dtype_code(target_logits), R, V, stride,
+                                             None if row_index is None else row_index.data_ptr(),
+                                             parent.data_ptr(), B, int(M), draft_tokens.data_ptr(), knn.data_ptr(),
+                                             int(knn.shape[1]), {"tvd": DIV_TVD, "jsd": DIV_JSD}[divergence],
+                                             float(delta), uniforms.data_ptr(), n.data_ptr(), path.data_ptr(),
+                                             nxt.data_ptr(), workspace.data_ptr(),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != OK:
+        raise LanternError(rc, "lantern_verify_trees_sequential")
+    return n, path, nxt
+
+
+def trees_sequential_workspace_bytes(B: int, V: int) -> int:
+    return int(load().lantern_verify_trees_sequential_workspace_bytes(int(B), int(V)))
 
 
 def verify_trees_greedy(target_logits, row_index, parent, M: int, draft_tokens, knn, delta: float, stream=None):

@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblantern.so")
-SOURCES = ("api.hip", "verify.hip", "greedy.hip", "chain.hip", "knn.hip", "random_table.hip", "probe.hip")
+SOURCES = ("api.hip", "verify.hip", "greedy.hip", "chain.hip", "sequential.hip", "knn.hip", "random_table.hip", "probe.hip")
 
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -6,6 +6,7 @@
 
 #include "knn_args.h"
 #include "lantern.h"
+#include "sequential_args.h"
 #include "verify_args.h"
 
 namespace {
@@ -320,12 +321,62 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
     return lantern_accept_trees(out_accept, out_token, parent, B, M, out_len, out_path, out_next, hip_stream);
 }
 
+size_t lantern_verify_trees_sequential_workspace_bytes(int B, int V) {
+    if (B < 0 || V < 1 || V > LANTERN_MAX_VOCAB) return 0;
+    return (size_t)B * 2 * (size_t)V * sizeof(double);
+}
+
+int lantern_verify_trees_sequential(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
+                                    int R, int V, int64_t row_stride_elems, const int32_t* row_index,
+                                    const int32_t* parent, int B, int M, const int32_t* draft_tokens,
+                                    const int32_t* knn, int k, int divergence, float delta, const float* uniforms,
+                                    int32_t* out_len, int32_t* out_path, int32_t* out_next, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+    if (!dtype_ok((int)logits_dtype)) return LANTERN_E_DTYPE;
+    if (B < 0 || M < 1 || (int64_t)B * M > INT_MAX) return LANTERN_E_SHAPE;
+    if (R < 0 || V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V || row_stride_elems < V) return LANTERN_E_SHAPE;
+    if (divergence != LANTERN_DIV_TVD && divergence != LANTERN_DIV_JSD) return LANTERN_E_SHAPE;
+    if (B > 0 && R < 1) return LANTERN_E_SHAPE;
+    if (!(delta >= 0.0f)) return LANTERN_E_DELTA;
+    if (B == 0) return LANTERN_OK;
+    if (!row_index && R != B * M) return LANTERN_E_SHAPE;   // without an index array candidate i reads row i
+    if (!target_logits || !draft_logits || !parent || !draft_tokens || !knn || !uniforms || !out_len || !out_path ||
+        !out_next)
+        return LANTERN_E_NULL;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < lantern_verify_trees_sequential_workspace_bytes(B, V))
+        return LANTERN_E_WORKSPACE;
+    lantern::SequentialArgs a;
+    a.target = target_logits;
+    a.draft = draft_logits;
+    a.R = R;
+    a.V = V;
+    a.stride = row_stride_elems;
+    a.row_index = row_index;
+    a.parent = parent;
+    a.B = B;
+    a.M = M;
+    a.tokens = draft_tokens;
+    a.knn = knn;
+    a.k = k;
+    a.divergence = divergence;
+    a.delta = delta;
+    a.uniforms = uniforms;
+    a.out_len = out_len;
+    a.out_path = out_path;
+    a.out_next = out_next;
+    a.work = static_cast<double*>(workspace);
+    const hipError_t e = lantern::launch_trees_sequential(a, (int)logits_dtype, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
+}
+
 int lantern_prepare(lantern_dtype logits_dtype, int V, int k) {
     if (!dtype_ok((int)logits_dtype)) return LANTERN_E_DTYPE;
     if (V < 1 || V > LANTERN_MAX_VOCAB || k < 1 || k > V) return LANTERN_E_SHAPE;
     hipError_t e = lantern::prepare_verify((int)logits_dtype, V, k);
     if (e == hipSuccess) e = lantern::prepare_greedy((int)logits_dtype, V, k);
     if (e == hipSuccess) e = lantern::prepare_walks();
+    if (e == hipSuccess) e = lantern::prepare_sequential();
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 
@@ -342,6 +393,6 @@ const char* lantern_status_string(int status) {
     }
 }
 
-int lantern_version(void) { return 200; }
+int lantern_version(void) { return 210; }
 
 }  // extern "C"

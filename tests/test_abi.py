@@ -180,3 +180,32 @@ def test_static_build_and_prepare_argument_errors(lib):
     assert lib.lantern_prepare(L.F32, 0, 1) == L.binding.E_SHAPE
     assert lib.lantern_prepare(L.F32, 16, 17) == L.binding.E_SHAPE
     assert lib.lantern_prepare(L.BF16, L.MAX_VOCAB + 1, 4) == L.binding.E_SHAPE
+
+
+def test_sequential_tree_argument_errors(lib):
+    """Host-side validation of lantern_verify_trees_sequential and of its workspace size."""
+    import paper_2410_03355_amd as L
+    B_ = L.binding
+    p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    nul = ctypes.c_void_p(0)
+    size = lib.lantern_verify_trees_sequential_workspace_bytes
+    assert size(3, 16) == 3 * 2 * 16 * 8
+    assert size(0, 16) == 0 and size(-1, 16) == 0 and size(3, 0) == 0 and size(3, L.MAX_VOCAB + 1) == 0
+
+    def call(tl=p, dl=p, dt=L.F32, R=5, V=16, stride=16, ri=p, par=p, B=2, M=3, tok=p, knn=p, k=4, div=0, delta=0.1,
+             un=p, ol=p, op=p, on=p, ws=p, ws_bytes=1 << 20):
+        return lib.lantern_verify_trees_sequential(tl, dl, dt, R, V, stride, ri, par, B, M, tok, knn, k, div, delta,
+                                                   un, ol, op, on, ws, ws_bytes, nul)
+
+    assert call(dt=9) == B_.E_DTYPE
+    for kw in (dict(B=-1), dict(M=0), dict(B=1 << 20, M=1 << 20), dict(R=-1), dict(R=0), dict(V=0), dict(k=0),
+               dict(k=17), dict(stride=15), dict(div=2), dict(ri=nul, R=5), dict(V=L.MAX_VOCAB + 1,
+                                                                                stride=L.MAX_VOCAB + 1)):
+        assert call(**kw) == B_.E_SHAPE, kw
+    assert call(delta=-0.1) == B_.E_DELTA and call(delta=float("nan")) == B_.E_DELTA
+    for name in ("tl", "dl", "par", "tok", "knn", "un", "ol", "op", "on"):
+        assert call(**{name: nul}) == B_.E_NULL, name
+    assert call(ws=nul) == B_.E_WORKSPACE
+    assert call(ws=ctypes.c_void_p(4096 + 64)) == B_.E_WORKSPACE
+    assert call(ws_bytes=2 * 2 * 16 * 8 - 1) == B_.E_WORKSPACE
+    assert call(B=0, tl=nul, dl=nul, ws=nul, ws_bytes=0) == B_.OK   # nothing to do
