@@ -87,7 +87,7 @@ class Runner:
             self.keep = (tb, parent)
 
             if mode == "tree_seq":
-                need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, cfg.V))
+                need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, M, cfg.V))
                 work = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
                 self.keep = (tb, parent, work)
 

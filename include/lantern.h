@@ -436,7 +436,9 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
  * t_{j+1}.  The first accepted child is taken and the walk goes on from it.
  * With k = 1 or delta = 0 and tokens drawn independently from g this is
  * recursive rejection sampling, and the emitted token follows the target.
- * Everything is evaluated in fp64; one launch, one workgroup per tree.
+ * Two launches: the plain verification of all B*M candidates (it decides the
+ * first child of every group, whose test is against t_1 itself), then one
+ * workgroup per tree that walks it and evaluates the residual targets in fp64.
  *
  *   row_index, draft_tokens, uniforms, parent  [B*M] as in lantern_verify_trees
  *              (row_index may be NULL when R == B*M); each candidate owns its
@@ -451,14 +453,15 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
  *              than the first child's); -3, with len 0, for a malformed parent
  *              array
  *   workspace  device memory, 256-byte aligned, of at least
- *              lantern_verify_trees_sequential_workspace_bytes(B, V) bytes
- *              (2 V doubles per tree; 0 for invalid arguments); owned by the
+ *              lantern_verify_trees_sequential_workspace_bytes(B, M, V) bytes
+ *              (2 V doubles per tree and 4 bytes per candidate; 0 for invalid
+ *              arguments and for B = 0); owned by the
  *              caller, contents unspecified afterwards, must not be shared by
  *              calls that may overlap
  * Errors: E_DTYPE, E_SHAPE (as lantern_verify_trees, and an unknown
  * divergence), E_DELTA, E_NULL, E_WORKSPACE, E_DEVICE.  B = 0 does nothing.
  */
-size_t lantern_verify_trees_sequential_workspace_bytes(int B, int V);
+size_t lantern_verify_trees_sequential_workspace_bytes(int B, int M, int V);
 
 int lantern_verify_trees_sequential(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
                                     int R, int V, int64_t row_stride_elems, const int32_t* row_index,

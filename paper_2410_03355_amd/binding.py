@@ -86,7 +86,7 @@ def load() -> ctypes.CDLL:
     lib.lantern_verify_trees_greedy.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp, vp,
                                                 vp, vp, vp]
     lib.lantern_verify_trees_greedy.restype = i32
-    lib.lantern_verify_trees_sequential_workspace_bytes.argtypes = [i32, i32]
+    lib.lantern_verify_trees_sequential_workspace_bytes.argtypes = [i32, i32, i32]
     lib.lantern_verify_trees_sequential_workspace_bytes.restype = sz
     lib.lantern_verify_trees_sequential.argtypes = [vp, vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, i32, i32, f32,
                                                     vp, vp, vp, vp, vp, sz, vp]
@@ -502,7 +502,7 @@ def verify_trees(target_logits, draft_logits, row_index, parent, M: int, draft_t
 def verify_trees_sequential(target_logits, draft_logits, row_index, parent, M: int, draft_tokens, knn, delta: float,
                             uniforms, divergence: str = "tvd", workspace=None, stream=None):
     """lantern_verify_trees_sequential; returns (len int32[B], path int32[B, M], next int32[B]).
-    workspace: a uint8 device tensor of at least trees_sequential_workspace_bytes(B, V) bytes, or None
+    workspace: a uint8 device tensor of at least trees_sequential_workspace_bytes(B, M, V) bytes, or None
     to allocate one."""
     lib = load()
     R, V, N, stride = _rows_args(target_logits, draft_logits, row_index, draft_tokens, knn, uniforms)
@@ -511,7 +511,7 @@ def verify_trees_sequential(target_logits, draft_logits, row_index, parent, M: i
         raise ValueError("parent must be a contiguous int32 tensor of B*M entries")
     B = N // M
     dev = target_logits.device
-    need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, V))
+    need = int(lib.lantern_verify_trees_sequential_workspace_bytes(B, int(M), V))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     _need_cuda(workspace)
@@ -531,8 +531,8 @@ def verify_trees_sequential(target_logits, draft_logits, row_index, parent, M: i
     return n, path, nxt
 
 
-def trees_sequential_workspace_bytes(B: int, V: int) -> int:
-    return int(load().lantern_verify_trees_sequential_workspace_bytes(int(B), int(V)))
+def trees_sequential_workspace_bytes(B: int, M: int, V: int) -> int:
+    return int(load().lantern_verify_trees_sequential_workspace_bytes(int(B), int(M), int(V)))
 
 
 def verify_trees_greedy(target_logits, row_index, parent, M: int, draft_tokens, knn, delta: float, stream=None):

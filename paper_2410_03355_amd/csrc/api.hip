@@ -321,9 +321,12 @@ int lantern_verify_trees_greedy(const void* target_logits, lantern_dtype logits_
     return lantern_accept_trees(out_accept, out_token, parent, B, M, out_len, out_path, out_next, hip_stream);
 }
 
-size_t lantern_verify_trees_sequential_workspace_bytes(int B, int V) {
-    if (B < 0 || V < 1 || V > LANTERN_MAX_VOCAB) return 0;
-    return (size_t)B * 2 * (size_t)V * sizeof(double);
+size_t lantern_verify_trees_sequential_workspace_bytes(int B, int M, int V) {
+    if (B < 0 || M < 1 || V < 1 || V > LANTERN_MAX_VOCAB || (int64_t)B * M > INT_MAX) return 0;
+    // per tree the current target and the drafter's distribution (fp64); then one decision per candidate
+    const size_t vectors = (size_t)B * 2 * (size_t)V * sizeof(double);
+    const size_t decisions = (((size_t)B * M * sizeof(int32_t)) + 255) & ~size_t(255);
+    return B == 0 ? 0 : vectors + decisions;
 }
 
 int lantern_verify_trees_sequential(const void* target_logits, const void* draft_logits, lantern_dtype logits_dtype,
@@ -344,9 +347,17 @@ int lantern_verify_trees_sequential(const void* target_logits, const void* draft
         !out_next)
         return LANTERN_E_NULL;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-        workspace_bytes < lantern_verify_trees_sequential_workspace_bytes(B, V))
+        workspace_bytes < lantern_verify_trees_sequential_workspace_bytes(B, M, V))
         return LANTERN_E_WORKSPACE;
+    // the plain verification of every candidate decides the first child of every sibling group
+    int32_t* decisions = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) +
+                                                    (size_t)B * 2 * (size_t)V * sizeof(double));
+    const int rc = lantern_decide_rows(target_logits, draft_logits, logits_dtype, R, V, row_stride_elems, row_index,
+                                       B * M, draft_tokens, knn, k, divergence, delta, uniforms, decisions, nullptr,
+                                       hip_stream);
+    if (rc != LANTERN_OK) return rc;
     lantern::SequentialArgs a;
+    a.accept = decisions;
     a.target = target_logits;
     a.draft = draft_logits;
     a.R = R;

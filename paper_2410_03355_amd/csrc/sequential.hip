@@ -11,7 +11,10 @@
 //
 // The chain t_1, t_2, ... is sequential, so one workgroup of 1024 threads walks one tree and keeps
 // the current target and the drafter's distribution as fp64 probability vectors in a workspace
-// (2 V doubles per tree, cache resident).  Everything is evaluated in fp64.
+// (2 V doubles per tree, cache resident), evaluated in fp64.  The test of a group's first child is
+// the plain verification of that candidate, so its decision is read from the row-parallel pass
+// (lantern_decide_rows over all candidates, launched first): only groups whose first child is
+// rejected build the vectors.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <stdint.h>
@@ -33,30 +36,80 @@ __device__ __forceinline__ double lane63_d(double v) {
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
-// softmax of one logit row into prob[0, V) (fp64): exp(l - max) / sum.  Returns false, with prob
-// unspecified, for a row with a NaN, a +inf or no finite logit.  Ends with every thread past a
-// barrier that follows its last write.
+// Elements a thread keeps in flight per step of a pass: the loads of a step are all issued before
+// the first of them is used, so a pass pays the memory latency once per step, not once per element.
+constexpr int SU = 8;
+
+// softmax of the target row and of the drafter's row into pt[0, V) and pg[0, V) (fp64):
+// exp(l - max) / sum for each.  Returns false, with the outputs unspecified, if either row has a
+// NaN, a +inf or no finite logit.  Ends with every thread past a barrier that follows its last
+// write.
 template <typename LT>
-__device__ bool softmax_to(const LT* row, int V, double* prob, ExactShared& sh, int tid) {
+__device__ bool softmax_pair(const LT* trow, const LT* grow, int V, double* pt, double* pg, ExactShared& sh, int tid) {
     using L = Lane<LT>;
-    double mx = -__builtin_huge_val();
+    const float inf = __builtin_huge_valf();
+    float mt = -inf, mg = -inf;
     int bad = 0;
-    for (int x = tid; x < V; x += SNT) {
-        const float l = L::glob(row, x);
-        if (l != l || l == __builtin_huge_valf()) bad = 1;
-        mx = fmax(mx, (double)l);
+    for (int xb = tid; xb < V; xb += SNT * SU) {
+        float lt[SU], lg[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int x = xb + u * SNT;
+            lt[u] = x < V ? L::glob(trow, x) : -inf;
+            lg[u] = x < V ? L::glob(grow, x) : -inf;
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            if (lt[u] != lt[u] || lt[u] == inf || lg[u] != lg[u] || lg[u] == inf) bad = 1;
+            mt = fmaxf(mt, lt[u]);
+            mg = fmaxf(mg, lg[u]);
+        }
     }
     bad = block_or_i<SNW>(bad, sh.ired, tid);
-    mx = block_max<SNW>(mx, sh.red, tid);
-    if (bad || mx == -__builtin_huge_val()) return false;   // uniform
-    double z = 0.0;
-    for (int x = tid; x < V; x += SNT) {
-        const double e = exp_nonpos((double)L::glob(row, x) - mx);
-        prob[x] = e;
-        z += e;
+    const double mxt = block_max<SNW>((double)mt, sh.red, tid);
+    const double mxg = block_max<SNW>((double)mg, sh.red2, tid);
+    if (bad || mxt == -__builtin_huge_val() || mxg == -__builtin_huge_val()) return false;   // uniform
+    double zt = 0.0, zg = 0.0;
+    for (int xb = tid; xb < V; xb += SNT * SU) {
+        float lt[SU], lg[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int x = xb + u * SNT;
+            lt[u] = x < V ? L::glob(trow, x) : -inf;
+            lg[u] = x < V ? L::glob(grow, x) : -inf;
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int x = xb + u * SNT;
+            const double et = exp_nonpos((double)lt[u] - mxt);
+            const double eg = exp_nonpos((double)lg[u] - mxg);
+            if (x < V) {
+                pt[x] = et;
+                pg[x] = eg;
+                zt += et;
+                zg += eg;
+            }
+        }
     }
-    z = block_sum<SNW>(z, sh.red2, tid);
-    for (int x = tid; x < V; x += SNT) prob[x] = prob[x] / z;   // the element this thread wrote
+    zt = block_sum<SNW>(zt, sh.red, tid);
+    zg = block_sum<SNW>(zg, sh.red2, tid);
+    for (int xb = tid; xb < V; xb += SNT * SU) {   // the elements this thread wrote
+        double et[SU], eg[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int x = xb + u * SNT;
+            et[u] = x < V ? pt[x] : 0.0;
+            eg[u] = x < V ? pg[x] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int x = xb + u * SNT;
+            if (x < V) {
+                pt[x] = et[u] / zt;
+                pg[x] = eg[u] / zg;
+            }
+        }
+    }
     __syncthreads();
     return true;
 }
@@ -120,12 +173,27 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
             const int64_t c = (int64_t)b * M + i;
             const int r = a.row_index ? a.row_index[c] : (int)c;
             const int xt = a.tokens[c];
-            if (!have_rows) {   // the first child brings the group's rows
+            if (!have_rows) {
+                // The first child is tested against t_1 = t itself, which is the plain verification the
+                // row-parallel pass has already decided for every candidate: an accepted first child is
+                // taken without building the group's vectors.
+                const int decided = a.accept[c];
+                if (decided == 1) {
+                    taken = i;
+                    break;
+                }
+                if (decided < 0) {   // unusable row, token or table entry
+                    next = -2;
+                    break;
+                }
+                // rejected: the first child brings the group's rows, and is verified again below in
+                // fp64 for its distorted target and residual
                 have_rows = true;
                 group_row = r;
                 bool ok = (r >= 0 && r < a.R);
-                if (ok) ok = softmax_to<LT>(reinterpret_cast<const LT*>(a.target) + (int64_t)r * a.stride, V, cur, sh, tid);
-                if (ok) ok = softmax_to<LT>(reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, V, g, sh, tid);
+                if (ok)
+                    ok = softmax_pair<LT>(reinterpret_cast<const LT*>(a.target) + (int64_t)r * a.stride,
+                                          reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, V, cur, g, sh, tid);
                 if (!ok) {
                     next = -2;
                     break;
@@ -191,11 +259,20 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
             if (tid == 0) cur[xt] = mass;
             __syncthreads();
             double pr = 0.0, pt = 0.0;
-            for (int x = x0 + lane; x < x1; x += WAVE) {
-                const double ta = cur[x];
-                const double d = ta - g[x];
-                pr += (d > 0.0) ? d : 0.0;
-                pt += ta;
+            for (int xb = x0 + lane; xb < x1; xb += WAVE * SU) {
+                double ta[SU], gv[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int x = xb + u * WAVE;
+                    ta[u] = x < x1 ? cur[x] : 0.0;
+                    gv[u] = x < x1 ? g[x] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const double d = ta[u] - gv[u];
+                    pr += (d > 0.0) ? d : 0.0;
+                    pt += ta[u];
+                }
             }
             pr = wave_sum(pr);
             pt = wave_sum(pt);
@@ -219,20 +296,26 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
             const double edge = u_res * zz;
             double run = zero_resid ? base_t : base_r;
             int found = INT_MAX;
-            for (int xb = x0; xb < x1; xb += WAVE) {   // uniform per wavefront
-                const int x = xb + lane;
-                const bool valid = x < x1;
-                double rx = 0.0;
-                if (valid) {
-                    const double ta = cur[x];
-                    const double d = zero_resid ? ta : ta - g[x];
-                    rx = (d > 0.0) ? d : 0.0;
+            for (int xb = x0; xb < x1; xb += WAVE * SU) {   // uniform per wavefront
+                double rx[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int x = xb + u * WAVE + lane;
+                    const double ta = x < x1 ? cur[x] : 0.0;
+                    const double gv = (x < x1 && !zero_resid) ? g[x] : 0.0;
+                    const double d = ta - gv;
+                    rx[u] = (d > 0.0) ? d : 0.0;
                 }
-                const double incl = run + wave_scan_incl(rx);
-                const unsigned long long m = __ballot(valid && incl > edge);
-                if (found == INT_MAX && m) found = xb + __ffsll((long long)m) - 1;
-                run = lane63_d(incl);
-                if (valid) cur[x] = rx / zz;
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int x = xb + u * WAVE + lane;
+                    const bool valid = x < x1;
+                    const double incl = run + wave_scan_incl(rx[u]);
+                    const unsigned long long m = __ballot(valid && incl > edge);
+                    if (found == INT_MAX && m) found = xb + u * WAVE + __ffsll((long long)m) - 1;
+                    run = lane63_d(incl);
+                    if (valid) cur[x] = rx[u] / zz;
+                }
             }
             next = block_min_i<SNW>(found, sh.ired, tid);
             if (next == INT_MAX) next = -1;

@@ -22,6 +22,7 @@ struct SequentialArgs {
     int divergence;            // bound on A: 0 total variation distance, 1 Jensen-Shannon divergence
     float delta;
     const float* uniforms;     // [B*M, 2]
+    const int32_t* accept;     // [B*M] decisions of the plain verification of every candidate (1, 0, -1)
     int32_t* out_len;          // [B]
     int32_t* out_path;         // [B*M]
     int32_t* out_next;         // [B]

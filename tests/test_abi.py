@@ -189,8 +189,10 @@ def test_sequential_tree_argument_errors(lib):
     p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
     nul = ctypes.c_void_p(0)
     size = lib.lantern_verify_trees_sequential_workspace_bytes
-    assert size(3, 16) == 3 * 2 * 16 * 8
-    assert size(0, 16) == 0 and size(-1, 16) == 0 and size(3, 0) == 0 and size(3, L.MAX_VOCAB + 1) == 0
+    assert size(3, 5, 16) == 3 * 2 * 16 * 8 + 256
+    assert size(3, 100, 16) == 3 * 2 * 16 * 8 + 1280
+    assert size(0, 5, 16) == 0 and size(-1, 5, 16) == 0 and size(3, 0, 16) == 0 and size(3, 5, 0) == 0
+    assert size(3, 5, L.MAX_VOCAB + 1) == 0 and size(1 << 20, 1 << 20, 16) == 0
 
     def call(tl=p, dl=p, dt=L.F32, R=5, V=16, stride=16, ri=p, par=p, B=2, M=3, tok=p, knn=p, k=4, div=0, delta=0.1,
              un=p, ol=p, op=p, on=p, ws=p, ws_bytes=1 << 20):
@@ -207,5 +209,5 @@ def test_sequential_tree_argument_errors(lib):
         assert call(**{name: nul}) == B_.E_NULL, name
     assert call(ws=nul) == B_.E_WORKSPACE
     assert call(ws=ctypes.c_void_p(4096 + 64)) == B_.E_WORKSPACE
-    assert call(ws_bytes=2 * 2 * 16 * 8 - 1) == B_.E_WORKSPACE
+    assert call(ws_bytes=2 * 2 * 16 * 8 + 255) == B_.E_WORKSPACE
     assert call(B=0, tl=nul, dl=nul, ws=nul, ws_bytes=0) == B_.OK   # nothing to do
