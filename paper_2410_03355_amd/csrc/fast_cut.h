@@ -2,11 +2,12 @@
 // (Algorithm 2, inference part, as a prefix scan over the k table slots).
 //
 // Every thread of the workgroup exponentiates its 4 consecutive slots of the
-// first 1024 (gathering the raw target logits from LDS), the wavefront scans
-// the partial sums and publishes them; after a barrier wavefront 0 adds the
-// wavefront offsets, compares every inclusive sum with delta * Z under the
-// rounding margin and finds the first slot that does not pass.  Slots beyond
-// 1024 are walked by wavefront 0 alone, 1024 at a time.
+// first 1024 (gathering the raw target logits from LDS) and the wavefront scans
+// the partial sums; after a barrier every wavefront adds the totals of the
+// wavefronts before it, compares the inclusive sums of its own slots with
+// delta * Z under the rounding margin and publishes the first slot that does
+// not pass; after a second barrier every thread combines the four results.
+// Slots beyond 1024 are walked by wavefront 0 alone, 1024 at a time.
 #pragma once
 
 #include "verify_common.h"
@@ -15,53 +16,6 @@ namespace lantern {
 
 constexpr int SPL = 16;              // table slots per lane when one wavefront walks 1024 slots
 constexpr int FAST_MAX_K = 8192;     // keeps the scan's summation depth inside the margin
-
-// LDS arrays of the scan: gs[NT*4] inclusive sums within the wavefront, gskip[NT] bit q set
-// when slot 4*tid+q is the token itself or beyond k, wtot[NW] wavefront totals, wbad[NW].
-struct ScanLds {
-    float* gs;
-    unsigned* gskip;
-    float* wtot;
-    int* wbad;
-};
-
-// All threads, before the barrier.  nb: table slots 4*tid .. 4*tid+3 (0 beyond k); nrow: the
-// token's table row.  Every one of the k entries is range-checked here, also those beyond the
-// first 1024 slots that the walk may never reach: a row with an entry outside [0, V) is unusable
-// wherever its cut falls.
-template <typename LT>
-__device__ __forceinline__ void scan_publish(const int (&nb)[4], int xt, int k, int V, const int32_t* nrow,
-                                             const unsigned char* s_row, float ct, const ScanLds& lds) {
-    using L = Lane<LT>;
-    const int tid = threadIdx.x;
-    const int lane = tid & (WAVE - 1);
-    const int wave = tid >> 6;
-    float run = 0.f;
-    float p[4];
-    unsigned skip = 0;
-    int bad = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const bool valid = tid * 4 + q < k;
-        const int n = nb[q];
-        const bool inr = (unsigned)n < (unsigned)V;
-        if (valid && !inr) bad = 1;
-        float e = 0.f;
-        if (n == xt || !valid) skip |= 1u << q;
-        else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
-        run += e;
-        p[q] = run;
-    }
-    for (int j = NT * 4 + tid; j < k; j += NT)
-        if ((unsigned)nrow[j] >= (unsigned)V) bad = 1;
-    const float incl = wave_scan_incl(run);
-    const float excl = wave_prev(incl, 0.f);
-    reinterpret_cast<float4*>(lds.gs)[tid] = make_float4(excl + p[0], excl + p[1], excl + p[2], excl + p[3]);
-    lds.gskip[tid] = skip;
-    bad = wave_or(bad);
-    if (lane == WAVE - 1) lds.wtot[wave] = incl;
-    if (lane == 0) lds.wbad[wave] = bad;
-}
 
 struct CutResult {
     int a_size;      // slots taken into A
@@ -200,7 +154,7 @@ __device__ __forceinline__ void classify_slots(const SlotTerms& st, const SlotTe
 }
 
 // Slots beyond the first 1024, walked by one wavefront 1024 at a time (k > 1024 and no cut among
-// the first 1024).  carry: the sum over the first 1024 slots.  Returns like scan_cut.
+// the first 1024).  carry: the sum over the first 1024 slots.  The result has the meaning of the combined per-wavefront results.
 template <typename LT>
 __device__ __forceinline__ CutResult walk_tail(const SlotTest& test, float carry, int xt, int xs, int k, int V,
                                                const int32_t* knn, const unsigned char* s_row, float ct) {
@@ -257,113 +211,6 @@ __device__ __forceinline__ CutResult walk_tail(const SlotTest& test, float carry
     r.a_size = (first_np == INT_MAX) ? k : first_np;
     r.S = (first_np == INT_MAX) ? carry : s_cut;
     r.bad = wave_or(bad);
-    return r;
-}
-
-// Wavefront 0, after the barrier.  Zt: sum of the unnormalised target terms; e_tx: the
-// unnormalised term of the token itself (used by the Jensen-Shannon bound only).
-template <typename LT>
-__device__ __forceinline__ CutResult scan_cut(float Zt, int divergence, float delta, float e_tx, int xt, int xs,
-                                              int k, int V, const int32_t* knn, const unsigned char* s_row,
-                                              float ct, const ScanLds& lds) {
-    using L = Lane<LT>;
-    const int lane = threadIdx.x & (WAVE - 1);
-    int bad = 0;
-    float woff[NW];
-    float run_off = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        bad |= lds.wbad[w];
-        woff[w] = run_off;
-        run_off += lds.wtot[w];
-    }
-    const float R = delta * Zt;                 // cut: divergence of the prefix, times Zt, < delta * Zt
-    SlotTest test;
-    test.divergence = divergence;
-    test.e_tx = e_tx;
-    test.lo = R * (1.f - TAU_CUT) - ABS_SLACK;
-    test.hi = R * (1.f + TAU_CUT) + ABS_SLACK;
-    // lane l takes slots 16 l .. 16 l + 15: threads 4 l .. 4 l + 3, all in wavefront l / 16
-    const float off = woff[lane >> 4];
-    int my_np = INT_MAX, my_df = INT_MAX;  // first slot not definitely passing / definitely failing
-    float my_s = 0.f;
-    float before = off + ((lane & 15) ? lds.gs[lane * SPL - 1] : 0.f);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const float4 v = reinterpret_cast<const float4*>(lds.gs)[lane * 4 + t];
-        const unsigned skip = lds.gskip[lane * 4 + t];
-        const float I[4] = {off + v.x, off + v.y, off + v.z, off + v.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (!((skip >> q) & 1u)) {
-                bool passes, fails;
-                test.classify(I[q], &passes, &fails);
-                if (my_np == INT_MAX && !passes) { my_np = lane * SPL + t * 4 + q; my_s = before; }
-                if (my_df == INT_MAX && fails) my_df = lane * SPL + t * 4 + q;
-            }
-            before = I[q];
-        }
-    }
-    int first_np = wave_min(my_np);
-    int first_df = wave_min(my_df);
-    float s_cut = 0.f;
-    float carry = run_off;
-    if (first_np != INT_MAX) {
-        const unsigned long long owner = __ballot(my_np == first_np);
-        s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s), __ffsll((long long)owner) - 1));
-    } else if (k > NT * 4) {
-        // slots beyond the first 1024: this wavefront walks them 1024 at a time
-        const int32_t* nrow = knn + (int64_t)xs * k;
-        for (int base = NT * 4; base < k; base += WAVE * SPL) {
-            const int j0 = base + lane * SPL;
-            float ev[SPL];
-            float run = 0.f;
-            unsigned skip = 0;
-#pragma unroll
-            for (int q = 0; q < SPL; ++q) {
-                const bool valid = j0 + q < k;
-                const int n = valid ? nrow[j0 + q] : 0;
-                const bool inr = (unsigned)n < (unsigned)V;
-                if (valid && !inr) bad = 1;
-                float e = 0.f;
-                if (n == xt || !valid) skip |= 1u << q;
-                else if (inr) e = hw_exp2(__builtin_fmaf(L::lds(s_row, n), LOG2E_F, -ct));
-                ev[q] = e;
-                run += e;
-            }
-            const float incl = wave_scan_incl(run);
-            const float ctot = lane63_f(incl);
-            float I = carry + wave_prev(incl, 0.f);
-            my_np = INT_MAX; my_df = INT_MAX; my_s = 0.f;
-#pragma unroll
-            for (int q = 0; q < SPL; ++q) {
-                const float bef = I;
-                I += ev[q];
-                if (!((skip >> q) & 1u)) {
-                    bool passes, fails;
-                    test.classify(I, &passes, &fails);
-                    if (my_np == INT_MAX && !passes) { my_np = j0 + q; my_s = bef; }
-                    if (my_df == INT_MAX && fails) my_df = j0 + q;
-                }
-            }
-            const int w_np = wave_min(my_np);
-            if (w_np != INT_MAX) {
-                const unsigned long long owner = __ballot(my_np == w_np);
-                first_np = w_np;
-                first_df = wave_min(my_df);
-                s_cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_s),
-                                                                 __ffsll((long long)owner) - 1));
-                break;
-            }
-            carry += ctot;
-        }
-        bad = wave_or(bad);
-    }
-    CutResult r;
-    r.definite = (first_np == INT_MAX) || (first_np == first_df);
-    r.a_size = (first_np == INT_MAX) ? k : first_np;
-    r.S = (first_np == INT_MAX) ? carry : s_cut;
-    r.bad = bad;
     return r;
 }
 

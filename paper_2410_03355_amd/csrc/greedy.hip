@@ -24,13 +24,10 @@ struct GreedyShared {
     int wbad[NW];
     float best_val[NW];   // arg-max outside A: per-wave value and lowest index
     int best_idx[NW];
-    int a_size;           // published cut
-    int cut_ok;           // cut definite, inputs usable
-    int early_accept;     // the mass of A beats the largest term of the whole row
-    int pad0;
-    float mass_z;         // (mass of A) * Z
-    float z;              // Z
-    int pad1[2];
+    int cut_np[NW];       // per wavefront: first slot not definitely passing, first slot definitely
+    int cut_df[NW];       // failing, and the sum before the former
+    float cut_s[NW];
+    int tail[4];          // the walk beyond slot 1024 (k > 1024): slots taken, sum, definite, bad
     // from here on the memory is reused by the exact path once the fp32 path gives up
     float gs[NT * 4];
     unsigned gskip[NT];
@@ -260,43 +257,76 @@ __global__ __launch_bounds__(NT) void greedy_fast(GreedyArgs a) {
     }
     st = wave_sum(st);
     emax = wave_max(emax);
-    const ScanLds scan{sh.gs, sh.gskip, sh.wtot, sh.wbad};
-    scan_publish<LT>(nb, xt, k, V, nrow, s_row, ct, scan);
+    const SlotTerms slots = slot_terms<LT>(nb, xt, k, V, nrow, s_row, ct, sh.wtot, sh.wbad);
     if (lane == 0) { sh.wsum[wave] = st; sh.wemax[wave] = emax; }
     __syncthreads();
 
-    // ---- wavefront 0: the cut ----
-    if (wave == 0) {
-        float Zt = 0.f, Emax = 0.f;
+    // ---- every wavefront: the bound on its own slots ----
+    float Zt = 0.f, Emax = 0.f, woff = 0.f, run_off = 0.f;
+    int bad = (tok_ok && row_ok) ? 0 : 1;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) { Zt += sh.wsum[w]; Emax = fmaxf(Emax, sh.wemax[w]); }
-        const CutResult cut = scan_cut<LT>(Zt, 0, a.delta, 0.f, xt, xs, k, V, a.knn, s_row, ct, scan);
-        const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX);
-        const bool cut_ok = cut.definite && !cut.bad && tok_ok && row_ok && sums_ok;
-        const float mass_z = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct)) + cut.S;
-        // no term of the row, inside or outside A, reaches the mass of A: accepted without looking at A
-        const bool early = cut_ok && (mass_z * (1.f - TAU_ACC) > Emax * (1.f + TAU_ACC) + ABS_SLACK);
-        if (lane == 0) {
-            sh.a_size = cut.a_size;
-            sh.cut_ok = cut_ok ? 1 : 0;
-            sh.early_accept = early ? 1 : 0;
-            sh.mass_z = mass_z;
-            sh.z = Zt;
-            if (early) {
-                a.out_accept[row] = 1;
-                a.out_token[row] = -1;
-                if (a.out_path) a.out_path[row] = 0;
+    for (int w = 0; w < NW; ++w) {
+        Zt += sh.wsum[w];
+        Emax = fmaxf(Emax, sh.wemax[w]);
+        if (w < wave) woff += sh.wtot[w];
+        run_off += sh.wtot[w];
+        bad |= sh.wbad[w];
+    }
+    const float e_tx = hw_exp2(__builtin_fmaf(L::lds(s_row, xs), LOG2E_F, -ct));
+    SlotTest test;
+    {
+        const float R = a.delta * Zt;   // total variation of the prefix, times Zt, < delta * Zt
+        test.divergence = 0;
+        test.e_tx = e_tx;
+        test.lo = R * (1.f - TAU_CUT) - ABS_SLACK;
+        test.hi = R * (1.f + TAU_CUT) + ABS_SLACK;
+    }
+    classify_slots(slots, test, woff, WaveCut{sh.cut_np, sh.cut_df, sh.cut_s});
+    __syncthreads();
+
+    // ---- every thread: the cut and the mass (same inputs, same result) ----
+    int first_np = INT_MAX, first_df = INT_MAX;
+    float s_cut = 0.f;
+#pragma unroll
+    for (int w = NW - 1; w >= 0; --w) {
+        if (sh.cut_np[w] != INT_MAX) { first_np = sh.cut_np[w]; s_cut = sh.cut_s[w]; }
+        first_df = min(first_df, sh.cut_df[w]);
+    }
+    bool cut_definite = (first_np == INT_MAX) || (first_np == first_df);
+    int a_size = (first_np == INT_MAX) ? k : first_np;
+    float S = (first_np == INT_MAX) ? run_off : s_cut;
+    if (first_np == INT_MAX && k > NT * 4) {   // uniform: the walk goes on beyond slot 1024
+        if (wave == 0) {
+            const CutResult tail = walk_tail<LT>(test, run_off, xt, xs, k, V, a.knn, s_row, ct);
+            if (lane == 0) {
+                sh.tail[0] = tail.a_size;
+                sh.tail[1] = __float_as_int(tail.S);
+                sh.tail[2] = tail.definite ? 1 : 0;
+                sh.tail[3] = tail.bad;
             }
         }
+        __syncthreads();
+        a_size = sh.tail[0];
+        S = __int_as_float(sh.tail[1]);
+        cut_definite = sh.tail[2] != 0;
+        bad |= sh.tail[3];
     }
-    __syncthreads();
-    if (!sh.cut_ok) {  // uniform: the cut itself needs fp64 (or the row is unusable)
+    const bool sums_ok = (Zt >= 1.f) && (Zt <= Z_MAX);
+    const bool cut_ok = cut_definite && !bad && sums_ok;
+    const float mass_z = e_tx + S;
+    if (!cut_ok) {  // uniform: the cut itself needs fp64 (or the row is unusable)
         greedy_exact_row<LT, true>(a, row, ex_lds, s_row);
         return;
     }
-    if (sh.early_accept) return;
-    const int a_size = sh.a_size;
-    const float mass_z = sh.mass_z;
+    // no term of the row, inside or outside A, reaches the mass of A: accepted without looking at A
+    if (mass_z * (1.f - TAU_ACC) > Emax * (1.f + TAU_ACC) + ABS_SLACK) {
+        if (tid == 0) {
+            a.out_accept[row] = 1;
+            a.out_token[row] = -1;
+            if (a.out_path) a.out_path[row] = 0;
+        }
+        return;
+    }
 
     // ---- remove A and xt from the LDS row, then the arg-max of what is left ----
     for (int base = 0; base < a_size; base += NT * 4) {
