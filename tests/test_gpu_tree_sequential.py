@@ -182,3 +182,67 @@ def test_single_candidate_large_vocabulary_and_empty(oracle_mod, lantern_gpu):
                                                        torch.from_numpy(table).cuda(), 0.1,
                                                        torch.empty((0, 2), dtype=torch.float32, device="cuda"))
     assert n.numel() == 0 and path.numel() == 0 and nxt.numel() == 0
+
+
+def test_bench_step_size(oracle_mod, lantern_gpu):
+    """The step bench.py times in mode tree_seq: 64 trees of 60 candidates listed level by level on the
+    stress shape, the table built from the workload's own codebook, the reject and peaked mixes."""
+    cfg = workloads.CONFIGS["stress"]
+    cb = workloads.make_codebook(cfg, device="cuda:0")
+    knn = lantern_gpu.build_knn(cb, cfg.k)
+    table = knn.cpu().numpy()
+    B, M = 64, 60
+    parent = level_order(random_trees(np.random.default_rng(workloads.BASE_SEED), B, M))
+    for variant, delta in (("reject", 0.0), ("peaked", cfg.delta), ("plain", cfg.delta)):
+        st, row_index, tokens, un = tree_step(cfg, parent, step=0, variant=variant)
+        n, path, nxt = _both(oracle_mod, lantern_gpu, st, row_index, parent, M, tokens, un, table, delta, threads=16)
+        if variant == "plain":
+            assert n.mean() > 3
+
+
+def test_capture_and_replay(oracle_mod, lantern_gpu):
+    """The call only enqueues kernels on the caller's stream: captured into a HIP graph and replayed on
+    new inputs, every replay equals the oracle."""
+    cfg = workloads.CONFIGS["tiny"]
+    table = random_table(cfg.V, cfg.k, seed=12)
+    tb = torch.from_numpy(table).cuda()
+    B, M = 24, 9
+    parent = random_trees(np.random.default_rng(4), B, M, max_children=3)
+    par_d = torch.from_numpy(parent).cuda().reshape(-1)
+    steps = [tree_step(cfg, parent, step=s, variant=v) for s, v in ((1, "reject"), (2, "peaked"), (3, "plain"))]
+    R = B * (M + 1)
+    tl = torch.empty((R, cfg.V), dtype=steps[0][0].target_logits.dtype, device="cuda")
+    dl = torch.empty_like(tl)
+    ri = torch.empty(B * M, dtype=torch.int32, device="cuda")
+    tok = torch.empty(B * M, dtype=torch.int32, device="cuda")
+    un = torch.empty((B * M, 2), dtype=torch.float32, device="cuda")
+    work = torch.empty(lantern_gpu.trees_sequential_workspace_bytes(B, M, cfg.V), dtype=torch.uint8, device="cuda")
+
+    def load(step):
+        st, row_index, tokens, uniforms = step
+        tl.copy_(st.target_logits); dl.copy_(st.draft_logits)
+        ri.copy_(torch.from_numpy(row_index)); tok.copy_(torch.from_numpy(tokens)); un.copy_(uniforms)
+
+    delta = 0.05
+    load(steps[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm up outside the capture
+        lantern_gpu.verify_trees_sequential(tl, dl, ri, par_d, M, tok, tb, delta, un, workspace=work, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        n, path, nxt = lantern_gpu.verify_trees_sequential(tl, dl, ri, par_d, M, tok, tb, delta, un, workspace=work,
+                                                           stream=torch.cuda.current_stream())
+    for step in (steps[1], steps[2], steps[0], steps[1]):
+        load(step)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        st, row_index, tokens, uniforms = step
+        n_o, path_o, next_o = oracle_mod.verify_trees_sequential(st.target_logits, st.draft_logits, row_index, parent,
+                                                                 M, tokens, table, cfg.k, delta, uniforms, threads=8)
+        np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
