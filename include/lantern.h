@@ -69,6 +69,9 @@ typedef enum {
     LANTERN_E_SHAPE = -2,     /* V<1, d<1, N<0, k<1, k>V, row stride < V, V too large  */
     LANTERN_E_DTYPE = -3,     /* dtype is not one of lantern_dtype                     */
     LANTERN_E_DELTA = -4,     /* delta is NaN or negative                              */
+    LANTERN_E_TOKEN = -5,     /* a verification was unusable (see below); never returned
+                                 by the calls here, which are asynchronous: raised by the
+                                 Python binding's checked mode after it has synchronised */
     LANTERN_E_WORKSPACE = -6, /* workspace missing, misaligned or too small            */
     LANTERN_E_DEVICE = -7     /* a HIP call failed (launch error, no device)           */
 } lantern_status;

@@ -18,7 +18,7 @@ METRIC_L2, METRIC_COSINE = 0, 1
 MAX_VOCAB = 1 << 19
 
 OK = 0
-E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -6, -7
+E_NULL, E_SHAPE, E_DTYPE, E_DELTA, E_TOKEN, E_WORKSPACE, E_DEVICE = -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = (
     "lantern_build_knn_workspace_bytes", "lantern_build_knn", "lantern_build_knn_metric",
@@ -210,9 +210,21 @@ def _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms)
     return N, V, int(knn.shape[1])
 
 
+def _raise_if_unusable(acc, stream, where: str):
+    """Checked mode: waits for the call's stream and raises E_TOKEN if any verification came back unusable."""
+    (torch.cuda.current_stream(acc.device) if stream is None else stream).synchronize()
+    bad = torch.nonzero(acc < 0).flatten()
+    if bad.numel():
+        err = LanternError(E_TOKEN, where)
+        err.rows = bad.cpu().tolist()
+        raise err
+
+
 def verify(target_logits, draft_logits, draft_tokens, knn, delta: float, uniforms,
-           out_accept=None, out_resample=None, stream=None):
-    """lantern_verify; returns (accept int32[N], resample int32[N]) device tensors."""
+           out_accept=None, out_resample=None, stream=None, checked: bool = False):
+    """lantern_verify; returns (accept int32[N], resample int32[N]) device tensors.
+    checked: synchronise and raise LanternError(E_TOKEN) (with .rows) if a verification was unusable; by
+    default the call is asynchronous and such rows carry -1 in both outputs."""
     lib = load()
     N, V, k = _check_verify_args(target_logits, draft_logits, draft_tokens, knn, uniforms)
     dev = target_logits.device
@@ -224,6 +236,8 @@ def verify(target_logits, draft_logits, draft_tokens, knn, delta: float, uniform
                             uniforms.data_ptr(), acc.data_ptr(), res.data_ptr(), _stream_ptr(stream))
     if rc != OK:
         raise LanternError(rc, "lantern_verify")
+    if checked:
+        _raise_if_unusable(acc, stream, "lantern_verify")
     return acc, res
 
 

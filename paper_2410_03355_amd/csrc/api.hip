@@ -398,6 +398,7 @@ const char* lantern_status_string(int status) {
         case LANTERN_E_SHAPE: return "invalid shape argument";
         case LANTERN_E_DTYPE: return "unsupported dtype";
         case LANTERN_E_DELTA: return "delta is NaN or negative";
+        case LANTERN_E_TOKEN: return "unusable verification: token, table entry or row index out of range, or unusable logits";
         case LANTERN_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case LANTERN_E_DEVICE: return "HIP call failed";
         default: return "unknown status";

@@ -37,11 +37,11 @@ def test_status_strings_and_version(lib):
     import paper_2410_03355_amd as lantern
     assert lib.lantern_version() >= 100
     seen = set()
-    for code in (0, -1, -2, -3, -4, -6, -7):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         s = lantern.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert lantern.status_string(-99) == "unknown status"
 
 

@@ -364,3 +364,22 @@ def test_concurrent_host_threads(oracle_mod, lantern_gpu):
     for th in threads:
         th.join()
     assert not errors, errors
+
+
+def test_checked_mode_raises_on_unusable_rows(lantern_gpu):
+    """The binding's checked mode: the calls themselves are asynchronous and mark an unusable row with
+    -1; checked=True waits for the stream and raises E_TOKEN naming the rows."""
+    cfg = workloads.CONFIGS["tiny"]
+    st = workloads.make_step(cfg, step=3, rows=32)
+    table = torch.from_numpy(random_table(cfg.V, cfg.k, seed=2)).cuda()
+    tokens = st.draft_tokens.clone()
+    tokens[5] = cfg.V
+    tokens[17] = -3
+    args = (st.target_logits.cuda(), st.draft_logits.cuda())
+    acc, res = lantern_gpu.verify(*args, tokens.cuda(), table, cfg.delta, st.uniforms.cuda())
+    torch.cuda.synchronize()
+    assert acc[5].item() == -1 and acc[17].item() == -1 and res[5].item() == -1
+    with pytest.raises(lantern_gpu.LanternError) as info:
+        lantern_gpu.verify(*args, tokens.cuda(), table, cfg.delta, st.uniforms.cuda(), checked=True)
+    assert info.value.status == lantern_gpu.binding.E_TOKEN and info.value.rows == [5, 17]
+    lantern_gpu.verify(*args, st.draft_tokens.cuda(), table, cfg.delta, st.uniforms.cuda(), checked=True)
