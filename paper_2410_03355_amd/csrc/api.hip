@@ -387,7 +387,7 @@ int lantern_prepare(lantern_dtype logits_dtype, int V, int k) {
     hipError_t e = lantern::prepare_verify((int)logits_dtype, V, k);
     if (e == hipSuccess) e = lantern::prepare_greedy((int)logits_dtype, V, k);
     if (e == hipSuccess) e = lantern::prepare_walks();
-    if (e == hipSuccess) e = lantern::prepare_sequential();
+    if (e == hipSuccess) e = lantern::prepare_sequential((int)logits_dtype, V);
     return e == hipSuccess ? LANTERN_OK : LANTERN_E_DEVICE;
 }
 

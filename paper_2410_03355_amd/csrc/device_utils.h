@@ -86,48 +86,46 @@ __device__ __forceinline__ float wave_prev(float v, float identity) {
     return dpp_f<DPP_WAVE_SHR1, 0xF>(identity, v);
 }
 
-// fp64 sum over the wavefront with DPP on the two halves of the value (six steps of two moves
-// and one add, no LDS traffic); the result is uniform.  Lanes without a source add +0.0.
+// fp64 scans over the wavefront with DPP on the two halves of the value: six steps of two moves and
+// one operation, no LDS traffic (a shuffle through the LDS crossbar costs two ds_bpermute per step
+// and their latency, six times in a row).  Lanes without a source lane, and rows a step leaves out,
+// take `old`, the operation's identity.
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_d(double v) {
+__device__ __forceinline__ double dpp_d(double v, double old = 0.0) {
     const unsigned long long b = (unsigned long long)__double_as_longlong(v);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)b, CTRL, ROW_MASK, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    const unsigned long long o = (unsigned long long)__double_as_longlong(old);
+    const int lo = __builtin_amdgcn_update_dpp((int)(unsigned)o, (int)(unsigned)b, CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp((int)(unsigned)(o >> 32), (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xF, false);
     return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
 }
-__device__ __forceinline__ double wave_sum_dpp(double v) {
+__device__ __forceinline__ double lane63_d(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, 63);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 63);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+// Inclusive prefix sum in lane order: within rows of 16 lanes, then row totals onto the rows after.
+__device__ __forceinline__ double wave_scan_incl(double v) {
     v += dpp_d<DPP_ROW_SHR1, 0xF>(v);
     v += dpp_d<DPP_ROW_SHR2, 0xF>(v);
     v += dpp_d<DPP_ROW_SHR4, 0xF>(v);
     v += dpp_d<DPP_ROW_SHR8, 0xF>(v);
     v += dpp_d<DPP_ROW_BCAST15, 0xA>(v);
     v += dpp_d<DPP_ROW_BCAST31, 0xC>(v);
-    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
-    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, 63);
-    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 63);
-    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-}
-
-// fp64 versions go through the LDS crossbar (ds_bpermute); they are used only
-// by the exact path.
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, WAVE);
     return v;
 }
+// Sum and maximum over the wavefront; the result is uniform.
+__device__ __forceinline__ double wave_sum_dpp(double v) { return lane63_d(wave_scan_incl(v)); }
+__device__ __forceinline__ double wave_sum(double v) { return wave_sum_dpp(v); }
 __device__ __forceinline__ double wave_max(double v) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) v = fmax(v, __shfl_xor(v, s, WAVE));
-    return v;
-}
-__device__ __forceinline__ double wave_scan_incl(double v) {
-    const int lane = threadIdx.x & (WAVE - 1);
-#pragma unroll
-    for (int s = 1; s < WAVE; s <<= 1) {
-        const double up = __shfl_up(v, s, WAVE);
-        if (lane >= s) v += up;
-    }
-    return v;
+    const double ninf = -__builtin_huge_val();
+    v = fmax(v, dpp_d<DPP_ROW_SHR1, 0xF>(v, ninf));
+    v = fmax(v, dpp_d<DPP_ROW_SHR2, 0xF>(v, ninf));
+    v = fmax(v, dpp_d<DPP_ROW_SHR4, 0xF>(v, ninf));
+    v = fmax(v, dpp_d<DPP_ROW_SHR8, 0xF>(v, ninf));
+    v = fmax(v, dpp_d<DPP_ROW_BCAST15, 0xA>(v, ninf));
+    v = fmax(v, dpp_d<DPP_ROW_BCAST31, 0xC>(v, ninf));
+    return lane63_d(v);
 }
 
 // v_exp_f32: 2^x, flushes denormal results to zero, 2^-inf = 0.

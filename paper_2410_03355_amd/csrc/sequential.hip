@@ -10,8 +10,9 @@
 // With k = 1 or delta = 0 this is recursive rejection sampling, which keeps the target law.
 //
 // The chain t_1, t_2, ... is sequential, so one workgroup of 1024 threads walks one tree and keeps
-// the current target and the drafter's distribution as fp64 probability vectors in a workspace
-// (2 V doubles per tree, cache resident), evaluated in fp64.  The test of a group's first child is
+// the current target and the drafter's distribution as fp64 vectors (unnormalised terms and a
+// scale each: no division per token), the drafter's in a workspace (cache resident), the current
+// target in LDS when it fits and in the workspace otherwise; evaluated in fp64.  The test of a group's first child is
 // the plain verification of that candidate, so its decision is read from the row-parallel pass
 // (lantern_decide_rows over all candidates, launched first): only groups whose first child is
 // rejected build the vectors.
@@ -21,6 +22,7 @@
 
 #include "device_utils.h"
 #include "exp64.h"
+#include "lds_limit.h"
 #include "sequential_args.h"
 #include "verify_common.h"
 
@@ -29,23 +31,17 @@ namespace lantern {
 constexpr int SNT = 1024;
 constexpr int SNW = SNT / WAVE;
 
-__device__ __forceinline__ double lane63_d(double v) {
-    const unsigned long long u = (unsigned long long)__double_as_longlong(v);
-    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u & 0xffffffffull), 63);
-    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), 63);
-    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-}
-
 // Elements a thread keeps in flight per step of a pass: the loads of a step are all issued before
 // the first of them is used, so a pass pays the memory latency once per step, not once per element.
 constexpr int SU = 8;
 
-// softmax of the target row and of the drafter's row into pt[0, V) and pg[0, V) (fp64):
-// exp(l - max) / sum for each.  Returns false, with the outputs unspecified, if either row has a
-// NaN, a +inf or no finite logit.  Ends with every thread past a barrier that follows its last
-// write.
+// Unnormalised softmax terms exp(l - max) of the target row and of the drafter's row into
+// pt[0, V) and pg[0, V) (fp64), and their sums into *zt and *zg: the probabilities are pt[x] / *zt
+// and pg[x] / *zg.  Returns false, with the outputs unspecified, if either row has a NaN, a +inf
+// or no finite logit.  Ends with every thread past a barrier that follows its last write.
 template <typename LT>
-__device__ bool softmax_pair(const LT* trow, const LT* grow, int V, double* pt, double* pg, ExactShared& sh, int tid) {
+__device__ bool softmax_pair(const LT* trow, const LT* grow, int V, double* pt, double* pg, double* zt_out,
+                             double* zg_out, ExactShared& sh, int tid) {
     using L = Lane<LT>;
     const float inf = __builtin_huge_valf();
     float mt = -inf, mg = -inf;
@@ -91,25 +87,8 @@ __device__ bool softmax_pair(const LT* trow, const LT* grow, int V, double* pt, 
             }
         }
     }
-    zt = block_sum<SNW>(zt, sh.red, tid);
-    zg = block_sum<SNW>(zg, sh.red2, tid);
-    for (int xb = tid; xb < V; xb += SNT * SU) {   // the elements this thread wrote
-        double et[SU], eg[SU];
-#pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            const int x = xb + u * SNT;
-            et[u] = x < V ? pt[x] : 0.0;
-            eg[u] = x < V ? pg[x] : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            const int x = xb + u * SNT;
-            if (x < V) {
-                pt[x] = et[u] / zt;
-                pg[x] = eg[u] / zg;
-            }
-        }
-    }
+    *zt_out = block_sum<SNW>(zt, sh.red, tid);
+    *zg_out = block_sum<SNW>(zg, sh.red2, tid);
     __syncthreads();
     return true;
 }
@@ -129,8 +108,14 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
     const int M = a.M;
     const int32_t* par = a.parent + (int64_t)b * M;
     int32_t* path = a.out_path + (int64_t)b * M;
-    double* cur = a.work + (int64_t)b * 2 * V;   // t_j
-    double* g = cur + V;                          // the drafter's distribution of the group
+    // t_j and the drafter's distribution of the group, both unnormalised: t_j(x) = cur[x] * inv_st,
+    // g(x) = g[x] * inv_sg.  The drafter's terms are written once per group and then only read: they
+    // stay in the workspace.  t_j is read at random by the walk and rewritten for every rejected
+    // child: it lives in LDS when V doubles fit beside the rest (a.cur_in_lds), else in the workspace.
+    extern __shared__ __align__(16) unsigned char seq_smem[];
+    double* cur = a.cur_in_lds ? reinterpret_cast<double*>(seq_smem) : a.work + (int64_t)b * 2 * V;
+    double* g = a.work + (int64_t)b * 2 * V + V;
+    double inv_st = 0.0, inv_sg = 0.0, st = 0.0;
     const double delta = (double)a.delta;
 
     // the part of the vocabulary this wavefront sums and scans: [x0, x1), in steps of 64
@@ -191,9 +176,13 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                 have_rows = true;
                 group_row = r;
                 bool ok = (r >= 0 && r < a.R);
+                double sg = 0.0;
                 if (ok)
                     ok = softmax_pair<LT>(reinterpret_cast<const LT*>(a.target) + (int64_t)r * a.stride,
-                                          reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, V, cur, g, sh, tid);
+                                          reinterpret_cast<const LT*>(a.draft) + (int64_t)r * a.stride, V, cur, g, &st,
+                                          &sg, sh, tid);
+                inv_st = 1.0 / st;
+                inv_sg = 1.0 / sg;
                 if (!ok) {
                     next = -2;
                     break;
@@ -213,7 +202,7 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
             }
 
             // ---- nearest-first walk on t_j (Algorithm 2, inference part) ----
-            const double t_tok = cur[xt];
+            const double t_tok = cur[xt] * inv_st;
             double carry = 0.0, S = 0.0;
             int a_size = k;
             for (int base = 0; base < k; base += SNT) {
@@ -221,7 +210,7 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                 const bool valid = j < k;
                 const int n = valid ? nrow[j] : xt;
                 const bool self = (n == xt);
-                const double tj = self ? 0.0 : cur[n];
+                const double tj = self ? 0.0 : cur[n] * inv_st;
                 double ctot;
                 const double incl = carry + block_scan_incl<SNW>(tj, sh.red, tid, &ctot);
                 const int fail_j =
@@ -242,7 +231,7 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                 S = carry;
             }
             const double mass = t_tok + S;
-            const double gx = g[xt];
+            const double gx = g[xt] * inv_sg;
             const double u_acc = (double)a.uniforms[2 * c];
             const double u_res = (double)a.uniforms[2 * c + 1];
             if (u_acc * gx < mass) {
@@ -256,7 +245,7 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                 const int n = nrow[j];
                 if (n != xt) cur[n] = 0.0;
             }
-            if (tid == 0) cur[xt] = mass;
+            if (tid == 0) cur[xt] = mass * st;
             __syncthreads();
             double pr = 0.0, pt = 0.0;
             for (int xb = x0 + lane; xb < x1; xb += WAVE * SU) {
@@ -269,9 +258,10 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                 }
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const double d = ta[u] - gv[u];
+                    const double tn = ta[u] * inv_st;
+                    const double d = tn - gv[u] * inv_sg;
                     pr += (d > 0.0) ? d : 0.0;
-                    pt += ta[u];
+                    pt += tn;
                 }
             }
             pr = wave_sum(pr);
@@ -303,7 +293,7 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                     const int x = xb + u * WAVE + lane;
                     const double ta = x < x1 ? cur[x] : 0.0;
                     const double gv = (x < x1 && !zero_resid) ? g[x] : 0.0;
-                    const double d = ta - gv;
+                    const double d = ta * inv_st - gv * inv_sg;
                     rx[u] = (d > 0.0) ? d : 0.0;
                 }
 #pragma unroll
@@ -314,9 +304,11 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
                     const unsigned long long m = __ballot(valid && incl > edge);
                     if (found == INT_MAX && m) found = xb + u * WAVE + __ffsll((long long)m) - 1;
                     run = lane63_d(incl);
-                    if (valid) cur[x] = rx[u] / zz;
+                    if (valid) cur[x] = rx[u];   // t_{j+1}, unnormalised: its scale is zz
                 }
             }
+            st = zz;
+            inv_st = 1.0 / zz;
             next = block_min_i<SNW>(found, sh.ired, tid);
             if (next == INT_MAX) next = -1;
             __syncthreads();   // t_{j+1} is complete
@@ -332,19 +324,37 @@ __global__ __launch_bounds__(SNT) void trees_sequential(SequentialArgs a) {
     }
 }
 
-hipError_t prepare_sequential() {
+// LDS for the current target: V doubles when they fit beside the static arrays of the kernel.
+constexpr size_t SEQ_LDS_BUDGET = 150 * 1024;
+static size_t sequential_lds_bytes(int V) {
+    const size_t need = (size_t)V * sizeof(double);
+    return need <= SEQ_LDS_BUDGET ? need : 0;
+}
+
+template <typename LT>
+static hipError_t launch_typed(SequentialArgs a, hipStream_t stream, bool launch) {
+    const size_t lds = sequential_lds_bytes(a.V);
+    a.cur_in_lds = lds > 0 ? 1 : 0;
+    const hipError_t e = allow_lds<&trees_sequential<LT>>(lds);
+    if (e != hipSuccess || !launch) return e;
+    hipLaunchKernelGGL((trees_sequential<LT>), dim3(a.B), dim3(SNT), lds, stream, a);
+    return hipGetLastError();
+}
+
+// Loads the kernels on the current device and raises their LDS limit for this vocabulary size.
+hipError_t prepare_sequential(int logits_dtype, int V) {
+    SequentialArgs a{};
+    a.V = V;
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&trees_sequential<float>));
-    if (e == hipSuccess) e = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&trees_sequential<uint16_t>));
-    return e;
+    hipError_t e = hipFuncGetAttributes(&attr, logits_dtype == 0
+                                                   ? reinterpret_cast<const void*>(&trees_sequential<float>)
+                                                   : reinterpret_cast<const void*>(&trees_sequential<uint16_t>));
+    if (e != hipSuccess) return e;
+    return logits_dtype == 0 ? launch_typed<float>(a, nullptr, false) : launch_typed<uint16_t>(a, nullptr, false);
 }
 
 hipError_t launch_trees_sequential(const SequentialArgs& a, int logits_dtype, hipStream_t stream) {
-    if (logits_dtype == 0)
-        hipLaunchKernelGGL((trees_sequential<float>), dim3(a.B), dim3(SNT), 0, stream, a);
-    else
-        hipLaunchKernelGGL((trees_sequential<uint16_t>), dim3(a.B), dim3(SNT), 0, stream, a);
-    return hipGetLastError();
+    return logits_dtype == 0 ? launch_typed<float>(a, stream, true) : launch_typed<uint16_t>(a, stream, true);
 }
 
 }  // namespace lantern

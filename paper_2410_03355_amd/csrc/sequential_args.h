@@ -27,11 +27,13 @@ struct SequentialArgs {
     int32_t* out_path;         // [B*M]
     int32_t* out_next;         // [B]
     double* work;              // [B, 2, V] current target and drafter distribution of every tree
+    int cur_in_lds;            // set by the launch: the current target lives in LDS (V doubles fit)
 };
 
 // One workgroup per tree.  logits_dtype: 0 fp32, 1 bf16.
 hipError_t launch_trees_sequential(const SequentialArgs& a, int logits_dtype, hipStream_t stream);
 
-hipError_t prepare_sequential();   // loads the kernels on the current device
+// Loads the kernels on the current device and raises their LDS limit for this vocabulary size.
+hipError_t prepare_sequential(int logits_dtype, int V);
 
 }  // namespace lantern
