@@ -35,17 +35,17 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # (FETCH_SIZE scaled by the factor a plain 256 MiB copy gives in the same run).  Counters cannot be
 # read from inside this process, so the figure is a record of that run: it is reported only while the
 # library still has the version it was measured at, and with the file it comes from.
-_FETCH_SCALE = 262144.0 / 131090.1   # what FETCH_SIZE read for a 256 MiB copy in the same run
+_FETCH_SCALE = 262144.0 / 131089.9   # what FETCH_SIZE read for a 256 MiB copy in the same run
 MEASURED_TRAFFIC = {
     # (workload, variant, mode): (bytes per launch, library version, source)
-    ("stress", "plain", "sample"): ((130998.1 * _FETCH_SCALE + 240.2) * 1024, 210,
-                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 210)"),
-    ("stress", "reject", "sample"): ((167830.1 * _FETCH_SCALE + 14007.1) * 1024, 210,
-                                     "profiles/verify_fast_stress_plain.md (reject mix; version 210)"),
-    ("wide_latent", "plain", "sample"): ((124425.0 * _FETCH_SCALE + 246.8) * 1024, 210,
-                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 210)"),
-    ("stress", "plain", "greedy"): ((69193.1 * _FETCH_SCALE + 240.0) * 1024, 210,
-                                    "profiles/greedy_fast_stress_plain.md (version 210)"),
+    ("stress", "plain", "sample"): ((131000.1 * _FETCH_SCALE + 240.2) * 1024, 220,
+                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 220)"),
+    ("stress", "reject", "sample"): ((165145.9 * _FETCH_SCALE + 4925.2) * 1024, 220,
+                                     "profiles/verify_fast_stress_plain.md (reject mix; version 220)"),
+    ("wide_latent", "plain", "sample"): ((124425.8 * _FETCH_SCALE + 240.3) * 1024, 220,
+                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 220)"),
+    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 220,
+                                    "profiles/greedy_fast_stress_plain.md (version 220)"),
 }
 
 
