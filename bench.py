@@ -49,6 +49,17 @@ MEASURED_TRAFFIC = {
 }
 
 
+# Per-kernel split of a table build, from the kernel trace summarised under profiles/ (events inside this
+# process only bracket the whole build): us per block of 2048 query rows, reported under the same rule.
+MEASURED_KNN_SPLIT = {
+    # workload: ({kernel: us per block}, blocks per build, library version, source)
+    "stress": ({"contraction": 52.3, "selection": 123.5, "exact_check": 6.2}, 8, 220,
+               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 220)"),
+    "wide_latent": ({"contraction": 52.7, "selection": 57.1, "exact_check": 6.0}, 4, 220,
+                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 220)"),
+}
+
+
 def algorithmic_bytes_per_verification(V: int, k: int, logit_bytes: int) -> int:
     """Both logit rows once, one table row, token, two uniforms, two outputs."""
     return 2 * V * logit_bytes + 4 * k + 20
@@ -210,16 +221,26 @@ def time_knn_build(lantern, codebook, k, repeats=3):
     return knn, ms[len(ms) // 2]
 
 
-def knn_report(cfg, build_ms):
+def knn_report(cfg, build_ms, version=None):
     """The build against the MFMA roofline of its contraction (2 V^2 d flop in the codebook's type) and
     against the HBM roofline of what it must move (codebook in, table out)."""
     flop = 2.0 * cfg.V * cfg.V * cfg.d
     peak = MFMA_PEAK_TFLOPS[cfg.cb_dtype]
     io_bytes = cfg.V * cfg.d * (2 if cfg.cb_dtype == "bf16" else 4) + 4 * cfg.V * cfg.k
-    return {"codebook": f"V={cfg.V} d={cfg.d} {cfg.cb_dtype} k={cfg.k}", "build_ms": build_ms,
-            "contraction_flop": flop, "mfma_peak_tflops": peak,
-            "mfma_frac": flop / (build_ms * 1e-3) / 1e12 / peak,
-            "algorithmic_bytes": io_bytes, "hbm_frac": io_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    rep = {"codebook": f"V={cfg.V} d={cfg.d} {cfg.cb_dtype} k={cfg.k}", "build_ms": build_ms,
+           "contraction_flop": flop, "mfma_peak_tflops": peak,
+           "mfma_frac": flop / (build_ms * 1e-3) / 1e12 / peak,
+           "algorithmic_bytes": io_bytes, "hbm_frac": io_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    split = MEASURED_KNN_SPLIT.get(cfg.name)
+    if split is not None and version == split[2]:
+        per_block, blocks = split[0], split[1]
+        rep["contraction_ms"] = per_block["contraction"] * blocks * 1e-3
+        rep["select_ms"] = per_block["selection"] * blocks * 1e-3
+        rep["exact_check_ms"] = per_block["exact_check"] * blocks * 1e-3
+        # the contraction alone against the matrix-core peak of its type
+        rep["contraction_mfma_frac"] = flop / (rep["contraction_ms"] * 1e-3) / 1e12 / peak
+        rep["split_source"] = split[3]
+    return rep
 
 
 def main() -> int:
@@ -385,7 +406,7 @@ def main() -> int:
                                 "workgroup per 64 KiB: what a kernel with this access pattern reaches on this device",
         },
         "knn_build_ms": knn_build_ms,
-        "knn": {cfg.name: knn_report(cfg, knn_build_ms)},
+        "knn": {cfg.name: knn_report(cfg, knn_build_ms, int(lib.lantern_version()))},
     }
 
     if extras:
@@ -422,7 +443,7 @@ def main() -> int:
                                    "sibling rule (its accepted_fraction is accepted nodes / candidates); frac = algorithmic bytes / kernel time / 8 TB/s")
         wl = workloads.CONFIGS["wide_latent"]
         _, wl_ms = time_knn_build(lantern, workloads.make_codebook(wl, device=dev), wl.k)
-        result["knn"][wl.name] = knn_report(wl, wl_ms)
+        result["knn"][wl.name] = knn_report(wl, wl_ms, int(lib.lantern_version()))
 
     if not args.no_cpu_baseline and args.mode == "sample" and args.divergence == "tvd":
         import numpy as np  # noqa: F401
