@@ -373,19 +373,20 @@ __global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const f
 }
 
 // ---- stage 2: select, re-rank exactly, emit ----
+constexpr int SEL_MAXW = 8;   // wavefronts of the largest selection workgroup (512 threads)
 template <int CAP>
 struct SelectShared {
     double key[CAP];
     int idx[CAP];
-    unsigned red_u[2 * NW];
-    int red_c[2][NW];     // per-wavefront counts of a counting pass, double-buffered
+    unsigned red_u[2 * SEL_MAXW];
+    int red_c[2][SEL_MAXW];   // per-wavefront counts of a counting pass, double-buffered
 };
 
 // Error model of the approximate keys:
 //   |approximate - exact| <= err_rel * |exact| + err_abs + err_norm * (norm_i + max norm)
 // (the last term applies when norms is not null: keys formed as n_i + n_j - 2 G_ij).
 //
-// NK > 0: the row's V <= NK * 256 approximate keys are held in registers as order-preserving
+// NK > 0: the row's V <= NK * TNT approximate keys (TNT threads per row) are held in registers as order-preserving
 // unsigned integers; NK == 0: they are re-read from the workspace in every pass.
 // A threshold with between k-1+pad and `fit` keys at or below it is found by bisection over the
 // keys' integer range, every step one counting pass over the registers (compare, add, one
@@ -401,11 +402,12 @@ __device__ __forceinline__ void for_keys(int npt, F body) {
     }
 }
 
-template <typename CT, int NK, int CAP>
-__global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
+template <typename CT, int NK, int CAP, int TNT>
+__global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
                                                  const float* dist, float err_rel, float err_abs,
                                                  float err_norm, const float* norms, const float* nmax,
                                                  int32_t* out, int* flags) {
+    constexpr int TNW = TNT / WAVE;
     __shared__ SelectShared<CAP> sh;
     const int row = blockIdx.x;
     const int i = r0 + row;
@@ -431,23 +433,23 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
 
     constexpr int NKR = NK > 0 ? NK : 1;
     uint32_t keys[NKR];
-    const int npt = NK > 0 ? NK : (V + NT - 1) / NT;   // keys per thread
+    const int npt = NK > 0 ? NK : (V + TNT - 1) / TNT;   // keys per thread
     // Token of element e of this thread.  Keys in registers: groups of four consecutive tokens per
-    // thread, (e / 4) * NT + tid being the group, so that a group is one 16-byte load; else e * NT + tid.
+    // thread, (e / 4) * TNT + tid being the group, so that a group is one 16-byte load; else e * TNT + tid.
     auto token_of = [&](int e) -> int {
-        return NK > 0 ? (((e >> 2) * NT + tid) << 2) + (e & 3) : e * NT + tid;
+        return NK > 0 ? (((e >> 2) * TNT + tid) << 2) + (e & 3) : e * TNT + tid;
     };
     // key of element e; 0xFFFFFFFF for the row's own token and padding
     auto key_at = [&](int e) -> uint32_t {
         if (NK > 0) return keys[e];
-        const int j = e * NT + tid;
+        const int j = e * TNT + tid;
         return (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
     };
     if (NK > 0) {
         const bool row_vec = (V & 3) == 0;   // then every row of the key block starts 16-byte aligned
 #pragma unroll
         for (int g = 0; g < NKR / 4; ++g) {
-            const int j0 = (g * NT + tid) << 2;
+            const int j0 = (g * TNT + tid) << 2;
             float f[4];
             if (row_vec && j0 + 3 < V) {
                 const float4 q = *reinterpret_cast<const float4*>(drow + j0);
@@ -473,11 +475,11 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     // unsigned order through signed scans: flip the top bit
     kmin = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMin>((int)(kmin ^ 0x80000000u), INT_MAX), 63) ^ 0x80000000u;
     kmax = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMax>((int)(kmax ^ 0x80000000u), INT_MIN), 63) ^ 0x80000000u;
-    if (lane == 0) { sh.red_u[wave] = kmin; sh.red_u[NW + wave] = kmax; }
+    if (lane == 0) { sh.red_u[wave] = kmin; sh.red_u[TNW + wave] = kmax; }
     __syncthreads();
-    kmin = sh.red_u[0]; kmax = sh.red_u[NW];
+    kmin = sh.red_u[0]; kmax = sh.red_u[TNW];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) { kmin = min(kmin, sh.red_u[w]); kmax = max(kmax, sh.red_u[NW + w]); }
+    for (int w = 1; w < TNW; ++w) { kmin = min(kmin, sh.red_u[w]); kmax = max(kmax, sh.red_u[TNW + w]); }
 
     // the sort works on a power of two: aim at the smallest one that holds `want`
     int fit = 1;
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         __syncthreads();         // one barrier per pass: the buffers alternate
         c = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) c += sh.red_c[pass & 1][w];
+        for (int w = 0; w < TNW; ++w) c += sh.red_c[pass & 1][w];
         if (c < want) {
             lo = mid64;
         } else {
@@ -532,7 +534,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     int count = 0;
     uint32_t thr_max = 0u;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < TNW; ++w) {
         if (w < wave) slot += sh.red_c[0][w];
         count += sh.red_c[0][w];
         thr_max = max(thr_max, sh.red_u[w]);
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
     const float thr = ord_inv(thr_max);   // every discarded token has an approximate key above this
     int P = 1;
     while (P < count) P <<= 1;
-    for (int c = tid; c < P; c += NT) {
+    for (int c = tid; c < P; c += TNT) {
         if (c < count) {
             sh.key[c] = exact_key<CT>(cb, d, i, sh.idx[c], metric, vec4);
         } else {
@@ -569,7 +571,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
             }
-            for (int t = tid; t < (P >> 1); t += NT) {
+            for (int t = tid; t < (P >> 1); t += TNT) {
                 const int l = 2 * t - (t & (stride - 1));
                 const int r = l + stride;
                 const bool up = (l & size) == 0;
@@ -600,7 +602,7 @@ __global__ __launch_bounds__(NT) void knn_select(const CT* cb, int V, int d, int
         if (tid == 0) flags[row] = 1;
         return;
     }
-    for (int s = tid; s < need; s += NT) orow[1 + s] = sh.idx[s];
+    for (int s = tid; s < need; s += TNT) orow[1 + s] = sh.idx[s];
 }
 
 // ---- stage 3: flagged rows, all V keys in fp64, rank by counting ----
@@ -689,20 +691,24 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
         // of workgroups a compute unit holds at once, and that number is set by this LDS footprint
         // (12 bytes a slot).
         const int want_slots = (a.k - 1) + 8 + (a.k - 1) / 128;
-#define LANTERN_LAUNCH_SELECT(NKV, CAPV)                                                                    \
-        hipLaunchKernelGGL((knn_select<CT, NKV, CAPV>), dim3(rows), dim3(NT), 0, stream, cb, a.V, a.d, a.k,  \
-                           a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
-#define LANTERN_LAUNCH_SELECT_NK(NKV)                                                                       \
+#define LANTERN_LAUNCH_SELECT(NKV, CAPV, TNTV)                                                              \
+        hipLaunchKernelGGL((knn_select<CT, NKV, CAPV, TNTV>), dim3(rows), dim3(TNTV), 0, stream, cb, a.V, a.d, \
+                           a.k, a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
+#define LANTERN_LAUNCH_SELECT_NK(NKV, TNTV)                                                                 \
         do {                                                                                                \
-            if (want_slots <= 256) LANTERN_LAUNCH_SELECT(NKV, 256);                                         \
-            else if (want_slots <= 1024) LANTERN_LAUNCH_SELECT(NKV, 1024);                                  \
-            else if (want_slots <= 2048) LANTERN_LAUNCH_SELECT(NKV, 2048);                                  \
-            else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP);                                                      \
+            if (want_slots <= 256) LANTERN_LAUNCH_SELECT(NKV, 256, TNTV);                                   \
+            else if (want_slots <= 1024) LANTERN_LAUNCH_SELECT(NKV, 1024, TNTV);                            \
+            else if (want_slots <= 2048) LANTERN_LAUNCH_SELECT(NKV, 2048, TNTV);                            \
+            else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP, TNTV);                                                \
         } while (0)
-        if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8);
-        else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32);
-        else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64);
-        else LANTERN_LAUNCH_SELECT_NK(0);
+        // threads per row and keys per thread: up to 64 keys per thread in registers; vocabularies
+        // beyond 64 x 256 tokens take 512 threads per row (32 keys per thread on 512 threads measured
+        // the same as 64 on 256 at V = 16384); beyond 64 x 512 the keys are re-read in every pass
+        if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8, NT);
+        else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32, NT);
+        else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64, NT);
+        else if (a.V <= 64 * 512) LANTERN_LAUNCH_SELECT_NK(64, 512);
+        else LANTERN_LAUNCH_SELECT_NK(0, NT);
 #undef LANTERN_LAUNCH_SELECT_NK
 #undef LANTERN_LAUNCH_SELECT
         const int wgs = rows < L.slow_wgs ? rows : L.slow_wgs;

@@ -74,6 +74,19 @@ def test_shapes(oracle_mod, lantern_gpu, V, d, k, dtype):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("V,d,k,dtype", [(20001, 8, 300, torch.float32), (32768, 16, 64, torch.bfloat16),
+                                         (33000, 4, 20, torch.float32)])
+def test_large_vocabularies(oracle_mod, lantern_gpu, V, d, k, dtype):
+    """Vocabularies beyond 16384: 512 threads per row with the keys in registers up to 32768 tokens
+    (ragged and full), and beyond that the variant that re-reads the keys; whole tables compared."""
+    g = torch.Generator().manual_seed(V + d)
+    cb = torch.randn(V, d, generator=g).to(dtype)
+    got = _gpu_table(lantern_gpu, cb, k)
+    _check_structure(got, V, k)
+    want = oracle_mod.build_knn(cb.float().numpy(), k, threads=16)
+    np.testing.assert_array_equal(got, want)
+
+
 def test_exact_ties_and_duplicates(oracle_mod, lantern_gpu):
     """Integer lattice (many exactly equal distances) and repeated codes: the
     lower index wins and the token itself stays in slot 0."""
