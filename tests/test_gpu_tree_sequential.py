@@ -246,3 +246,46 @@ def test_capture_and_replay(oracle_mod, lantern_gpu):
         np.testing.assert_array_equal(n.cpu().numpy(), n_o)
         np.testing.assert_array_equal(path.cpu().numpy(), path_o)
         np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+
+
+@pytest.mark.parametrize("V,k,dtype", [(24001, 700, torch.float32), (1 << 19, 64, torch.bfloat16)])
+def test_vocabularies_beyond_the_lds_copy(oracle_mod, lantern_gpu, V, k, dtype):
+    """Beyond 19200 tokens the current target no longer fits in LDS and lives in the workspace; up to the
+    largest vocabulary the library takes.  Children drafted as the drafter's most likely tokens, draws
+    that reject often."""
+    rng = np.random.default_rng(V)
+    B, M = 3, 7
+    parent = random_trees(rng, B, M, max_children=3)
+    R = B * (M + 1)
+    tl = torch.from_numpy(rng.normal(0, 2.5, (R, V)).astype(np.float32)).to(dtype)
+    dl = torch.from_numpy((tl.float().numpy() + rng.normal(0, 1.0, (R, V))).astype(np.float32)).to(dtype)
+    row_index = (np.arange(B, dtype=np.int64)[:, None] * (M + 1) + parent + 1).astype(np.int32).reshape(-1)
+    rank = np.zeros((B, M), dtype=np.int64)
+    for b in range(B):
+        seen = {}
+        for i in range(M):
+            rank[b, i] = seen.get(parent[b, i], 0)
+            seen[parent[b, i]] = rank[b, i] + 1
+    top = torch.topk(dl.float(), int(rank.max()) + 1, dim=1).indices.numpy()
+    tokens = top[row_index, rank.reshape(-1)].astype(np.int32)
+    # every row valid (the token itself, then its successors); the rows of the drafted tokens random
+    table = ((np.arange(V, dtype=np.int64)[:, None] + np.arange(k, dtype=np.int64)[None, :]) % V).astype(np.int32)
+    for x in set(int(t) for t in tokens):
+        others = rng.choice(V - 1, size=k - 1, replace=False)
+        table[x, 1:] = others + (others >= x)
+    un = torch.from_numpy(rng.random((B * M, 2)).astype(np.float32))
+    un[::2, 0] = 0.9999
+    resampled = 0
+    for delta in (0.0, 0.1):
+        n_o, path_o, next_o = oracle_mod.verify_trees_sequential(tl, dl, row_index, parent, M, tokens, table, k, delta,
+                                                                 un, threads=8)
+        n, path, nxt = lantern_gpu.verify_trees_sequential(tl.cuda(), dl.cuda(), torch.from_numpy(row_index).cuda(),
+                                                           torch.from_numpy(parent).cuda().reshape(-1), M,
+                                                           torch.from_numpy(tokens).cuda(),
+                                                           torch.from_numpy(table).cuda(), delta, un.cuda())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(path.cpu().numpy(), path_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), next_o)
+        resampled += int((next_o >= 0).sum())
+    assert resampled > 0
