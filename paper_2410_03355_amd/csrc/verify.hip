@@ -78,7 +78,7 @@ __device__ void exact_row(const VerifyArgs& a, int row, unsigned char* ex, const
 // registers from the fp32 pass on would cost that pass registers it does not have), the target row
 // is in LDS, the first 1024 table slots in registers.
 constexpr int AMB_CAP = 40;          // tokens whose residual sign fp32 leaves open (about one per row)
-constexpr double TAU_SIGN = 2.0e-5;  // covers the errors of the two fp32 sums in the sign test (<= 8.8e-6 together)
+constexpr double TAU_SIGN = 2.0e-5;  // covers the error of ln(Z_t32 / Z_g32) in the sign test (<= 8.8e-6)
 
 struct AmbEntry {
     double et, eg;   // unnormalised fp64 terms
@@ -114,11 +114,12 @@ __device__ __forceinline__ double one_pass_term(float lt, float lg, bool zero, d
 
 // What the pass does for one token: its fp64 terms into the normalisers; into the segment's sums
 // when the residual is certainly positive; onto the list when that cannot be told.
-// The sign test compares the fp64 terms across the fp32 sums: t(x) > g(x) <=> e_t Z_g > e_g Z_t,
-// where only Z_t32 and Z_g32 carry an error (at most 4.4e-6 relative each: terms 2.5e-6, tree
-// sums 1.9e-6), so a margin of TAU_SIGN = 2e-5 on either side makes "positive" and "not positive"
-// certain.  floor_t, floor_g: the row's reference logit minus 700; logits below it (filtered
-// tokens at -inf among them) are evaluated there: a term of 1e-304 of the sum either way.
+// The sign test works on the exponents: t(x) > g(x) <=> (l_t - r_t) - (l_g - r_g) > ln(Z_t / Z_g),
+// where only the two fp32 sums on the right carry an error (at most 4.4e-6 relative each: terms
+// 2.5e-6, tree sums 1.9e-6, i.e. 8.8e-6 on the logarithm), so a margin of TAU_SIGN = 2e-5 on either
+// side of ln(Z_t32 / Z_g32) makes "positive" and "not positive" certain.  floor_t, floor_g: the row's
+// reference logit minus 700; logits below it (filtered tokens at -inf among them) are evaluated
+// there: a term of 1e-304 of the sum either way.
 // max of two floats as the one hardware instruction (fmaxf first quiets both operands, two more
 // instructions per call; no NaN reaches this path).
 __device__ __forceinline__ float max_f32_1(float a, float b) {
@@ -131,15 +132,17 @@ struct OnePassAcc {
     double zt, zg, pt, pg;
 };
 __device__ __forceinline__ void one_pass_token(OnePassAcc& acc, float lt, float lg, bool zero, int x, double rt,
-                                               double rg, float floor_t, float floor_g, double Zt, double Zg,
+                                               double rg, float floor_t, float floor_g, double ln_hi, double ln_lo,
                                                const unsigned char* tab, AmbEntry* amb, int* amb_count) {
-    const double et = exp_tab_core((double)max_f32_1(lt, floor_t) - rt, tab);
-    const double eg = exp_tab_core((double)max_f32_1(lg, floor_g) - rg, tab);
+    const double dt = (double)max_f32_1(lt, floor_t) - rt;
+    const double dg = (double)max_f32_1(lg, floor_g) - rg;
+    const double et = exp_tab_core(dt, tab);
+    const double eg = exp_tab_core(dg, tab);
     acc.zt += et;
     acc.zg += eg;
-    const double lhs = et * Zg, rhs = eg * Zt;              // t(x) > g(x)  <=>  lhs > rhs
-    const bool pos = !zero && (rhs < lhs * (1.0 - TAU_SIGN));
-    const bool neg = zero || (lhs < rhs * (1.0 - TAU_SIGN));
+    const double dd = dt - dg;                               // t(x) > g(x)  <=>  dd > ln(Z_t / Z_g)
+    const bool pos = !zero && (dd > ln_hi);
+    const bool neg = zero || (dd < ln_lo);
     const double m = pos ? 1.0 : 0.0;
     acc.pt = __builtin_fma(et, m, acc.pt);
     acc.pg = __builtin_fma(eg, m, acc.pg);
@@ -229,7 +232,16 @@ __device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int
     acc.zt = 0.0;
     acc.zg = 0.0;
     const float floor_t = ref_t - 700.f, floor_g = ref_g - 700.f;
-    const double Zt64 = (double)Zt32, Zg64 = (double)Zg32;
+    // ln(Z_t / Z_g) from the fp32 sums (both finite and at least one).  Their terms are
+    // 2^(l * LOG2E_F - c) with c = ref * LOG2E_F rounded to fp32, the fp64 terms here e^(l - ref): per
+    // term the two differ by (l - ref) (LOG2E_F - log2 e), which the term's error bound holds, and by
+    // the rounding of c, common to the row and known exactly (the product of two floats is exact in
+    // fp64): that one is put back.
+    const double LN2_D = 0.69314718055994530942;
+    const double adj_t = ((double)(ref_t * LOG2E_F) - rt * (double)LOG2E_F) * LN2_D;
+    const double adj_g = ((double)(ref_g * LOG2E_F) - rg * (double)LOG2E_F) * LN2_D;
+    const double ln_z = log((double)Zt32 / (double)Zg32) + adj_t - adj_g;
+    const double ln_hi = ln_z + TAU_SIGN, ln_lo = ln_z - TAU_SIGN;
 #pragma unroll 1
     for (int c = 0; c < NV; ++c) {
         uint4 gv = G[0];
@@ -250,8 +262,8 @@ __device__ __forceinline__ void exact_one_pass(const VerifyArgs& a, int row, int
             // and a filtered target token has t = 0
             const bool zero0 = (in_a & 1u) || (x0 + e == xt) || lt0 == neg_inf_f();
             const bool zero1 = (in_a & 2u) || (x0 + e + 1 == xt) || lt1 == neg_inf_f();
-            one_pass_token(acc, lt0, lg0, zero0, x0 + e, rt, rg, floor_t, floor_g, Zt64, Zg64, tab_lds, amb, amb_count);
-            one_pass_token(acc, lt1, lg1, zero1, x0 + e + 1, rt, rg, floor_t, floor_g, Zt64, Zg64, tab_lds, amb, amb_count);
+            one_pass_token(acc, lt0, lg0, zero0, x0 + e, rt, rg, floor_t, floor_g, ln_hi, ln_lo, tab_lds, amb, amb_count);
+            one_pass_token(acc, lt1, lg1, zero1, x0 + e + 1, rt, rg, floor_t, floor_g, ln_hi, ln_lo, tab_lds, amb, amb_count);
             tv = L::drop2(tv);
             gv = L::drop2(gv);
             in_a >>= 2;

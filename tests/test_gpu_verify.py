@@ -139,6 +139,26 @@ def test_stress_reject_heavy(oracle_mod, lantern_gpu):
     assert np.all(res[rej] >= 0) and np.all(res[~rej] == -1)
 
 
+@pytest.mark.parametrize("shift_t,shift_g", [(250.0, -180.0), (-600.0, 650.0)])
+def test_large_logit_offsets(oracle_mod, lantern_gpu, shift_t, shift_g):
+    """Rows whose logits sit far from zero (a softmax does not care): the reference of the fp32 pass
+    is then a large number, whose rounding the fp64 sign test of the rejected rows has to account for."""
+    V, k, N = 8192, 100, 384                                # fp32 logits: the offsets keep their resolution
+    rng = np.random.default_rng(31)
+    base = rng.normal(0.0, 1.5, (N, V))
+    tl = torch.from_numpy((base + shift_t).astype(np.float32))
+    dl = torch.from_numpy((base + rng.normal(0.0, 0.8, (N, V)) + shift_g).astype(np.float32))
+    tokens = dl.argmax(dim=1).to(torch.int32)               # the drafter's favourite: g(xt) > t(xt) mostly
+    un = torch.from_numpy(philox.uniforms(77, N, stream=1))
+    un[:, 0] = 1.0 - 2.0 ** -24                             # acceptance draw just below one
+    table = random_table(V, k, seed=9)
+    for delta in (0.0, 0.05):
+        acc, res, diag, g = compare_verify(oracle_mod, lantern_gpu, tl, dl, tokens, table, delta,
+                                           un, threads=16, label="offset logits")
+        assert (acc == 0).mean() > 0.2 and np.all(res[acc == 0] >= 0)
+        assert (g["path"][acc == 0] == 1).all()
+
+
 @pytest.mark.parametrize("V,k,N,dtype", [
     (1, 1, 3, torch.float32),          # degenerate vocabulary
     (7, 7, 5, torch.float32),          # ragged, k = V
