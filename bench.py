@@ -35,17 +35,17 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # (FETCH_SIZE scaled by the factor a plain 256 MiB copy gives in the same run).  Counters cannot be
 # read from inside this process, so the figure is a record of that run: it is reported only while the
 # library still has the version it was measured at, and with the file it comes from.
-_FETCH_SCALE = 262144.0 / 131089.9   # what FETCH_SIZE read for a 256 MiB copy in the same run
+_FETCH_SCALE = 262144.0 / 131097.1   # what FETCH_SIZE read for a 256 MiB copy in the same run
 MEASURED_TRAFFIC = {
     # (workload, variant, mode): (bytes per launch, library version, source)
-    ("stress", "plain", "sample"): ((131000.1 * _FETCH_SCALE + 240.2) * 1024, 220,
-                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 220)"),
-    ("stress", "reject", "sample"): ((165145.9 * _FETCH_SCALE + 4925.2) * 1024, 220,
-                                     "profiles/verify_fast_stress_plain.md (reject mix; version 220)"),
-    ("wide_latent", "plain", "sample"): ((124425.8 * _FETCH_SCALE + 240.3) * 1024, 220,
-                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 220)"),
-    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 220,
-                                    "profiles/greedy_fast_stress_plain.md (version 220)"),
+    ("stress", "plain", "sample"): ((130995.4 * _FETCH_SCALE + 240.1) * 1024, 221,
+                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 221)"),
+    ("stress", "reject", "sample"): ((167759.8 * _FETCH_SCALE + 13891.4) * 1024, 221,
+                                     "profiles/verify_fast_stress_plain.md (reject mix; version 221)"),
+    ("wide_latent", "plain", "sample"): ((124427.7 * _FETCH_SCALE + 240.6) * 1024, 221,
+                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 221)"),
+    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 221,
+                                    "profiles/greedy_fast_stress_plain.md (version 221)"),
 }
 
 
@@ -53,10 +53,10 @@ MEASURED_TRAFFIC = {
 # process only bracket the whole build): us per block of 2048 query rows, reported under the same rule.
 MEASURED_KNN_SPLIT = {
     # workload: ({kernel: us per block}, blocks per build, library version, source)
-    "stress": ({"contraction": 52.3, "selection": 123.5, "exact_check": 6.2}, 8, 220,
-               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 220)"),
-    "wide_latent": ({"contraction": 52.7, "selection": 57.1, "exact_check": 6.0}, 4, 220,
-                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 220)"),
+    "stress": ({"contraction": 52.3, "selection": 123.5, "exact_check": 6.2}, 8, 221,
+               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 221)"),
+    "wide_latent": ({"contraction": 52.7, "selection": 57.1, "exact_check": 6.0}, 4, 221,
+                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 221)"),
 }
 
 
