@@ -4,7 +4,7 @@
  *
  * The two operations of the method:
  *   lantern_build_knn  the latent-space neighbour table B_k of the VQ codebook
- *                      (Section 4.2; Algorithm 2, "Precompute B_k" part)
+ *                      (Section 4.2; Algorithm 2, precompute part)
  *   lantern_verify     one relaxed verification per row: TVD-bounded
  *                      neighbourhood A_{k,delta}, acceptance test, residual
  *                      resampling (Section 4.3; Algorithm 2, inference part;
