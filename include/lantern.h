@@ -143,7 +143,10 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
  * start at zero): calls that overlap in time on one GPU - from several streams
  * or threads - race and give undefined tables; serialise them.  The first call
  * on a device looks the array's address up (a runtime call, no allocation):
- * make it outside a stream capture.
+ * make it outside a stream capture.  The HIP runtime places the array in device
+ * memory when it loads the library's device code, which it may put off until
+ * the first launch of these kernels in the process: free device memory can
+ * drop by the array's size across that one call, never across a later one.
  * Errors: E_NULL, E_SHAPE, E_DTYPE, E_WORKSPACE (V over the limit), E_DEVICE.
  */
 #define LANTERN_STATIC_MAX_V 32768
