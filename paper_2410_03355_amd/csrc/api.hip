@@ -216,7 +216,7 @@ int lantern_accept_chains(const int32_t* accept, const int32_t* resample, int B,
 
 size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k) {
     if (!dtype_ok((int)cb_dtype) || V < 1 || d < 1 || k < 1 || k > V) return 0;
-    return lantern::knn_workspace_bytes(V, d, k);
+    return lantern::knn_workspace_bytes(V, d, k, (int)cb_dtype);
 }
 
 int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
@@ -226,7 +226,7 @@ int lantern_build_knn_metric(const void* codebook, lantern_dtype cb_dtype, int V
     if (V < 1 || d < 1 || k < 1 || k > V) return LANTERN_E_SHAPE;
     if (metric != LANTERN_METRIC_L2 && metric != LANTERN_METRIC_COSINE) return LANTERN_E_SHAPE;
     if (!codebook || !out_knn) return LANTERN_E_NULL;
-    const size_t need = lantern::knn_workspace_bytes(V, d, k);
+    const size_t need = lantern::knn_workspace_bytes(V, d, k, (int)cb_dtype);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
         return LANTERN_E_WORKSPACE;
     lantern::KnnArgs a;

@@ -12,6 +12,14 @@
 //      to it; otherwise it is flagged.
 //   3. flagged rows: fp64 keys for all V tokens and ranking by counting.
 // The written order is therefore always the fp64 one.
+//
+// Vocabularies of 4096 tokens and more (aligned codebooks, k from about 250 to about 1000) never form the
+// whole key block: a row's threshold is first estimated from the keys to a stratified sample of
+// one token in eight, the contraction then runs with an epilogue that appends only the
+// (key, token) pairs at or below the row's threshold to a short per-row list, and step 2 works
+// on that list.  The threshold only decides how many candidates a row gets; the proof condition
+// of step 2 is unchanged (every token left out has an approximate key above every key kept),
+// and a row whose list came out too short or too long is flagged like any other.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -31,28 +39,107 @@ constexpr int SLOW_WGS = 128;     // workgroups (and fp64 row buffers) of the ex
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Plan of the sampled-threshold path for one shape.  A row's threshold is the key of rank `rank`
+// among its keys to `S` sampled tokens; the number of keys at or below it over the whole row then
+// has mean `rank * V / S` and, for a sample drawn without replacement, a hypergeometric spread.
+// The mean is put 5.5 standard deviations above the k-1+pad candidates the selection wants and the
+// list capacity 7 above the largest mean the search for the threshold may stop at (either miss is below 1e-12 per row for every shape admitted;
+// a stratified sample spreads no wider than a simple one).  use == false: the shape takes the
+// whole-key-block path.
+struct FilterPlan {
+    bool use;
+    int S;      // sampled tokens, a multiple of 64, at most 4096
+    int rank;   // the threshold has between rank and rank + slack of a row's S sample keys at or below it
+    int slack;
+    int cap;    // slots of a row's candidate list: 2048, 3072 or 4096
+};
+
+static FilterPlan filter_plan(int V, int d, int k, int cb_dtype) {
+    FilterPlan P = {false, 0, 0, 0, 0};
+    const bool vec = cb_dtype == 1 ? (d % 8) == 0 : (d % 4) == 0;   // what the matrix-core kernels need
+    const int need = k - 1;
+    const int want = need + 8 + need / 128;
+    // 256 candidates or fewer: the selection is short next to the contraction, and sampling does not pay
+    if (!vec || V < 4096 || want <= 256 || want > 1024) return P;
+    int S = V / 8;
+    if (S > 4096) S = 4096;
+    S = S / 64 * 64;
+    const double rho = (double)V / (double)S;
+    const double zlo = 5.5, zhi = 7.0;
+    const double x = 0.5 * (zlo * sqrt(rho) + sqrt(zlo * zlo * rho + 4.0 * (double)want));
+    const double mean = x * x;
+    const double sd = sqrt(mean * rho);
+    int rank = (int)ceil(mean / rho);
+    if (rank > S) rank = S;
+    // the search for the threshold stops anywhere between rank and rank + slack (a sixteenth more)
+    const int slack = rank / 16 < S - rank ? rank / 16 : S - rank;
+    const double mean_hi = (double)(rank + slack) * rho;
+    const int cap = ((int)(mean_hi + zhi * sqrt(mean_hi * rho)) + 1023) / 1024 * 1024;
+    if (cap > 4096) return P;
+    P.use = true;
+    P.S = S;
+    P.rank = rank;
+    P.slack = slack;
+    P.cap = cap;
+    return P;
+}
+
 struct KnnLayout {
     size_t stats, norms, nmax, dist, flags, slow, total;
+    // sampled-threshold path (filter.use): the sample's codes and norms, a row block's keys to the
+    // sample, its thresholds, list lengths and candidate lists; `dist` is then not laid out
+    size_t scb, snorms, skeys, thr, counts, cand;
+    FilterPlan filter;
     int row_block;   // query rows per pass through the key block
     int slow_wgs;    // workgroups (and fp64 row buffers) of the exact pass
 };
 
-static KnnLayout knn_layout(int V, int row_block, int slow_wgs) {
+static KnnLayout knn_layout(int V, int d, int cb_dtype, const FilterPlan& plan, int row_block, int slow_wgs) {
     KnnLayout L;
+    L.filter = plan;
     L.row_block = V < row_block ? V : row_block;
     L.slow_wgs = slow_wgs;
     size_t off = 0;
     L.stats = off; off = align_up(off + 256, 256);   // int32[0]: rows that took the exact all-pairs pass
     L.norms = off; off = align_up(off + sizeof(float) * (size_t)V, 256);
     L.nmax = off;  off = align_up(off + 256, 256);
-    L.dist = off;  off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
+    L.dist = L.scb = L.snorms = L.skeys = L.thr = L.counts = L.cand = off;
+    if (plan.use) {
+        L.scb = off;    off = align_up(off + (cb_dtype == 1 ? 2 : 4) * (size_t)plan.S * d, 256);
+        L.snorms = off; off = align_up(off + sizeof(float) * (size_t)plan.S, 256);
+        L.skeys = off;  off = align_up(off + sizeof(float) * (size_t)L.row_block * plan.S, 256);
+        L.thr = off;    off = align_up(off + sizeof(float) * (size_t)L.row_block, 256);
+        L.counts = off; off = align_up(off + sizeof(int) * (size_t)L.row_block, 256);
+        L.cand = off;   off = align_up(off + sizeof(uint2) * (size_t)L.row_block * plan.cap, 256);
+    } else {
+        L.dist = off;   off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
+    }
     L.flags = off; off = align_up(off + sizeof(int) * (size_t)L.row_block, 256);
     L.slow = off;  off = align_up(off + sizeof(double) * (size_t)L.slow_wgs * V, 256);
     L.total = off;
     return L;
 }
 
-size_t knn_workspace_bytes(int V, int, int) { return knn_layout(V, ROW_BLOCK, SLOW_WGS).total; }
+// The largest layout of the given path that fits `bytes`: as many query rows per pass as the
+// rest holds (a multiple of 128, the contraction's tile).  row_block 0: nothing fits.
+static KnnLayout knn_layout_within(int V, int d, int cb_dtype, const FilterPlan& plan, int slow_wgs, size_t bytes) {
+    for (int rb = ROW_BLOCK; rb >= 128; rb -= 128) {
+        const KnnLayout L = knn_layout(V, d, cb_dtype, plan, rb, slow_wgs);
+        if (L.total <= bytes) return L;
+    }
+    KnnLayout none = knn_layout(V, d, cb_dtype, plan, 128, slow_wgs);
+    none.row_block = 0;
+    return none;
+}
+
+static const FilterPlan NO_FILTER = {false, 0, 0, 0, 0};
+
+// What lantern_build_knn asks of its caller: the layout of the path the shape takes.  A codebook
+// that turns out not to be 16-byte aligned falls back to whole key blocks of as many rows as
+// this size holds.
+size_t knn_workspace_bytes(int V, int d, int k, int cb_dtype) {
+    return knn_layout(V, d, cb_dtype, filter_plan(V, d, k, cb_dtype), ROW_BLOCK, SLOW_WGS).total;
+}
 
 // ---- scratch of the entry point that allocates nothing ----
 // Device memory that lives as long as the process, one copy per GPU.  Host code never uses the
@@ -61,21 +148,14 @@ size_t knn_workspace_bytes(int V, int, int) { return knn_layout(V, ROW_BLOCK, SL
 constexpr size_t STATIC_SCRATCH_BYTES = LANTERN_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
-// The largest layout that fits the static scratch: fewer exact-pass buffers, and as many query
-// rows per pass as the rest holds (a multiple of 128, the contraction's tile).  row_block 0: V is
-// beyond what the scratch can serve.
-static KnnLayout knn_layout_static(int V) {
-    const int slow_wgs = 32;
-    for (int rb = ROW_BLOCK; rb >= 128; rb -= 128) {
-        const KnnLayout L = knn_layout(V, rb, slow_wgs);
-        if (L.total <= STATIC_SCRATCH_BYTES) return L;
-    }
-    KnnLayout none = knn_layout(V, 128, slow_wgs);
-    none.row_block = 0;
-    return none;
+// The static scratch serves the whole-key-block path with fewer exact-pass buffers and as many
+// query rows per pass as fit.  row_block 0: V is beyond what the scratch can serve.
+constexpr int STATIC_SLOW_WGS = 32;
+static KnnLayout knn_layout_static(int V, int d, int cb_dtype) {
+    return knn_layout_within(V, d, cb_dtype, NO_FILTER, STATIC_SLOW_WGS, STATIC_SCRATCH_BYTES);
 }
 
-bool knn_static_fits(int V) { return knn_layout_static(V).row_block > 0; }
+bool knn_static_fits(int V) { return knn_layout_static(V, 4, 0).row_block > 0; }
 
 // Device address of the static scratch on the current device (looked up once per device).
 static hipError_t static_scratch_ptr(void** out) {
@@ -243,40 +323,31 @@ __global__ __launch_bounds__(NT) void knn_norm_max(const float* norms, int V, fl
 
 // Accumulator element r of lane l of a 32x32 MFMA tile is row 8*(r/4) + 4*(l/32) + r%4,
 // column l%32 (rows come from the A operand, columns from the B operand).
+__device__ __forceinline__ float approx_key(float g, float ni, float nj, int metric) {
+    return metric == 0 ? (ni + nj) - 2.f * g : -g * rsqrtf(ni * nj);
+}
+
+// Columns are the VB tokens of the column operand (the codebook itself, or a sample of it) with
+// norms nb; a row of dist holds VB keys.
 __device__ __forceinline__ void store_tile(const f32x16& acc, int i0, int j0, int lane, int r0, int rows,
-                                           int V, int metric, const float* norms, float* dist) {
+                                           int VB, int metric, const float* norms, const float* nb, float* dist) {
     const int j = j0 + (lane & 31);
-    if (j >= V) return;
-    const float nj = norms[j];
+    if (j >= VB) return;
+    const float nj = nb[j];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int i = i0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (i < r0 + rows) {
-            const float ni = norms[i];
-            const float g = acc[r];
-            const float key = metric == 0 ? (ni + nj) - 2.f * g : -g * rsqrtf(ni * nj);
-            dist[(int64_t)(i - r0) * V + j] = key;
-        }
+        if (i < r0 + rows) dist[(int64_t)(i - r0) * VB + j] = approx_key(acc[r], norms[i], nj, metric);
     }
 }
 
+// 64x64 block of G = A B^T for one wavefront: rows arow[0], arow[1] (32 each, one per lane & 31),
+// columns brow[0], brow[1]; acc[a][b] is the 32x32 tile of row strip a and column strip b.
+//
 // bf16 codebook, d a multiple of 8: v_mfma_f32_32x32x16_bf16, 16 coordinates per step
 // (lanes 0-31 carry coordinates k0..k0+7 of their row, lanes 32-63 k0+8..k0+15).
-__global__ __launch_bounds__(NT) void knn_dist_mfma_bf16(const uint16_t* cb, const float* norms, int V, int d,
-                                                         int r0, int rows, int metric, float* dist) {
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = threadIdx.x >> 6;
-    const int i_base = r0 + blockIdx.y * 128 + (wave >> 1) * 64;
-    const int j_base = blockIdx.x * 128 + (wave & 1) * 64;
-    if (i_base >= r0 + rows || j_base >= V) return;
-    const uint16_t* arow[2];
-    const uint16_t* brow[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
-        brow[t] = cb + (int64_t)min(j_base + t * 32 + (lane & 31), V - 1) * d;
-    }
-    f32x16 acc[2][2];
+__device__ __forceinline__ void contract_block(const uint16_t* const (&arow)[2], const uint16_t* const (&brow)[2],
+                                               int d, int lane, f32x16 (&acc)[2][2]) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -304,30 +375,12 @@ __global__ __launch_bounds__(NT) void knn_dist_mfma_bf16(const uint16_t* cb, con
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     __builtin_bit_cast(bf16x8, fa[a]), __builtin_bit_cast(bf16x8, fb[b]), acc[a][b], 0, 0, 0);
     }
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-            store_tile(acc[a][b], i_base + a * 32, j_base + b * 32, lane, r0, rows, V, metric, norms, dist);
 }
 
 // fp32 codebook, d a multiple of 4: v_mfma_f32_32x32x2_f32, 2 coordinates per step
 // (lanes 0-31 carry coordinate k, lanes 32-63 coordinate k+1); rows are read 8 floats at a time.
-__global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const float* norms, int V, int d,
-                                                        int r0, int rows, int metric, float* dist) {
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = threadIdx.x >> 6;
-    const int i_base = r0 + blockIdx.y * 128 + (wave >> 1) * 64;
-    const int j_base = blockIdx.x * 128 + (wave & 1) * 64;
-    if (i_base >= r0 + rows || j_base >= V) return;
-    const float* arow[2];
-    const float* brow[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
-        brow[t] = cb + (int64_t)min(j_base + t * 32 + (lane & 31), V - 1) * d;
-    }
-    f32x16 acc[2][2];
+__device__ __forceinline__ void contract_block(const float* const (&arow)[2], const float* const (&brow)[2], int d,
+                                               int lane, f32x16 (&acc)[2][2]) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -365,18 +418,233 @@ __global__ __launch_bounds__(NT) void knn_dist_mfma_f32(const float* cb, const f
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[a], vb[b], acc[a][b], 0, 0, 0);
         }
     }
+}
+
+// All keys of rows [r0, r0 + rows) of the codebook cb (V tokens, norms `norms`) against the VB
+// tokens of the column operand cbB (norms nb: the codebook itself, or a sample of it) into dist.
+// blockIdx = (column tile, row tile).
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_dist_mfma(const CT* cb, const CT* cbB, const float* norms, const float* nb,
+                                                    int V, int VB, int d, int r0, int rows, int metric, float* dist) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    const int i_base = r0 + blockIdx.y * 128 + (wave >> 1) * 64;
+    const int j_base = blockIdx.x * 128 + (wave & 1) * 64;
+    if (i_base >= r0 + rows || j_base >= VB) return;
+    const CT* arow[2];
+    const CT* brow[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
+        brow[t] = cbB + (int64_t)min(j_base + t * 32 + (lane & 31), VB - 1) * d;
+    }
+    f32x16 acc[2][2];
+    contract_block(arow, brow, d, lane, acc);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-            store_tile(acc[a][b], i_base + a * 32, j_base + b * 32, lane, r0, rows, V, metric, norms, dist);
+            store_tile(acc[a][b], i_base + a * 32, j_base + b * 32, lane, r0, rows, VB, metric, norms, nb, dist);
+}
+
+// Where the filtering contraction leaves a row block's candidates.
+struct FilterOut {
+    const float* thr;   // [rows] threshold of each row of the block
+    int* counts;        // [rows] keys at or below the threshold so far (may pass cap: the list is then cut)
+    uint2* cand;        // [rows, cap] (order-preserving key, token), in no particular order
+    int cap;
+};
+
+// LDS of the filtering contraction: per row of the workgroup's 128 its threshold, its norm and a
+// counter (pass 1: keys kept; pass 2: next free slot of the row's list).
+struct FilterShared {
+    float thr[128];
+    float norm[128];
+    int slots[128];
+};
+
+// One 32-row strip of a wavefront's 64x64 block in the filtering contraction, columns j0..j0+63
+// (tiles acc0, acc1); l0: the strip's first row within the workgroup's 128, i0 its token.  A key
+// stays if it is at or below its row's threshold (-inf for rows beyond the block) and is not the
+// row's own token.  Element r of lanes 0-31 belongs to one row and of lanes 32-63 to another, so
+// each half of the wavefront adds its number of kept keys to its row's counter with one LDS
+// atomic; WRITE: what the atomic returns is the first of the half's slots in the row's list, and
+// the keys are placed by their lane rank.
+template <bool WRITE, int METRIC>
+__device__ __forceinline__ void filter_strip(const f32x16& acc0, const f32x16& acc1, int l0, int i0, int j0, int lane,
+                                             int il_wg, int V, const float* norms, FilterShared& sh,
+                                             const FilterOut& f) {
+    const int half = lane >> 5;
+    const int hl = lane & 31;
+    const int ja = j0 + hl, jb = j0 + 32 + hl;
+    const bool va = ja < V, vb = jb < V;
+    const float na = norms[va ? ja : V - 1], nb = norms[vb ? jb : V - 1];
+    const uint32_t below = (1u << hl) - 1u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int l = l0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const int i = i0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float ni = sh.norm[l];
+        const float t = sh.thr[l];
+        const float ka = approx_key(acc0[r], ni, na, METRIC), kb = approx_key(acc1[r], ni, nb, METRIC);
+        const bool pa = va && ja != i && ka <= t;
+        const bool pb = vb && jb != i && kb <= t;
+        const uint64_t ma = __ballot(pa), mb = __ballot(pb);
+        const uint32_t ha = (uint32_t)(half ? ma >> 32 : ma), hb = (uint32_t)(half ? mb >> 32 : mb);
+        const int n = __popc(ha) + __popc(hb);
+        if (!WRITE) {
+            if (hl == 0 && n > 0) atomicAdd(&sh.slots[l], n);
+        } else {
+            int first = 0;
+            if (hl == 0 && n > 0) first = atomicAdd(&sh.slots[l], n);
+            const int b0 = __builtin_amdgcn_readlane(first, 0), b1 = __builtin_amdgcn_readlane(first, 32);
+            first = half ? b1 : b0;
+            uint2* list = f.cand + (int64_t)(il_wg + l) * f.cap;   // only dereferenced for rows of the block
+            const int sa = first + __popc(ha & below);
+            const int sb = first + __popc(ha) + __popc(hb & below);
+            if (pa && sa < f.cap) list[sa] = make_uint2(min(ord_key(ka), 0xFFFFFFFEu), (uint32_t)ja);
+            if (pb && sb < f.cap) list[sb] = make_uint2(min(ord_key(kb), 0xFFFFFFFEu), (uint32_t)jb);
+        }
+        if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // four rows in flight: keeps the register count down
+    }
+}
+
+// Filtering contraction: rows [r0, r0 + rows) against the whole codebook, keeping for every row
+// only the (key, token) pairs at or below the row's threshold.  A workgroup owns a tile of 128
+// rows by 128 tokens.  It contracts, counts the kept keys per row in LDS, reserves each row's
+// slots in its list with one atomic add per row, and then places the keys (the accumulators stay
+// in registers meanwhile).
+// Grid: one-dimensional, 8 * ceil(row tiles / 8) * column tiles workgroups, dealt so that all
+// column tiles of a row strip run on one XCD (workgroups go to the eight XCDs in turn) and a
+// row's list and counter stay in that XCD's L2.
+template <typename CT, int METRIC>
+__global__ __launch_bounds__(NT, 2) void knn_filter_mfma(const CT* cb, const float* norms, int V, int d, int r0,
+                                                         int rows, FilterOut f) {
+    __shared__ FilterShared sh;
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = tid >> 6;
+    const int nct = (V + 127) / 128, nrt = (rows + 127) / 128;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int ti = (q / nct) * 8 + xcd;
+    const int tj = q % nct;
+    if (ti >= nrt) return;   // the whole workgroup
+    const int il_wg = ti * 128;        // first row of the workgroup within the block
+    const int l_base = (wave >> 1) * 64;
+    const int i_base = r0 + il_wg + l_base;
+    const int j_base = tj * 128 + (wave & 1) * 64;
+    const bool live = j_base < V;      // rows beyond the block are kept out by their thresholds
+    if (tid < 128) {
+        const bool row_ok = il_wg + tid < rows;
+        sh.thr[tid] = row_ok ? f.thr[il_wg + tid] : -INFINITY;
+        sh.norm[tid] = row_ok ? norms[r0 + il_wg + tid] : 0.f;
+        sh.slots[tid] = 0;
+    }
+    __syncthreads();
+    f32x16 acc[2][2];
+    if (live) {
+        const CT* arow[2];
+        const CT* brow[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            arow[t] = cb + (int64_t)min(i_base + t * 32 + (lane & 31), V - 1) * d;
+            brow[t] = cb + (int64_t)min(j_base + t * 32 + (lane & 31), V - 1) * d;
+        }
+        contract_block(arow, brow, d, lane, acc);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            filter_strip<false, METRIC>(acc[a][0], acc[a][1], l_base + a * 32, i_base + a * 32, j_base, lane, il_wg, V,
+                                        norms, sh, f);
+    }
+    __syncthreads();
+    if (tid < 128) {
+        const int n = sh.slots[tid];   // n > 0 only for rows of the block
+        sh.slots[tid] = n > 0 ? atomicAdd(f.counts + il_wg + tid, n) : 0;
+    }
+    __syncthreads();
+    if (live) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            filter_strip<true, METRIC>(acc[a][0], acc[a][1], l_base + a * 32, i_base + a * 32, j_base, lane, il_wg, V,
+                                       norms, sh, f);
+    }
+}
+
+// ---- sampled thresholds ----
+// Token of sample slot s: one token out of each of S equal strata of the vocabulary, at a hashed
+// place inside the stratum.
+__host__ __device__ inline int sample_token(int s, int S, int V) {
+    const uint32_t h = ((uint32_t)s * 2654435761u) >> 16;   // 16 hashed bits
+    const int64_t j = ((int64_t)s * V + (((int64_t)h * V) >> 16)) / S;
+    return j < V ? (int)j : V - 1;
+}
+
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_gather_sample(const CT* cb, const float* norms, int V, int d, int S,
+                                                        CT* scb, float* snorms) {
+    const int64_t t = (int64_t)blockIdx.x * NT + threadIdx.x;
+    if (t >= (int64_t)S * d) return;
+    const int s = (int)(t / d), c = (int)(t % d);
+    const int j = sample_token(s, S, V);
+    scb[t] = cb[(int64_t)j * d + c];
+    if (c == 0) snorms[s] = norms[j];
+}
+
+// One wavefront per row: a value with between rank and rank + slack of the row's S <= 64 * NS keys
+// to the sample at or below it (bisection over the integer range of the keys, each step one
+// count) becomes the row's threshold; the row's list length is cleared.
+template <int NS>
+__global__ __launch_bounds__(NT) void knn_sample_rank(const float* skeys, int S, int rows, int rank, int slack,
+                                                      float* thr, int* counts) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int row = blockIdx.x * NW + (threadIdx.x >> 6);
+    if (row >= rows) return;   // whole wavefronts leave; no workgroup barrier below
+    const float* krow = skeys + (int64_t)row * S;
+    uint32_t keys[NS];
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        const int sidx = e * WAVE + lane;
+        keys[e] = sidx < S ? min(ord_key(krow[sidx]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+        if (sidx < S) { kmin = min(kmin, keys[e]); kmax = max(kmax, keys[e]); }
+    }
+    kmin = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMin>((int)(kmin ^ 0x80000000u), INT_MAX), 63) ^ 0x80000000u;
+    kmax = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMax>((int)(kmax ^ 0x80000000u), INT_MIN), 63) ^ 0x80000000u;
+    // count(lo) < rank <= count(hi)
+    int64_t lo = (int64_t)kmin - 1, hi = (int64_t)kmax;
+    while (hi - lo > 1) {
+        const int64_t mid64 = lo + ((hi - lo) >> 1);
+        const uint32_t mid = (uint32_t)mid64;
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < NS; ++e) c += keys[e] <= mid ? 1 : 0;
+        c = __builtin_amdgcn_readlane(wave_scan_i<OpSum>(c, 0), 63);
+        if (c < rank) {
+            lo = mid64;
+        } else {
+            hi = mid64;
+            if (c <= rank + slack) break;
+        }
+    }
+    if (lane == 0) {
+        thr[row] = ord_inv((uint32_t)hi);
+        counts[row] = 0;
+    }
 }
 
 // ---- stage 2: select, re-rank exactly, emit ----
 constexpr int SEL_MAXW = 8;   // wavefronts of the largest selection workgroup (512 threads)
+// Element e of the candidate arrays lives in slot lds_slot(e): bits 5 and 6 of e are folded into
+// the low five bits (bit 6 into bits 0, 2, 4, bit 5 into bits 1, 3).  The sort's threads read four
+// elements base + q h each; whichever power of two h is, the 32 lanes of an 8-byte access then
+// fall into 32 different bank pairs, where the plain layout has them collide four at a time for
+// small h.  The map is linear over exclusive-or and stays inside aligned blocks of 128 slots.
+__device__ __forceinline__ int lds_slot(int e) { return e ^ ((e & 64) ? 21 : 0) ^ ((e & 32) ? 10 : 0); }
+
 template <int CAP>
 struct SelectShared {
-    double key[CAP];
+    static_assert(CAP % 128 == 0, "lds_slot permutes blocks of 128 slots");
+    double key[CAP];   // both indexed by lds_slot
     int idx[CAP];
     unsigned red_u[2 * SEL_MAXW];
     int red_c[2][SEL_MAXW];   // per-wavefront counts of a counting pass, double-buffered
@@ -402,11 +670,17 @@ __device__ __forceinline__ void for_keys(int npt, F body) {
     }
 }
 
-template <typename CT, int NK, int CAP, int TNT>
-__global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
-                                                 const float* dist, float err_rel, float err_abs,
+//
+// LIST: the row's keys are not a row of the key block but its candidate list of the filtering
+// contraction, list.counts[row] pairs (key, token) with NK * TNT >= list.cap; every token not on
+// the list has an approximate key above every key on it, so the proof below reads the same.  A
+// list that was cut at its capacity, or is shorter than the selection wants, flags the row.
+template <typename CT, int NK, int CAP, int TNT, bool LIST>
+__global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(const CT* cb, int V, int d, int k, int metric, int r0,
+                                                 const float* dist, FilterOut list, float err_rel, float err_abs,
                                                  float err_norm, const float* norms, const float* nmax,
                                                  int32_t* out, int* flags) {
+    static_assert(!LIST || NK > 0, "a candidate list is held in registers");
     constexpr int TNW = TNT / WAVE;
     __shared__ SelectShared<CAP> sh;
     const int row = blockIdx.x;
@@ -414,7 +688,7 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = tid >> 6;
-    const float* drow = dist + (int64_t)row * V;
+    const float* drow = LIST ? nullptr : dist + (int64_t)row * V;
     int32_t* orow = out + (int64_t)i * k;
     const int need = k - 1;
     // rows of four-coordinate groups, each group one aligned load (16 bytes fp32, 8 bytes bf16)
@@ -433,10 +707,17 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
 
     constexpr int NKR = NK > 0 ? NK : 1;
     uint32_t keys[NKR];
+    uint32_t toks[LIST ? NKR : 1];
     const int npt = NK > 0 ? NK : (V + TNT - 1) / TNT;   // keys per thread
+    const int listed = LIST ? list.counts[row] : 0;
+    if (LIST && (listed > list.cap || listed < want)) {
+        if (tid == 0) flags[row] = 1;
+        return;
+    }
     // Token of element e of this thread.  Keys in registers: groups of four consecutive tokens per
     // thread, (e / 4) * TNT + tid being the group, so that a group is one 16-byte load; else e * TNT + tid.
     auto token_of = [&](int e) -> int {
+        if (LIST) return (int)toks[e];
         return NK > 0 ? (((e >> 2) * TNT + tid) << 2) + (e & 3) : e * TNT + tid;
     };
     // key of element e; 0xFFFFFFFF for the row's own token and padding
@@ -445,7 +726,17 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
         const int j = e * TNT + tid;
         return (j < V && j != i) ? min(ord_key(drow[j]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
     };
-    if (NK > 0) {
+    if (LIST) {
+        const uint2* lrow = list.cand + (int64_t)row * list.cap;
+#pragma unroll
+        for (int e = 0; e < NKR; ++e) {
+            const int slot = e * TNT + tid;
+            uint2 q = make_uint2(0xFFFFFFFFu, 0u);
+            if (slot < listed) q = lrow[slot];
+            keys[e] = q.x;
+            toks[e] = q.y;
+        }
+    } else if (NK > 0) {
         const bool row_vec = (V & 3) == 0;   // then every row of the key block starts 16-byte aligned
 #pragma unroll
         for (int g = 0; g < NKR / 4; ++g) {
@@ -490,7 +781,7 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
     // fits the LDS; the search stops as soon as that number fits the aimed-at power of two.
     int64_t lo = (int64_t)kmin - 1, hi = (int64_t)kmax;
     uint32_t thr_key = kmax;
-    int best = V - 1;            // count(kmax): every other token
+    int best = LIST ? listed : V - 1;   // count(kmax): every listed token, every other token
     for (int pass = 0; pass < 40 && best > fit && hi - lo > 1; ++pass) {
         const int64_t mid64 = lo + ((hi - lo) >> 1);
         const uint32_t mid = (uint32_t)mid64;
@@ -504,9 +795,10 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
         for (int w = 0; w < TNW; ++w) c += sh.red_c[pass & 1][w];
         if (c < want) {
             lo = mid64;
-        } else {
+        } else {   // counts grow with the threshold: c <= best = count(hi)
             hi = mid64;
-            if (c < best) { best = c; thr_key = mid; }
+            best = c;
+            thr_key = mid;
         }
     }
     if (best > CAP) {            // more (nearly) equal keys around the threshold than the LDS holds
@@ -544,44 +836,99 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
         return;
     }
     for_keys<NK>(npt, [&](int e) {
-        if (key_at(e) <= thr_key) sh.idx[slot++] = token_of(e);
+        if (key_at(e) <= thr_key) sh.idx[lds_slot(slot++)] = token_of(e);
     });
     __syncthreads();
     const float thr = ord_inv(thr_max);   // every discarded token has an approximate key above this
-    int P = 1;
+    int P = 4;   // the sort takes four elements per thread
     while (P < count) P <<= 1;
     for (int c = tid; c < P; c += TNT) {
         if (c < count) {
-            sh.key[c] = exact_key<CT>(cb, d, i, sh.idx[c], metric, vec4);
+            sh.key[lds_slot(c)] = exact_key<CT>(cb, d, i, sh.idx[lds_slot(c)], metric, vec4);
         } else {
-            sh.key[c] = INFINITY;
-            sh.idx[c] = INT_MAX;
+            sh.key[lds_slot(c)] = INFINITY;
+            sh.idx[lds_slot(c)] = INT_MAX;
         }
     }
-    // Bitonic sort ascending by (key, idx).  Pair t of a step works on elements l = 2t - (t mod stride)
-    // and l + stride; a wavefront takes pairs 64w .. 64w+63 (and the same 256, 512 ... further on), so
-    // for strides up to 64 it reads and writes only its own blocks of 128 elements: a step of stride
-    // below 64 follows one that stayed inside those blocks and needs the wavefront's own LDS order,
-    // not a workgroup barrier.
-    for (int size = 2; size <= P; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (stride >= WAVE || size == 2) {   // also the step after a wider one, and the very first
-                __syncthreads();
-            } else {
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-            for (int t = tid; t < (P >> 1); t += TNT) {
-                const int l = 2 * t - (t & (stride - 1));
-                const int r = l + stride;
-                const bool up = (l & size) == 0;
-                const double kl = sh.key[l], kr = sh.key[r];
-                const int il = sh.idx[l], ir = sh.idx[r];
-                const bool l_after_r = (kl > kr) || (kl == kr && il > ir);
-                if (l_after_r == up) {
-                    sh.key[l] = kr; sh.key[r] = kl;
-                    sh.idx[l] = ir; sh.idx[r] = il;
+    // Bitonic sort ascending by (key, idx), four elements per thread and round trip through the LDS:
+    // for two consecutive strides 2h and h of a merge, thread g takes the elements base, base + h,
+    // base + 2h, base + 3h (base: g with two zero bits put in at the strides' places) and does both
+    // steps on them in registers; a merge with an odd number of steps ends with a step of stride 1
+    // on four consecutive elements.  A wavefront's 64 threads cover 256 consecutive elements as
+    // long as 4h <= 256, and the same 256 from step to step, so such a step needs the wavefront's
+    // own LDS order, not a workgroup barrier, unless the step before it was a wider one.
+    auto exchange = [](double& ka, int& ia, double& kb, int& ib, bool up) {
+        const bool a_after_b = (ka > kb) || (ka == kb && ia > ib);
+        const bool sw = a_after_b == up;
+        const double k0 = sw ? kb : ka, k1 = sw ? ka : kb;
+        const int i0 = sw ? ib : ia, i1 = sw ? ia : ib;
+        ka = k0; kb = k1; ia = i0; ib = i1;
+    };
+    bool wide_before = true;   // no step yet: the keys were written by other wavefronts
+    auto order_lds = [&](bool wide) {
+        if (wide || wide_before) {
+            __syncthreads();
+        } else {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        wide_before = wide;
+    };
+    // Up to 256 elements the network runs a pair per thread and step instead (element l = 2t - t mod
+    // stride against l + stride): four per thread would leave all but half a wavefront idle, and the
+    // steps are then short enough for their number not to matter.  A wavefront's pairs stay inside
+    // its own blocks of 128 elements for strides up to 64.
+    if (P <= 256) {
+        for (int size = 2; size <= P; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                order_lds(stride > WAVE);
+                const int t = tid;
+                if (t < (P >> 1)) {
+                    const int l = 2 * t - (t & (stride - 1));
+                    const bool up = (l & size) == 0;
+                    const int pl = lds_slot(l), pr = pl ^ lds_slot(stride);
+                    const double kl = sh.key[pl], kr = sh.key[pr];
+                    const int il = sh.idx[pl], ir = sh.idx[pr];
+                    const bool l_after_r = (kl > kr) || (kl == kr && il > ir);
+                    if (l_after_r == up) {
+                        sh.key[pl] = kr; sh.key[pr] = kl;
+                        sh.idx[pl] = ir; sh.idx[pr] = il;
+                    }
                 }
+            }
+        }
+    }
+    for (int size = 2, m = 1; P > 256 && size <= P; size <<= 1, ++m) {
+        int J = m - 1;   // the widest stride still to do in this merge is 2^J
+        for (; J >= 1; J -= 2) {
+            order_lds(J + 1 > 8);
+            const int h = 1 << (J - 1);
+            for (int g = tid; g < (P >> 2); g += TNT) {
+                const int base = ((g >> (J - 1)) << (J + 1)) | (g & (h - 1));
+                const bool up = (base & size) == 0;
+                // base has zero bits where h and 2h have theirs, and lds_slot is linear
+                const int p0 = lds_slot(base), p1 = p0 ^ lds_slot(h), p2 = p0 ^ lds_slot(2 * h), p3 = p0 ^ lds_slot(3 * h);
+                double k0 = sh.key[p0], k1 = sh.key[p1], k2 = sh.key[p2], k3 = sh.key[p3];
+                int i0 = sh.idx[p0], i1 = sh.idx[p1], i2 = sh.idx[p2], i3 = sh.idx[p3];
+                exchange(k0, i0, k2, i2, up);
+                exchange(k1, i1, k3, i3, up);
+                exchange(k0, i0, k1, i1, up);
+                exchange(k2, i2, k3, i3, up);
+                sh.key[p0] = k0; sh.key[p1] = k1; sh.key[p2] = k2; sh.key[p3] = k3;
+                sh.idx[p0] = i0; sh.idx[p1] = i1; sh.idx[p2] = i2; sh.idx[p3] = i3;
+            }
+        }
+        if (J == 0) {
+            order_lds(false);
+            for (int g = tid; g < (P >> 2); g += TNT) {
+                const int base = 4 * g;
+                const int p0 = lds_slot(base), p1 = p0 ^ 1, p2 = p0 ^ 2, p3 = p0 ^ 3;
+                double k0 = sh.key[p0], k1 = sh.key[p1], k2 = sh.key[p2], k3 = sh.key[p3];
+                int i0 = sh.idx[p0], i1 = sh.idx[p1], i2 = sh.idx[p2], i3 = sh.idx[p3];
+                exchange(k0, i0, k1, i1, (base & size) == 0);
+                exchange(k2, i2, k3, i3, ((base + 2) & size) == 0);
+                sh.key[p0] = k0; sh.key[p1] = k1; sh.key[p2] = k2; sh.key[p3] = k3;
+                sh.idx[p0] = i0; sh.idx[p1] = i1; sh.idx[p2] = i2; sh.idx[p3] = i3;
             }
         }
     }
@@ -590,8 +937,8 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
     // approximate key above thr, hence an exact key above thr - err; the last
     // token taken must lie at or below that.
     bool ok = true;
-    if (count < V - 1) {
-        const double last = sh.key[need - 1];
+    if (LIST || count < V - 1) {
+        const double last = sh.key[lds_slot(need - 1)];
         double eabs = (double)err_abs;
         if (norms) eabs += (double)err_norm * ((double)norms[i] + (double)*nmax);
         const double num = (double)thr - eabs;
@@ -602,7 +949,7 @@ __global__ __launch_bounds__(TNT) void knn_select(const CT* cb, int V, int d, in
         if (tid == 0) flags[row] = 1;
         return;
     }
-    for (int s = tid; s < need; s += TNT) orow[1 + s] = sh.idx[s];
+    for (int s = tid; s < need; s += TNT) orow[1 + s] = sh.idx[lds_slot(s)];
 }
 
 // ---- stage 3: flagged rows, all V keys in fp64, rank by counting ----
@@ -639,6 +986,13 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
 __global__ void knn_clear_stats(int* stats) { stats[threadIdx.x] = 0; }
 __global__ void knn_copy_stats(const int* stats, int32_t* out) { *out = stats[0]; }
 
+template <int NS>
+static void launch_sample_rank(const float* skeys, const FilterPlan& plan, int rows, float* thr, int* counts,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL((knn_sample_rank<NS>), dim3((rows + NW - 1) / NW), dim3(NT), 0, stream, skeys, plan.S, rows,
+                       plan.rank, plan.slack, thr, counts);
+}
+
 template <typename CT>
 static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t stream) {
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
@@ -653,6 +1007,7 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
     // matrix-core path: rows 16-byte aligned and coordinates in whole vectors
     const bool aligned = (reinterpret_cast<uintptr_t>(a.codebook) & 15) == 0;
     const bool mfma = aligned && (sizeof(CT) == 2 ? (a.d % 8) == 0 : (a.d % 4) == 0) && a.V >= 32;
+    const FilterPlan& plan = L.filter;   // the caller lays the filtering path out only for an aligned codebook
     // one rounding is at most 2^-23 relative here (twice the fp32 unit, to cover a
     // contraction that truncates); a d-term sum takes d + 8 of them
     const float gamma = (float)(a.d + 8) * 1.1920929e-7f;
@@ -671,45 +1026,80 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
         err_abs = a.metric == 0 ? 0.f : 2.f * gamma;
         err_norm = 0.f;
     }
+    CT* scb = reinterpret_cast<CT*>(ws + L.scb);
+    float* snorms = reinterpret_cast<float*>(ws + L.snorms);
+    float* skeys = reinterpret_cast<float*>(ws + L.skeys);
+    FilterOut fo;
+    fo.thr = reinterpret_cast<float*>(ws + L.thr);
+    fo.counts = reinterpret_cast<int*>(ws + L.counts);
+    fo.cand = reinterpret_cast<uint2*>(ws + L.cand);
+    fo.cap = plan.cap;
+    const FilterOut no_list = {nullptr, nullptr, nullptr, 0};
+    if (plan.use) {
+        if (!mfma) return hipErrorInvalidValue;
+        const int64_t elems = (int64_t)plan.S * a.d;
+        hipLaunchKernelGGL((knn_gather_sample<CT>), dim3((unsigned)((elems + NT - 1) / NT)), dim3(NT), 0, stream, cb,
+                           norms, a.V, a.d, plan.S, scb, snorms);
+    }
+    // all keys of rows [r0, r0 + rows) against the tokens of cbB
+    auto contract = [&](const CT* cbB, const float* nb, int VB, int r0, int rows, float* keys) {
+        hipLaunchKernelGGL((knn_dist_mfma<CT>), dim3((VB + 127) / 128, (rows + 127) / 128), dim3(NT), 0, stream, cb,
+                           cbB, norms, nb, a.V, VB, a.d, r0, rows, a.metric, keys);
+    };
+    auto filter = [&](int r0, int rows) {
+        const int nct = (a.V + 127) / 128, nrt = (rows + 127) / 128;
+        const dim3 grid((unsigned)((nrt + 7) / 8 * 8 * nct));
+        if (a.metric == 0)
+            hipLaunchKernelGGL((knn_filter_mfma<CT, 0>), grid, dim3(NT), 0, stream, cb, norms, a.V, a.d, r0, rows, fo);
+        else
+            hipLaunchKernelGGL((knn_filter_mfma<CT, 1>), grid, dim3(NT), 0, stream, cb, norms, a.V, a.d, r0, rows, fo);
+    };
     for (int r0 = 0; r0 < a.V; r0 += L.row_block) {
         const int rows = (a.V - r0) < L.row_block ? (a.V - r0) : L.row_block;
-        if (mfma) {
-            const dim3 grid((a.V + 127) / 128, (rows + 127) / 128);
-            if (sizeof(CT) == 2)
-                hipLaunchKernelGGL(knn_dist_mfma_bf16, grid, dim3(NT), 0, stream,
-                                   reinterpret_cast<const uint16_t*>(cb), norms, a.V, a.d, r0, rows, a.metric, dist);
-            else
-                hipLaunchKernelGGL(knn_dist_mfma_f32, grid, dim3(NT), 0, stream,
-                                   reinterpret_cast<const float*>(cb), norms, a.V, a.d, r0, rows, a.metric, dist);
-        } else {
-            hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
-                               cb, a.V, a.d, r0, a.metric, dist);
-        }
         const float* nsel = mfma && a.metric == 0 ? norms : nullptr;
         // candidate capacity: the smallest of 256 / 1024 / 2048 / 4096 slots that holds k-1+pad.  The
         // selection is bound by the latency of its many short phases, so its throughput is the number
         // of workgroups a compute unit holds at once, and that number is set by this LDS footprint
         // (12 bytes a slot).
         const int want_slots = (a.k - 1) + 8 + (a.k - 1) / 128;
-#define LANTERN_LAUNCH_SELECT(NKV, CAPV, TNTV)                                                              \
-        hipLaunchKernelGGL((knn_select<CT, NKV, CAPV, TNTV>), dim3(rows), dim3(TNTV), 0, stream, cb, a.V, a.d, \
-                           a.k, a.metric, r0, dist, err_rel, err_abs, err_norm, nsel, nmax, a.out, flags)
+#define LANTERN_LAUNCH_SELECT(NKV, CAPV, TNTV, LISTV)                                                       \
+        hipLaunchKernelGGL((knn_select<CT, NKV, CAPV, TNTV, LISTV>), dim3(rows), dim3(TNTV), 0, stream, cb, \
+                           a.V, a.d, a.k, a.metric, r0, dist, LISTV ? fo : no_list, err_rel, err_abs,       \
+                           err_norm, nsel, nmax, a.out, flags)
+        if (plan.use) {
+            // thresholds from the sample, then the contraction that keeps what lies below them
+            contract(scb, snorms, plan.S, r0, rows, skeys);
+            if (plan.S <= 8 * WAVE) launch_sample_rank<8>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
+            else if (plan.S <= 16 * WAVE) launch_sample_rank<16>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
+            else if (plan.S <= 32 * WAVE) launch_sample_rank<32>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
+            else launch_sample_rank<64>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
+            filter(r0, rows);
+            // a list of cap slots on 256 threads: cap / 256 pairs per thread; 256 < want_slots <= 1024
+            if (plan.cap <= 8 * NT) LANTERN_LAUNCH_SELECT(8, 1024, NT, true);
+            else if (plan.cap <= 12 * NT) LANTERN_LAUNCH_SELECT(12, 1024, NT, true);
+            else LANTERN_LAUNCH_SELECT(16, 1024, NT, true);
+        } else {
+            if (mfma) contract(cb, norms, a.V, r0, rows, dist);
+            else
+                hipLaunchKernelGGL((knn_dist_direct<CT>), dim3((a.V + NT - 1) / NT, rows), dim3(NT), 0, stream,
+                                   cb, a.V, a.d, r0, a.metric, dist);
 #define LANTERN_LAUNCH_SELECT_NK(NKV, TNTV)                                                                 \
-        do {                                                                                                \
-            if (want_slots <= 256) LANTERN_LAUNCH_SELECT(NKV, 256, TNTV);                                   \
-            else if (want_slots <= 1024) LANTERN_LAUNCH_SELECT(NKV, 1024, TNTV);                            \
-            else if (want_slots <= 2048) LANTERN_LAUNCH_SELECT(NKV, 2048, TNTV);                            \
-            else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP, TNTV);                                                \
-        } while (0)
-        // threads per row and keys per thread: up to 64 keys per thread in registers; vocabularies
-        // beyond 64 x 256 tokens take 512 threads per row (32 keys per thread on 512 threads measured
-        // the same as 64 on 256 at V = 16384); beyond 64 x 512 the keys are re-read in every pass
-        if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8, NT);
-        else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32, NT);
-        else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64, NT);
-        else if (a.V <= 64 * 512) LANTERN_LAUNCH_SELECT_NK(64, 512);
-        else LANTERN_LAUNCH_SELECT_NK(0, NT);
+            do {                                                                                            \
+                if (want_slots <= 256) LANTERN_LAUNCH_SELECT(NKV, 256, TNTV, false);                        \
+                else if (want_slots <= 1024) LANTERN_LAUNCH_SELECT(NKV, 1024, TNTV, false);                 \
+                else if (want_slots <= 2048) LANTERN_LAUNCH_SELECT(NKV, 2048, TNTV, false);                 \
+                else LANTERN_LAUNCH_SELECT(NKV, CAND_CAP, TNTV, false);                                     \
+            } while (0)
+            // threads per row and keys per thread: up to 64 keys per thread in registers; vocabularies
+            // beyond 64 x 256 tokens take 512 threads per row (32 keys per thread on 512 threads measured
+            // the same as 64 on 256 at V = 16384); beyond 64 x 512 the keys are re-read in every pass
+            if (a.V <= 8 * NT) LANTERN_LAUNCH_SELECT_NK(8, NT);
+            else if (a.V <= 32 * NT) LANTERN_LAUNCH_SELECT_NK(32, NT);
+            else if (a.V <= 64 * NT) LANTERN_LAUNCH_SELECT_NK(64, NT);
+            else if (a.V <= 64 * 512) LANTERN_LAUNCH_SELECT_NK(64, 512);
+            else LANTERN_LAUNCH_SELECT_NK(0, NT);
 #undef LANTERN_LAUNCH_SELECT_NK
+        }
 #undef LANTERN_LAUNCH_SELECT
         const int wgs = rows < L.slow_wgs ? rows : L.slow_wgs;
         hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
@@ -721,7 +1111,14 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
 }
 
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream) {
-    const KnnLayout L = knn_layout(a.V, ROW_BLOCK, SLOW_WGS);
+    // The workspace has the size of the shape's own layout.  A codebook that is not 16-byte aligned
+    // cannot take the filtering path: it gets whole key blocks of as many rows as that size holds.
+    FilterPlan plan = filter_plan(a.V, a.d, a.k, a.cb_dtype);
+    KnnLayout L = knn_layout(a.V, a.d, a.cb_dtype, plan, ROW_BLOCK, SLOW_WGS);
+    if (plan.use && (reinterpret_cast<uintptr_t>(a.codebook) & 15) != 0) {
+        L = knn_layout_within(a.V, a.d, a.cb_dtype, NO_FILTER, SLOW_WGS, L.total);
+        if (L.row_block == 0) return hipErrorInvalidValue;
+    }
     if (a.cb_dtype == 0) return build_typed<float>(a, L, stream);
     return build_typed<uint16_t>(a, L, stream);
 }
@@ -729,7 +1126,7 @@ hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream) {
 // The same build with the library's static scratch as workspace; a.workspace is ignored.
 // exact_rows: device int32 that receives the number of rows ranked by the all-pairs pass, or null.
 hipError_t launch_build_knn_static(const KnnArgs& a_in, int32_t* exact_rows, hipStream_t stream) {
-    const KnnLayout L = knn_layout_static(a_in.V);
+    const KnnLayout L = knn_layout_static(a_in.V, a_in.d, a_in.cb_dtype);
     if (L.row_block == 0) return hipErrorInvalidValue;   // the host entry has checked this
     KnnArgs a = a_in;
     hipError_t e = static_scratch_ptr(&a.workspace);

@@ -18,7 +18,7 @@ struct KnnArgs {
     void* workspace;
 };
 
-size_t knn_workspace_bytes(int V, int d, int k);
+size_t knn_workspace_bytes(int V, int d, int k, int cb_dtype);
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream);
 
 // The build on the library's static device scratch (no workspace from the caller, nothing
