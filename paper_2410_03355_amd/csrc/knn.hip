@@ -605,8 +605,13 @@ __global__ __launch_bounds__(NT) void knn_sample_rank(const float* skeys, int S,
 #pragma unroll
     for (int e = 0; e < NS; ++e) {
         const int sidx = e * WAVE + lane;
-        keys[e] = sidx < S ? min(ord_key(krow[sidx]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
-        if (sidx < S) { kmin = min(kmin, keys[e]); kmax = max(kmax, keys[e]); }
+        // no branch and no select on the loaded value, so that all loads are in flight together:
+        // beyond the sample the index is clamped and the key forced to all ones by a mask
+        const uint32_t beyond = (uint32_t)((S - 1 - sidx) >> 31);
+        const float v = krow[min(sidx, S - 1)];
+        keys[e] = min(ord_key(v), 0xFFFFFFFEu) | beyond;
+        kmin = min(kmin, keys[e]);
+        kmax = max(kmax, keys[e] & ~beyond);
     }
     kmin = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMin>((int)(kmin ^ 0x80000000u), INT_MAX), 63) ^ 0x80000000u;
     kmax = (uint32_t)__builtin_amdgcn_readlane(wave_scan_i<OpMax>((int)(kmax ^ 0x80000000u), INT_MIN), 63) ^ 0x80000000u;
@@ -731,28 +736,39 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
 #pragma unroll
         for (int e = 0; e < NKR; ++e) {
             const int slot = e * TNT + tid;
-            uint2 q = make_uint2(0xFFFFFFFFu, 0u);
-            if (slot < listed) q = lrow[slot];
-            keys[e] = q.x;
+            const uint2 q = lrow[slot < list.cap ? slot : list.cap - 1];   // unconditional: all loads in flight together
+            keys[e] = slot < listed ? q.x : 0xFFFFFFFFu;
             toks[e] = q.y;
         }
     } else if (NK > 0) {
-        const bool row_vec = (V & 3) == 0;   // then every row of the key block starts 16-byte aligned
+        if ((V & 3) == 0) {   // every row of the key block starts 16-byte aligned and ends with a whole group
+            // No branch and no select on a loaded value, so that all the row's loads are in flight
+            // together: a group beyond the row re-reads the last one, and its keys, like the row's own
+            // token's, are forced to all ones by a mask.
+            float4 q[NKR / 4 > 0 ? NKR / 4 : 1];
 #pragma unroll
-        for (int g = 0; g < NKR / 4; ++g) {
-            const int j0 = (g * TNT + tid) << 2;
-            float f[4];
-            if (row_vec && j0 + 3 < V) {
-                const float4 q = *reinterpret_cast<const float4*>(drow + j0);
-                f[0] = q.x; f[1] = q.y; f[2] = q.z; f[3] = q.w;
-            } else {
+            for (int g = 0; g < NKR / 4; ++g)
+                q[g] = *reinterpret_cast<const float4*>(drow + min((g * TNT + tid) << 2, V - 4));
 #pragma unroll
-                for (int q = 0; q < 4; ++q) f[q] = (j0 + q < V) ? drow[j0 + q] : 0.f;
+            for (int g = 0; g < NKR / 4; ++g) {
+                const int j0 = (g * TNT + tid) << 2;
+                const float f[4] = {q[g].x, q[g].y, q[g].z, q[g].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = j0 + e;
+                    const uint32_t out = (uint32_t)((V - 1 - j) >> 31) | (uint32_t)(-(int)(j == i));
+                    keys[4 * g + e] = min(ord_key(f[e]), 0xFFFFFFFEu) | out;
+                }
             }
+        } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int j = j0 + q;
-                keys[4 * g + q] = (j < V && j != i) ? min(ord_key(f[q]), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+            for (int g = 0; g < NKR / 4; ++g) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = ((g * TNT + tid) << 2) + e;
+                    const float f = j < V ? drow[j] : 0.f;
+                    keys[4 * g + e] = (j < V && j != i) ? min(ord_key(f), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+                }
             }
         }
     }
