@@ -87,6 +87,50 @@ def test_large_vocabularies(oracle_mod, lantern_gpu, V, d, k, dtype):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("V,d,k,dtype,metric", [
+    (8192, 256, 300, torch.bfloat16, "l2"),      # matrix cores on bf16 codes, 16 steps of 16 coordinates
+    (5000, 12, 260, torch.float32, "l2"),        # ragged last tile of rows and of columns, smallest k class
+    (4096, 8, 1009, torch.float32, "cosine"),    # smallest vocabulary and largest k of the path
+    (40000, 8, 400, torch.float32, "l2"),        # beyond what the whole-row selection holds in registers
+])
+def test_sampled_threshold_path(oracle_mod, lantern_gpu, V, d, k, dtype, metric):
+    """Shapes that take the sampled thresholds and the filtering contraction (4096 tokens or more,
+    k - 1 + pad between 257 and 1024): whole tables compared, and no row may have needed the
+    all-pairs pass (every list came out between what the selection wants and its capacity)."""
+    g = torch.Generator().manual_seed(V * 7 + k)
+    cb = torch.randn(V, d, generator=g).to(dtype)
+    if metric == "cosine":
+        cb = (cb * (torch.rand(V, 1, generator=g) * 3 + 0.25)).to(dtype).contiguous()
+    got = _gpu_table(lantern_gpu, cb, k, metric=metric, max_exact_rows=0)
+    _check_structure(got, V, k)
+    want = oracle_mod.build_knn(cb.float().numpy(), k, metric=metric, threads=16)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_sampled_threshold_path_falls_back(oracle_mod, lantern_gpu):
+    """The same shapes when the sample misleads or the lists overflow.  (a) 64 distinct codes, each
+    64 times: whole shells of equal keys sit at every threshold, lists come out too long or too
+    short, and the rows must be ranked by the all-pairs pass, not guessed.  (b) A codebook whose
+    first byte is not 16-byte aligned cannot use the matrix cores: it takes whole key blocks in a
+    workspace that was sized for the lists."""
+    rng = np.random.default_rng(11)
+    base = rng.standard_normal((64, 8)).astype(np.float32)
+    dup = np.repeat(base, 64, axis=0)[rng.permutation(4096)]
+    got, exact_rows = lantern_gpu.build_knn(torch.from_numpy(dup).cuda(), 300, return_stats=True)
+    torch.cuda.synchronize()
+    assert int(exact_rows.item()) > 0
+    np.testing.assert_array_equal(got.cpu().numpy(), oracle_mod.build_knn(dup, 300, threads=16))
+
+    g = torch.Generator().manual_seed(12)
+    V, d, k = 6000, 8, 300
+    holder = torch.randn(V * d + 1, generator=g).cuda()
+    cb = holder[1:].view(V, d)                       # 4 bytes past an aligned address
+    assert cb.data_ptr() % 16 != 0 and cb.is_contiguous()
+    got = lantern_gpu.build_knn(cb, k)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got.cpu().numpy(), oracle_mod.build_knn(cb.cpu().numpy(), k, threads=16))
+
+
 def test_exact_ties_and_duplicates(oracle_mod, lantern_gpu):
     """Integer lattice (many exactly equal distances) and repeated codes: the
     lower index wins and the token itself stays in slot 0."""
