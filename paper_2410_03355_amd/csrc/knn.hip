@@ -736,7 +736,7 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
 #pragma unroll
         for (int e = 0; e < NKR; ++e) {
             const int slot = e * TNT + tid;
-            const uint2 q = lrow[slot < list.cap ? slot : list.cap - 1];   // unconditional: all loads in flight together
+            const uint2 q = lrow[slot < listed ? slot : listed - 1];   // no branch: all loads in flight together (listed >= 1)
             keys[e] = slot < listed ? q.x : 0xFFFFFFFFu;
             toks[e] = q.y;
         }
