@@ -114,7 +114,7 @@ static KnnLayout knn_layout(int V, int d, int cb_dtype, const FilterPlan& plan, 
     } else {
         L.dist = off;   off = align_up(off + sizeof(float) * (size_t)L.row_block * V, 256);
     }
-    L.flags = off; off = align_up(off + sizeof(int) * (size_t)L.row_block, 256);
+    L.flags = off; off = align_up(off + sizeof(int) * (size_t)V, 256);   // one word per row of the table
     L.slow = off;  off = align_up(off + sizeof(double) * (size_t)L.slow_wgs * V, 256);
     L.total = off;
     return L;
@@ -970,16 +970,19 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
 
 // ---- stage 3: flagged rows, all V keys in fp64, rank by counting ----
 template <typename CT>
-__global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d, int k, int metric, int r0,
-                                                     int rows, const int* flags, double* bufs,
-                                                     int32_t* out, int* stats) {
+__global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d, int k, int metric,
+                                                     const int* flags, double* bufs, int32_t* out, int* stats) {
     const int tid = threadIdx.x;
     double* buf = bufs + (int64_t)blockIdx.x * V;
     const int need = k - 1;
-    for (int row = blockIdx.x; row < rows; row += gridDim.x) {
-        if (!flags[row]) continue;  // uniform
+    // the workgroup's rows are blockIdx.x, blockIdx.x + gridDim.x, ...: all their flags are looked at
+    // at once first, and a workgroup with none set is done
+    int any = 0;
+    for (int row = blockIdx.x + tid * gridDim.x; row < V; row += NT * gridDim.x) any |= flags[row];
+    if (!__syncthreads_or(any)) return;
+    for (int i = blockIdx.x; i < V; i += gridDim.x) {
+        if (!flags[i]) continue;  // uniform
         if (tid == 0) atomicAdd(stats, 1);
-        const int i = r0 + row;
         __syncthreads();
         for (int j = tid; j < V; j += NT)
             buf[j] = (j == i) ? INFINITY : exact_key<CT>(cb, d, i, j, metric, false);
@@ -1081,7 +1084,7 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
 #define LANTERN_LAUNCH_SELECT(NKV, CAPV, TNTV, LISTV)                                                       \
         hipLaunchKernelGGL((knn_select<CT, NKV, CAPV, TNTV, LISTV>), dim3(rows), dim3(TNTV), 0, stream, cb, \
                            a.V, a.d, a.k, a.metric, r0, dist, LISTV ? fo : no_list, err_rel, err_abs,       \
-                           err_norm, nsel, nmax, a.out, flags)
+                           err_norm, nsel, nmax, a.out, flags + r0)
         if (plan.use) {
             // thresholds from the sample, then the contraction that keeps what lies below them
             contract(scb, snorms, plan.S, r0, rows, skeys);
@@ -1117,13 +1120,14 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
 #undef LANTERN_LAUNCH_SELECT_NK
         }
 #undef LANTERN_LAUNCH_SELECT
-        const int wgs = rows < L.slow_wgs ? rows : L.slow_wgs;
-        hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k,
-                           a.metric, r0, rows, flags, slow, a.out, stats);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    // flagged rows of the whole table
+    const int wgs = a.V < L.slow_wgs ? a.V : L.slow_wgs;
+    hipLaunchKernelGGL((knn_exact_rows<CT>), dim3(wgs), dim3(NT), 0, stream, cb, a.V, a.d, a.k, a.metric, flags,
+                       slow, a.out, stats);
+    return hipGetLastError();
 }
 
 hipError_t launch_build_knn(const KnnArgs& a, hipStream_t stream) {
