@@ -35,28 +35,31 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # (FETCH_SIZE scaled by the factor a plain 256 MiB copy gives in the same run).  Counters cannot be
 # read from inside this process, so the figure is a record of that run: it is reported only while the
 # library still has the version it was measured at, and with the file it comes from.
-_FETCH_SCALE = 262144.0 / 131097.1   # what FETCH_SIZE read for a 256 MiB copy in the same run
+_FETCH_SCALE = 262144.0 / 131091.2   # what FETCH_SIZE read for a 256 MiB copy in the same run
 MEASURED_TRAFFIC = {
     # (workload, variant, mode): (bytes per launch, library version, source)
-    ("stress", "plain", "sample"): ((130995.4 * _FETCH_SCALE + 240.1) * 1024, 221,
-                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 221)"),
-    ("stress", "reject", "sample"): ((167759.8 * _FETCH_SCALE + 13891.4) * 1024, 221,
-                                     "profiles/verify_fast_stress_plain.md (reject mix; version 221)"),
-    ("wide_latent", "plain", "sample"): ((124427.7 * _FETCH_SCALE + 240.6) * 1024, 221,
-                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 221)"),
-    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 221,
-                                    "profiles/greedy_fast_stress_plain.md (version 221)"),
+    ("stress", "plain", "sample"): ((130997.7 * _FETCH_SCALE + 240.2) * 1024, 222,
+                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 222)"),
+    ("stress", "reject", "sample"): ((167877.9 * _FETCH_SCALE + 13905.8) * 1024, 222,
+                                     "profiles/verify_fast_stress_plain.md (reject mix; version 222)"),
+    ("wide_latent", "plain", "sample"): ((124430.2 * _FETCH_SCALE + 240.3) * 1024, 222,
+                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 222)"),
+    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 222,
+                                    "profiles/greedy_fast_stress_plain.md (version 222)"),
 }
 
 
 # Per-kernel split of a table build, from the kernel trace summarised under profiles/ (events inside this
-# process only bracket the whole build): us per block of 2048 query rows, reported under the same rule.
+# process only bracket the whole build): us per build, reported under the same rule.  The stress table takes
+# the path with sampled thresholds and a filtering contraction (its keys to a sample of 2048 tokens are
+# contracted first: 2 V S d further flop); the wide-latent table (k = 100) the path with whole key blocks.
 MEASURED_KNN_SPLIT = {
-    # workload: ({kernel: us per block}, blocks per build, library version, source)
-    "stress": ({"contraction": 52.3, "selection": 123.5, "exact_check": 6.2}, 8, 221,
-               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 221)"),
-    "wide_latent": ({"contraction": 52.7, "selection": 57.1, "exact_check": 6.0}, 4, 221,
-                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 221)"),
+    # workload: ({kernel: us per build}, extra contraction flop, library version, source)
+    "stress": ({"sample_contraction": 50.2, "thresholds": 36.3, "filter_contraction": 305.4, "selection": 410.9,
+                "exact_check": 4.1}, 2.0 * 16384 * 2048 * 8, 222,
+               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
+    "wide_latent": ({"contraction": 199.5, "selection": 177.6, "exact_check": 4.1}, 0.0, 222,
+                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
 }
 
 
@@ -233,12 +236,14 @@ def knn_report(cfg, build_ms, version=None):
            "algorithmic_bytes": io_bytes, "hbm_frac": io_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     split = MEASURED_KNN_SPLIT.get(cfg.name)
     if split is not None and version == split[2]:
-        per_block, blocks = split[0], split[1]
-        rep["contraction_ms"] = per_block["contraction"] * blocks * 1e-3
-        rep["select_ms"] = per_block["selection"] * blocks * 1e-3
-        rep["exact_check_ms"] = per_block["exact_check"] * blocks * 1e-3
-        # the contraction alone against the matrix-core peak of its type
-        rep["contraction_mfma_frac"] = flop / (rep["contraction_ms"] * 1e-3) / 1e12 / peak
+        us = split[0]
+        rep["contraction_ms"] = sum(v for n, v in us.items() if n.endswith("contraction")) * 1e-3
+        if "thresholds" in us:
+            rep["threshold_ms"] = us["thresholds"] * 1e-3
+        rep["select_ms"] = us["selection"] * 1e-3
+        rep["exact_check_ms"] = us["exact_check"] * 1e-3
+        # the contractions alone against the matrix-core peak of their type
+        rep["contraction_mfma_frac"] = (flop + split[1]) / (rep["contraction_ms"] * 1e-3) / 1e12 / peak
         rep["split_source"] = split[3]
     return rep
 

@@ -91,8 +91,12 @@ typedef enum {
 
 /*
  * Bytes of device workspace lantern_build_knn needs for this problem, or 0 if
- * the arguments are invalid.  The workspace holds approximate distances for a
- * block of query rows plus candidate lists; its contents are scratch.
+ * the arguments are invalid.  The workspace holds, for a block of query rows,
+ * either candidate lists and the rows' approximate distances to a sample of
+ * the codebook, or their approximate distances to every token (which of the
+ * two depends on V and k alone); its contents are scratch.  Sized for few,
+ * large launches: up to about 850 MiB (V = 65536, k = 1000), 528 MiB for
+ * V = 16384, k = 1000.
  */
 size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, int k);
 
@@ -114,9 +118,11 @@ size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, i
  *              therefore ranked from all V exact distances (slow; zero for
  *              codebooks without massive exact ties).
  *
- * An approximate distance from a matrix-core contraction only pre-selects
- * candidates; the order written is always the fp64 one, so the result does
- * not depend on the contraction's rounding.
+ * An approximate distance from a matrix-core contraction, and for larger k a
+ * per-row threshold estimated from a sample of the codebook, only pre-select
+ * candidates; the order written is always the fp64 one, and a row whose
+ * pre-selection cannot be proven complete is ranked from all V distances, so
+ * the result depends neither on the contraction's rounding nor on the sample.
  * Errors: E_NULL, E_SHAPE (k>V, V<1, d<1, k<1), E_DTYPE, E_WORKSPACE, E_DEVICE.
  */
 int lantern_build_knn(const void* codebook, lantern_dtype cb_dtype, int V, int d, int k,
