@@ -52,13 +52,14 @@ MEASURED_TRAFFIC = {
 # Per-kernel split of a table build, from the kernel trace summarised under profiles/ (events inside this
 # process only bracket the whole build): us per build, reported under the same rule.  The stress table takes
 # the path with sampled thresholds and a filtering contraction (its keys to a sample of 2048 tokens are
-# contracted first: 2 V S d further flop); the wide-latent table (k = 100) the path with whole key blocks.
+# contracted first: 2 V S d further flop), and so does the wide-latent table (a sample of 1024 tokens).
 MEASURED_KNN_SPLIT = {
     # workload: ({kernel: us per build}, extra contraction flop, library version, source)
-    "stress": ({"sample_contraction": 50.2, "thresholds": 36.3, "filter_contraction": 305.4, "selection": 410.9,
-                "exact_check": 4.1}, 2.0 * 16384 * 2048 * 8, 222,
+    "stress": ({"sample_contraction": 50.7, "thresholds": 36.1, "filter_contraction": 299.5, "selection": 402.7,
+                "exact_check": 4.0}, 2.0 * 16384 * 2048 * 8, 222,
                "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
-    "wide_latent": ({"contraction": 199.5, "selection": 177.6, "exact_check": 4.1}, 0.0, 222,
+    "wide_latent": ({"sample_contraction": 29.5, "thresholds": 12.7, "filter_contraction": 154.1, "selection": 129.5,
+                     "exact_check": 4.0}, 2.0 * 8192 * 1024 * 256, 222,
                     "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
 }
 

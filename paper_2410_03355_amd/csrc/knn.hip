@@ -13,7 +13,7 @@
 //   3. flagged rows: fp64 keys for all V tokens and ranking by counting.
 // The written order is therefore always the fp64 one.
 //
-// Vocabularies of 4096 tokens and more (aligned codebooks, k from about 250 to about 1000) never form the
+// Vocabularies of 4096 tokens and more (aligned codebooks, k from about 60 to about 1000) never form the
 // whole key block: a row's threshold is first estimated from the keys to a stratified sample of
 // one token in eight, the contraction then runs with an epilogue that appends only the
 // (key, token) pairs at or below the row's threshold to a short per-row list, and step 2 works
@@ -61,7 +61,7 @@ struct FilterPlan {
     int S;      // sampled tokens, a multiple of 64, at most 4096
     int rank;   // the threshold has between rank and rank + slack of a row's S sample keys at or below it
     int slack;
-    int cap;    // slots of a row's candidate list: 2048, 3072 or 4096
+    int cap;    // slots of a row's candidate list: 1024, 2048, 3072 or 4096
 };
 
 static FilterPlan filter_plan(int V, int d, int k, int cb_dtype) {
@@ -69,8 +69,8 @@ static FilterPlan filter_plan(int V, int d, int k, int cb_dtype) {
     const bool vec = cb_dtype == 1 ? (d % 8) == 0 : (d % 4) == 0;   // what the matrix-core kernels need
     const int need = k - 1;
     const int want = need + 8 + need / 128;
-    // 256 candidates or fewer: the selection is short next to the contraction, and sampling does not pay
-    if (!vec || V < 4096 || want <= 256 || want > 1024) return P;
+    // 64 candidates or fewer: the lists would be several times longer than what the selection wants
+    if (!vec || V < 4096 || want <= 64 || want > 1024) return P;
     int S = V / 8;
     if (S > 4096) S = 4096;
     S = S / 64 * 64;
@@ -1104,8 +1104,11 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
             else if (plan.S <= 32 * WAVE) launch_sample_rank<32>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
             else launch_sample_rank<64>(skeys, plan, rows, const_cast<float*>(fo.thr), fo.counts, stream);
             filter(r0, rows);
-            // a list of cap slots on 256 threads: cap / 256 pairs per thread; 256 < want_slots <= 1024
-            if (plan.cap <= 8 * NT) LANTERN_LAUNCH_SELECT(8, 1024, NT, true);
+            // a list of cap slots on 256 threads: cap / 256 pairs per thread; 64 < want_slots <= 1024
+            if (want_slots <= 256) {
+                if (plan.cap <= 4 * NT) LANTERN_LAUNCH_SELECT(4, 256, NT, true);
+                else LANTERN_LAUNCH_SELECT(8, 256, NT, true);
+            } else if (plan.cap <= 8 * NT) LANTERN_LAUNCH_SELECT(8, 1024, NT, true);
             else if (plan.cap <= 12 * NT) LANTERN_LAUNCH_SELECT(12, 1024, NT, true);
             else LANTERN_LAUNCH_SELECT(16, 1024, NT, true);
         } else {

@@ -89,13 +89,14 @@ def test_large_vocabularies(oracle_mod, lantern_gpu, V, d, k, dtype):
 
 @pytest.mark.parametrize("V,d,k,dtype,metric", [
     (8192, 256, 300, torch.bfloat16, "l2"),      # matrix cores on bf16 codes, 16 steps of 16 coordinates
-    (5000, 12, 260, torch.float32, "l2"),        # ragged last tile of rows and of columns, smallest k class
+    (5000, 12, 260, torch.float32, "l2"),        # ragged last tile of rows and of columns
+    (4100, 16, 58, torch.bfloat16, "l2"),        # smallest k of the path (65 candidates wanted), lists of 1024
     (4096, 8, 1009, torch.float32, "cosine"),    # smallest vocabulary and largest k of the path
     (40000, 8, 400, torch.float32, "l2"),        # beyond what the whole-row selection holds in registers
 ])
 def test_sampled_threshold_path(oracle_mod, lantern_gpu, V, d, k, dtype, metric):
     """Shapes that take the sampled thresholds and the filtering contraction (4096 tokens or more,
-    k - 1 + pad between 257 and 1024): whole tables compared, and no row may have needed the
+    k - 1 + pad between 65 and 1024): whole tables compared, and no row may have needed the
     all-pairs pass (every list came out between what the selection wants and its capacity)."""
     g = torch.Generator().manual_seed(V * 7 + k)
     cb = torch.randn(V, d, generator=g).to(dtype)
