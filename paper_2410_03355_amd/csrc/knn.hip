@@ -885,7 +885,8 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
     // long as 4h <= 256, and the same 256 from step to step, so such a step needs the wavefront's
     // own LDS order, not a workgroup barrier, unless the step before it was a wider one.
     auto exchange = [](double& ka, int& ia, double& kb, int& ib, bool up) {
-        const bool a_after_b = (ka > kb) || (ka == kb && ia > ib);
+        // bitwise, not short-circuit: three compares and two mask operations, no branches
+        const bool a_after_b = (ka > kb) | ((ka == kb) & (ia > ib));
         const bool sw = a_after_b == up;
         const double k0 = sw ? kb : ka, k1 = sw ? ka : kb;
         const int i0 = sw ? ib : ia, i1 = sw ? ia : ib;
@@ -916,7 +917,7 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
                     const int pl = lds_slot(l), pr = pl ^ lds_slot(stride);
                     const double kl = sh.key[pl], kr = sh.key[pr];
                     const int il = sh.idx[pl], ir = sh.idx[pr];
-                    const bool l_after_r = (kl > kr) || (kl == kr && il > ir);
+                    const bool l_after_r = (kl > kr) | ((kl == kr) & (il > ir));
                     if (l_after_r == up) {
                         sh.key[pl] = kr; sh.key[pr] = kl;
                         sh.idx[pl] = ir; sh.idx[pr] = il;
