@@ -55,10 +55,10 @@ MEASURED_TRAFFIC = {
 # contracted first: 2 V S d further flop), and so does the wide-latent table (a sample of 1024 tokens).
 MEASURED_KNN_SPLIT = {
     # workload: ({kernel: us per build}, extra contraction flop, library version, source)
-    "stress": ({"sample_contraction": 50.7, "thresholds": 36.1, "filter_contraction": 299.5, "selection": 402.7,
+    "stress": ({"sample_contraction": 51.3, "thresholds": 35.8, "filter_contraction": 301.0, "selection": 372.0,
                 "exact_check": 4.0}, 2.0 * 16384 * 2048 * 8, 222,
                "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
-    "wide_latent": ({"sample_contraction": 29.5, "thresholds": 12.7, "filter_contraction": 154.1, "selection": 129.5,
+    "wide_latent": ({"sample_contraction": 29.2, "thresholds": 12.9, "filter_contraction": 158.5, "selection": 133.0,
                      "exact_check": 4.0}, 2.0 * 8192 * 1024 * 256, 222,
                     "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
 }
