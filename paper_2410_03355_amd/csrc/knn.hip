@@ -30,6 +30,7 @@
 #include "device_utils.h"
 #include "knn_args.h"
 #include "lantern.h"
+#include "lds_sort.h"
 
 namespace lantern {
 
@@ -650,13 +651,6 @@ __global__ __launch_bounds__(NT) void knn_sample_rank(const float* skeys, int S,
 
 // ---- stage 2: select, re-rank exactly, emit ----
 constexpr int SEL_MAXW = 8;   // wavefronts of the largest selection workgroup (512 threads)
-// Element e of the candidate arrays lives in slot lds_slot(e): bits 5 and 6 of e are folded into
-// the low five bits (bit 6 into bits 0, 2, 4, bit 5 into bits 1, 3).  The sort's threads read four
-// elements base + q h each; whichever power of two h is, the 32 lanes of an 8-byte access then
-// fall into 32 different bank pairs, where the plain layout has them collide four at a time for
-// small h.  The map is linear over exclusive-or and stays inside aligned blocks of 128 slots.
-__device__ __forceinline__ int lds_slot(int e) { return e ^ ((e & 64) ? 21 : 0) ^ ((e & 32) ? 10 : 0); }
-
 template <int CAP>
 struct SelectShared {
     static_assert(CAP % 128 == 0, "lds_slot permutes blocks of 128 slots");
@@ -877,90 +871,16 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
             sh.idx[lds_slot(c)] = INT_MAX;
         }
     }
-    // Bitonic sort ascending by (key, idx), four elements per thread and round trip through the LDS:
-    // for two consecutive strides 2h and h of a merge, thread g takes the elements base, base + h,
-    // base + 2h, base + 3h (base: g with two zero bits put in at the strides' places) and does both
-    // steps on them in registers; a merge with an odd number of steps ends with a step of stride 1
-    // on four consecutive elements.  A wavefront's 64 threads cover 256 consecutive elements as
-    // long as 4h <= 256, and the same 256 from step to step, so such a step needs the wavefront's
-    // own LDS order, not a workgroup barrier, unless the step before it was a wider one.
-    auto exchange = [](double& ka, int& ia, double& kb, int& ib, bool up) {
-        // bitwise, not short-circuit: three compares and two mask operations, no branches
-        const bool a_after_b = (ka > kb) | ((ka == kb) & (ia > ib));
-        const bool sw = a_after_b == up;
-        const double k0 = sw ? kb : ka, k1 = sw ? ka : kb;
-        const int i0 = sw ? ib : ia, i1 = sw ? ia : ib;
-        ka = k0; kb = k1; ia = i0; ib = i1;
+    // ascending by (key, idx)
+    struct Cand {
+        double key;
+        int idx;
     };
-    bool wide_before = true;   // no step yet: the keys were written by other wavefronts
-    auto order_lds = [&](bool wide) {
-        if (wide || wide_before) {
-            __syncthreads();
-        } else {
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-        wide_before = wide;
-    };
-    // Up to 256 elements the network runs a pair per thread and step instead (element l = 2t - t mod
-    // stride against l + stride): four per thread would leave all but half a wavefront idle, and the
-    // steps are then short enough for their number not to matter.  A wavefront's pairs stay inside
-    // its own blocks of 128 elements for strides up to 64.
-    if (P <= 256) {
-        for (int size = 2; size <= P; size <<= 1) {
-            for (int stride = size >> 1; stride > 0; stride >>= 1) {
-                order_lds(stride > WAVE);
-                const int t = tid;
-                if (t < (P >> 1)) {
-                    const int l = 2 * t - (t & (stride - 1));
-                    const bool up = (l & size) == 0;
-                    const int pl = lds_slot(l), pr = pl ^ lds_slot(stride);
-                    const double kl = sh.key[pl], kr = sh.key[pr];
-                    const int il = sh.idx[pl], ir = sh.idx[pr];
-                    const bool l_after_r = (kl > kr) | ((kl == kr) & (il > ir));
-                    if (l_after_r == up) {
-                        sh.key[pl] = kr; sh.key[pr] = kl;
-                        sh.idx[pl] = ir; sh.idx[pr] = il;
-                    }
-                }
-            }
-        }
-    }
-    for (int size = 2, m = 1; P > 256 && size <= P; size <<= 1, ++m) {
-        int J = m - 1;   // the widest stride still to do in this merge is 2^J
-        for (; J >= 1; J -= 2) {
-            order_lds(J + 1 > 8);
-            const int h = 1 << (J - 1);
-            for (int g = tid; g < (P >> 2); g += TNT) {
-                const int base = ((g >> (J - 1)) << (J + 1)) | (g & (h - 1));
-                const bool up = (base & size) == 0;
-                // base has zero bits where h and 2h have theirs, and lds_slot is linear
-                const int p0 = lds_slot(base), p1 = p0 ^ lds_slot(h), p2 = p0 ^ lds_slot(2 * h), p3 = p0 ^ lds_slot(3 * h);
-                double k0 = sh.key[p0], k1 = sh.key[p1], k2 = sh.key[p2], k3 = sh.key[p3];
-                int i0 = sh.idx[p0], i1 = sh.idx[p1], i2 = sh.idx[p2], i3 = sh.idx[p3];
-                exchange(k0, i0, k2, i2, up);
-                exchange(k1, i1, k3, i3, up);
-                exchange(k0, i0, k1, i1, up);
-                exchange(k2, i2, k3, i3, up);
-                sh.key[p0] = k0; sh.key[p1] = k1; sh.key[p2] = k2; sh.key[p3] = k3;
-                sh.idx[p0] = i0; sh.idx[p1] = i1; sh.idx[p2] = i2; sh.idx[p3] = i3;
-            }
-        }
-        if (J == 0) {
-            order_lds(false);
-            for (int g = tid; g < (P >> 2); g += TNT) {
-                const int base = 4 * g;
-                const int p0 = lds_slot(base), p1 = p0 ^ 1, p2 = p0 ^ 2, p3 = p0 ^ 3;
-                double k0 = sh.key[p0], k1 = sh.key[p1], k2 = sh.key[p2], k3 = sh.key[p3];
-                int i0 = sh.idx[p0], i1 = sh.idx[p1], i2 = sh.idx[p2], i3 = sh.idx[p3];
-                exchange(k0, i0, k1, i1, (base & size) == 0);
-                exchange(k2, i2, k3, i3, ((base + 2) & size) == 0);
-                sh.key[p0] = k0; sh.key[p1] = k1; sh.key[p2] = k2; sh.key[p3] = k3;
-                sh.idx[p0] = i0; sh.idx[p1] = i1; sh.idx[p2] = i2; sh.idx[p3] = i3;
-            }
-        }
-    }
-    __syncthreads();
+    bitonic_sort_lds<TNT, Cand>(
+        P, tid, [&](int p) { return Cand{sh.key[p], sh.idx[p]}; },
+        [&](int p, const Cand& c) { sh.key[p] = c.key; sh.idx[p] = c.idx; },
+        [](const Cand& a, const Cand& b) { return (a.key > b.key) | ((a.key == b.key) & (a.idx > b.idx)); },
+        [](bool sw, const Cand& a, const Cand& b) { return Cand{sw ? b.key : a.key, sw ? b.idx : a.idx}; });
     // proof that no discarded token belongs to the row: every discarded j has an
     // approximate key above thr, hence an exact key above thr - err; the last
     // token taken must lie at or below that.
