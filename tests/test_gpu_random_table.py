@@ -10,7 +10,10 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("V,k", [(1, 1), (2, 2), (5, 5), (7, 1), (64, 64), (1000, 33), (1003, 1003),
-                                 (4096, 4096), (5000, 4096), (16384, 1000), (40000, 100)])
+                                 (4096, 4096), (5000, 4096), (16384, 1000), (40000, 100),
+                                 # keys held in registers (V <= 16384, k - 1 <= 2048): 16, 32 or 64 a thread,
+                                 # the largest k, one beyond it, a ragged vocabulary, a small k
+                                 (4096, 2049), (4096, 2050), (8000, 100), (16383, 999), (16384, 16)])
 def test_table_matches_oracle(oracle_mod, lantern_gpu, V, k):
     seed = 0xC0FFEE123456789 + V
     got = lantern_gpu.build_random(V, k, seed).cpu().numpy()
