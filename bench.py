@@ -35,17 +35,17 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # (FETCH_SIZE scaled by the factor a plain 256 MiB copy gives in the same run).  Counters cannot be
 # read from inside this process, so the figure is a record of that run: it is reported only while the
 # library still has the version it was measured at, and with the file it comes from.
-_FETCH_SCALE = 262144.0 / 131091.2   # what FETCH_SIZE read for a 256 MiB copy in the same run
+_FETCH_SCALE = 262144.0 / 131093.4   # what FETCH_SIZE read for a 256 MiB copy in the same run
 MEASURED_TRAFFIC = {
     # (workload, variant, mode): (bytes per launch, library version, source)
-    ("stress", "plain", "sample"): ((130997.7 * _FETCH_SCALE + 240.2) * 1024, 222,
-                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 222)"),
-    ("stress", "reject", "sample"): ((167877.9 * _FETCH_SCALE + 13905.8) * 1024, 222,
-                                     "profiles/verify_fast_stress_plain.md (reject mix; version 222)"),
-    ("wide_latent", "plain", "sample"): ((124430.2 * _FETCH_SCALE + 240.3) * 1024, 222,
-                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 222)"),
-    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 222,
-                                    "profiles/greedy_fast_stress_plain.md (version 222)"),
+    ("stress", "plain", "sample"): ((130992.9 * _FETCH_SCALE + 240.2) * 1024, 223,
+                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 223)"),
+    ("stress", "reject", "sample"): ((167914.9 * _FETCH_SCALE + 13893.2) * 1024, 223,
+                                     "profiles/verify_fast_stress_plain.md (reject mix; version 223)"),
+    ("wide_latent", "plain", "sample"): ((124427.8 * _FETCH_SCALE + 240.7) * 1024, 223,
+                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 223)"),
+    ("stress", "plain", "greedy"): ((69193.5 * _FETCH_SCALE + 240.0) * 1024, 223,
+                                    "profiles/greedy_fast_stress_plain.md (version 223)"),
 }
 
 
@@ -55,12 +55,12 @@ MEASURED_TRAFFIC = {
 # contracted first: 2 V S d further flop), and so does the wide-latent table (a sample of 1024 tokens).
 MEASURED_KNN_SPLIT = {
     # workload: ({kernel: us per build}, extra contraction flop, library version, source)
-    "stress": ({"sample_contraction": 51.3, "thresholds": 35.8, "filter_contraction": 301.0, "selection": 372.0,
-                "exact_check": 4.0}, 2.0 * 16384 * 2048 * 8, 222,
-               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
-    "wide_latent": ({"sample_contraction": 29.2, "thresholds": 12.9, "filter_contraction": 158.5, "selection": 133.0,
-                     "exact_check": 4.0}, 2.0 * 8192 * 1024 * 256, 222,
-                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 222)"),
+    "stress": ({"sample_contraction": 50.0, "thresholds": 37.0, "filter_contraction": 305.3, "selection": 379.7,
+                "exact_check": 4.0}, 2.0 * 16384 * 2048 * 8, 223,
+               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 223)"),
+    "wide_latent": ({"sample_contraction": 29.6, "thresholds": 14.4, "filter_contraction": 159.4, "selection": 134.7,
+                     "exact_check": 4.1}, 2.0 * 8192 * 1024 * 256, 223,
+                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 223)"),
 }
 
 

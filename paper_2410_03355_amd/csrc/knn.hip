@@ -608,7 +608,7 @@ __global__ __launch_bounds__(NT) void knn_gather_sample(const CT* cb, const floa
 // (At most four wavefronts per SIMD are aimed at: with more as its goal the compiler's scheduler
 // keeps the register count down by waiting for each of the 64 loads of the largest variant in turn.)
 template <int NS>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 4))) void knn_sample_rank(const float* skeys, int S, int rows, int rank, int slack,
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, NS > 32 ? 4 : 8))) void knn_sample_rank(const float* skeys, int S, int rows, int rank, int slack,
                                                       float* thr, int* counts) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int row = blockIdx.x * NW + (threadIdx.x >> 6);
