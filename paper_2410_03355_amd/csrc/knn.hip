@@ -477,7 +477,7 @@ struct FilterShared {
 
 // One 32-row strip of a wavefront's 64x64 block in the filtering contraction, columns j0..j0+63
 // (tiles acc0, acc1); l0: the strip's first row within the workgroup's 128, i0 its token.  A key
-// stays if it is at or below its row's threshold (-inf for rows beyond the block) and is not the
+// stays if it is at or below its row's threshold (NaN for rows beyond the block) and is not the
 // row's own token.  Element r of lanes 0-31 belongs to one row and of lanes 32-63 to another, so
 // each half of the wavefront adds its number of kept keys to its row's counter with one LDS
 // atomic; WRITE: what the atomic returns is the first of the half's slots in the row's list, and
@@ -545,11 +545,13 @@ __global__ __launch_bounds__(NT, 2) void knn_filter_mfma(const CT* cb, const flo
     const int l_base = (wave >> 1) * 64;
     const int i_base = r0 + il_wg + l_base;
     const int j_base = tj * 128 + (wave & 1) * 64;
-    const bool live = j_base < V;      // rows beyond the block are kept out by their thresholds
+    const bool live = j_base < V;      // rows beyond the block are kept out by their thresholds (NaN)
     if (tid < 128) {
         const bool row_ok = il_wg + tid < rows;
-        sh.thr[tid] = row_ok ? f.thr[il_wg + tid] : -INFINITY;
-        sh.norm[tid] = row_ok ? norms[r0 + il_wg + tid] : 0.f;
+        // rows beyond the block: no key compares at or below NaN (a threshold of -inf would let the
+        // cosine key -g / sqrt(0 n_j) = -inf through), and the norm is kept away from zero
+        sh.thr[tid] = row_ok ? f.thr[il_wg + tid] : NAN;
+        sh.norm[tid] = row_ok ? norms[r0 + il_wg + tid] : 1.f;
         sh.slots[tid] = 0;
     }
     __syncthreads();
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(NT, 2) void knn_filter_mfma(const CT* cb, const flo
     __syncthreads();
     if (tid < 128) {
         const int n = sh.slots[tid];   // n > 0 only for rows of the block
-        sh.slots[tid] = n > 0 ? atomicAdd(f.counts + il_wg + tid, n) : 0;
+        sh.slots[tid] = (n > 0 && il_wg + tid < rows) ? atomicAdd(f.counts + il_wg + tid, n) : 0;
     }
     __syncthreads();
     if (live) {
@@ -890,7 +892,18 @@ __global__ __launch_bounds__(TNT, (LIST || NK < 64) ? 8 : 4) void knn_select(con
     if (LIST || count < V - 1) {
         const double last = sh.key[lds_slot(need - 1)];
         double eabs = (double)err_abs;
-        if (norms) eabs += (double)err_norm * ((double)norms[i] + (double)*nmax);
+        if (norms) {
+            // Squared l2: the error of a key grows with the norms of its two codes, and the bound needs the
+            // largest norm a discarded token can have.  A token with norm n_j > 4 (n_i + last) is further
+            // away than the last one taken whatever its approximate key says, since |c_i - c_j|^2 >=
+            // (sqrt n_j - sqrt n_i)^2 > (2 sqrt(n_i + last) - sqrt n_i)^2 >= last; so only norms up to that
+            // (taken a thousandth larger, for the rounding of the fp32 norms) have to be covered.  A few
+            // codes of very large norm then no longer send every row to the all-pairs pass.
+            const double ni = (double)norms[i];
+            const double far = 4.004 * (ni + last);
+            const double nbound = far < (double)*nmax ? far : (double)*nmax;   // far may be inf or NaN: then the maximum
+            eabs += (double)err_norm * (ni + nbound);
+        }
         const double num = (double)thr - eabs;
         const double floor_discarded = num - 1.01 * (double)err_rel * fabs(num);
         ok = count >= need && last <= floor_discarded;
