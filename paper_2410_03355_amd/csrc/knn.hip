@@ -50,13 +50,47 @@ constexpr int SLOW_WGS = 128;     // workgroups (and fp64 row buffers) of the ex
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Plan of the sampled-threshold path for one shape.  A row's threshold is the key of rank `rank`
-// among its keys to `S` sampled tokens; the number of keys at or below it over the whole row then
-// has mean `rank * V / S` and, for a sample drawn without replacement, a hypergeometric spread.
-// The mean is put 5.5 standard deviations above the k-1+pad candidates the selection wants and the
-// list capacity 7 above the largest mean the search for the threshold may stop at (either miss is below 1e-12 per row for every shape admitted;
-// a stratified sample spreads no wider than a simple one).  use == false: the shape takes the
-// whole-key-block path.
+// Tails of the binomial law of n trials with success probability p, summed term by term from the
+// given end (the terms fall off geometrically there): P(X >= r) and P(X <= r).
+static double binomial_log_pmf(int n, double p, int x) {
+    return lgamma((double)n + 1.0) - lgamma((double)x + 1.0) - lgamma((double)(n - x) + 1.0) + (double)x * log(p) +
+           (double)(n - x) * log1p(-p);
+}
+static double binomial_upper_tail(int n, double p, int r) {
+    if (r <= 0) return 1.0;
+    if (r > n) return 0.0;
+    double term = exp(binomial_log_pmf(n, p, r)), sum = 0.0;
+    for (int x = r; x <= n && (term > 1e-300 || x < (int)(n * p)); ++x) {
+        sum += term;
+        term *= (double)(n - x) / (double)(x + 1) * p / (1.0 - p);
+        if (x > (int)(n * p) && term < sum * 1e-17) break;
+    }
+    return sum;
+}
+static double binomial_lower_tail(int n, double p, int r) {
+    if (r < 0) return 0.0;
+    if (r >= n) return 1.0;
+    double term = exp(binomial_log_pmf(n, p, r)), sum = 0.0;
+    for (int x = r; x >= 0; --x) {
+        sum += term;
+        if (x == 0) break;
+        term *= (double)x / (double)(n - x + 1) * (1.0 - p) / p;
+        if (x < (int)(n * p) && term < sum * 1e-17) break;
+    }
+    return sum;
+}
+
+// Plan of the sampled-threshold path for one shape.  A row's threshold has between `rank` and
+// `rank + slack` of the row's keys to `S` sampled tokens at or below it.  The row's list is too short
+// (fewer than the k-1+pad candidates the selection wants) only if at least rank - 1 of the sampled
+// tokens are among the row's k-2+pad nearest, and too long for its `cap` slots only if at most
+// rank + slack of them are among its cap+1 nearest (the row's own token may be in the sample: hence
+// the - 1).  The sample takes one token from each of S strata of the vocabulary, so the number of
+// sampled tokens in a given set is a sum of independent trials, whose tails are no heavier than
+// those of the binomial law with the same mean (Hoeffding): `rank` is the smallest and `cap` the
+// smallest of 1024 .. 4096 for which that bound puts either miss below 1e-10 per row, whatever
+// the codebook.  A row that misses all the same is flagged and ranked by the all-pairs pass.
+// use == false: the shape takes the whole-key-block path.
 struct FilterPlan {
     bool use;
     int S;      // sampled tokens, a multiple of 64, at most 4096
@@ -75,18 +109,22 @@ static FilterPlan filter_plan(int V, int d, int k, int cb_dtype) {
     int S = V / 8;
     if (S > 4096) S = 4096;
     S = S / 64 * 64;
-    const double rho = (double)V / (double)S;
-    const double zlo = 5.5, zhi = 7.0;
-    const double x = 0.5 * (zlo * sqrt(rho) + sqrt(zlo * zlo * rho + 4.0 * (double)want));
-    const double mean = x * x;
-    const double sd = sqrt(mean * rho);
-    int rank = (int)ceil(mean / rho);
-    if (rank > S) rank = S;
+    const double miss = 1e-10;
+    const double others = (double)(V - 1);
+    // too short: Binomial(S, (want - 1) / (V - 1)) >= rank - 1
+    const double p_lo = (double)(want - 1) / others;
+    int rank = (int)(S * p_lo) + 2;
+    while (rank < S && binomial_upper_tail(S, p_lo, rank - 1) > miss) ++rank;
+    if (rank >= S) return P;
     // the search for the threshold stops anywhere between rank and rank + slack (a sixteenth more)
     const int slack = rank / 16 < S - rank ? rank / 16 : S - rank;
-    const double mean_hi = (double)(rank + slack) * rho;
-    const int cap = ((int)(mean_hi + zhi * sqrt(mean_hi * rho)) + 1023) / 1024 * 1024;
-    if (cap > 4096) return P;
+    // too long: Binomial(S, (cap + 1) / (V - 1)) <= rank + slack
+    int cap = 0;
+    for (int c = 1024; c <= 4096 && cap == 0; c += 1024) {
+        const double p_hi = (double)(c + 1) / others;
+        if (p_hi >= 1.0 || binomial_lower_tail(S, p_hi, rank + slack) <= miss) cap = c;
+    }
+    if (cap == 0) return P;
     P.use = true;
     P.S = S;
     P.rank = rank;
