@@ -45,6 +45,26 @@ def test_status_strings_and_version(lib):
     assert lantern.status_string(-99) == "unknown status"
 
 
+def test_bench_records_are_of_this_library(lib):
+    """bench.py reports HBM traffic and the table build's per-kernel split from profiler runs that it
+    cannot repeat itself; each record names the library version it was measured at, and is only
+    reported while lantern_version() still says so.  A kernel change must come with a new version and
+    new measurements, or the bench line silently loses those fields: this keeps the two in step."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    version = lib.lantern_version()
+    assert bench.MEASURED_TRAFFIC and bench.MEASURED_KNN_SPLIT
+    for key, (nbytes, measured_at, source) in bench.MEASURED_TRAFFIC.items():
+        assert measured_at == version, f"traffic of {key} was measured at version {measured_at}, the library is {version}"
+        assert nbytes > 0 and os.path.exists(os.path.join(ROOT, source.split(" ")[0]))
+    for key, (us, extra_flop, measured_at, source) in bench.MEASURED_KNN_SPLIT.items():
+        assert measured_at == version, f"table-build split of {key} was measured at version {measured_at}"
+        assert os.path.exists(os.path.join(ROOT, source.split(" ")[0]))
+        assert f"version {version}" in open(os.path.join(ROOT, source.split(" ")[0])).read()
+
+
 def test_verify_argument_errors(lib):
     import paper_2410_03355_amd as L
     p = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
