@@ -208,16 +208,20 @@ def timed(runner, steps, warmup, stream):
 
 
 def time_knn_build(lantern, codebook, k, repeats=3):
-    """Median of a few builds between HIP events (the first call, untimed, loads the kernels)."""
+    """Median of a few builds between HIP events (the first call, untimed, loads the kernels); workspace
+    and table are allocated once, outside the timed calls."""
     import torch
-    lantern.build_knn(codebook, k)
+    V, d = codebook.shape
+    code = lantern.BF16 if codebook.dtype == torch.bfloat16 else lantern.F32
+    ws = torch.empty(lantern.binding.knn_workspace_bytes(code, V, d, k), dtype=torch.uint8, device=codebook.device)
+    knn = torch.empty((V, k), dtype=torch.int32, device=codebook.device)
+    lantern.build_knn(codebook, k, workspace=ws, out=knn)
     torch.cuda.synchronize()
     ms = []
-    knn = None
     for _ in range(repeats):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        knn = lantern.build_knn(codebook, k)
+        lantern.build_knn(codebook, k, workspace=ws, out=knn)
         e1.record()
         torch.cuda.synchronize()
         ms.append(e0.elapsed_time(e1))

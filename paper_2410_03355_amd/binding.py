@@ -144,9 +144,12 @@ def knn_workspace_bytes(cb_dtype: int, V: int, d: int, k: int) -> int:
     return int(load().lantern_build_knn_workspace_bytes(cb_dtype, V, d, k))
 
 
-def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None, return_stats: bool = False):
+def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None, return_stats: bool = False,
+              workspace: torch.Tensor = None, out: torch.Tensor = None):
     """lantern_build_knn on a [V, d] device tensor; returns int32 [V, k] on the device.
-    With return_stats also a device int32 scalar tensor: rows ranked by the exact all-pairs pass."""
+    With return_stats also a device int32 scalar tensor: rows ranked by the exact all-pairs pass.
+    workspace (uint8, at least knn_workspace_bytes, 256-byte aligned) and out ([V, k] int32) may be
+    brought by the caller, who then builds several tables without allocating in between."""
     lib = load()
     _need_cuda(codebook)
     if codebook.dim() != 2 or not codebook.is_contiguous():
@@ -156,14 +159,26 @@ def build_knn(codebook: torch.Tensor, k: int, metric: str = "l2", stream=None, r
     nbytes = knn_workspace_bytes(code, V, d, k)
     if nbytes == 0:
         raise LanternError(E_SHAPE, "lantern_build_knn_workspace_bytes")
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=codebook.device)
-    out = torch.empty((V, k), dtype=torch.int32, device=codebook.device)
+    if workspace is None:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=codebook.device)
+    else:
+        _need_cuda(workspace)
+        if workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.numel() < nbytes:
+            raise ValueError("workspace must be a contiguous uint8 tensor of at least knn_workspace_bytes")
+        ws = workspace
+    if out is None:
+        out = torch.empty((V, k), dtype=torch.int32, device=codebook.device)
+    else:
+        _need_cuda(out)
+        if out.dtype != torch.int32 or tuple(out.shape) != (V, k) or not out.is_contiguous():
+            raise ValueError("out must be a contiguous int32 [V, k] tensor")
     rc = lib.lantern_build_knn_metric(codebook.data_ptr(), code, V, d, k,
                                       {"l2": METRIC_L2, "cosine": METRIC_COSINE}[metric],
-                                      out.data_ptr(), ws.data_ptr(), nbytes, _stream_ptr(stream))
+                                      out.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
     if rc != OK:
         raise LanternError(rc, "lantern_build_knn")
-    ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
+    if workspace is None:
+        ws.record_stream(torch.cuda.current_stream() if stream is None else stream)
     if return_stats:
         return out, ws[:4].view(torch.int32)[0]
     return out
