@@ -344,30 +344,82 @@ __global__ __launch_bounds__(NT) void knn_dist_direct(const CT* cb, int V, int d
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <typename CT>
-__global__ __launch_bounds__(NT) void knn_norms(const CT* cb, int V, int d, float* norms) {
-    const int i = blockIdx.x * NT + threadIdx.x;
-    if (i >= V) return;
-    const CT* ci = cb + (int64_t)i * d;
-    float n = 0.f;
-    for (int t = 0; t < d; ++t) {
-        const float x = cb_f32<CT>(ci, t);
-        n = fmaf(x, x, n);
+// Sum of the squares of the coordinates held in 16 bytes of a row.
+template <typename CT> __device__ __forceinline__ float sum_squares(const uint4& v, float n);
+template <> __device__ __forceinline__ float sum_squares<float>(const uint4& v, float n) {
+    const float x0 = __uint_as_float(v.x), x1 = __uint_as_float(v.y), x2 = __uint_as_float(v.z), x3 = __uint_as_float(v.w);
+    return fmaf(x3, x3, fmaf(x2, x2, fmaf(x1, x1, fmaf(x0, x0, n))));
+}
+template <> __device__ __forceinline__ float sum_squares<uint16_t>(const uint4& v, float n) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xFFFF0000u);
+        n = fmaf(hi, hi, fmaf(lo, lo, n));
     }
-    norms[i] = n;
+    return n;
 }
 
-__global__ __launch_bounds__(NT) void knn_norm_max(const float* norms, int V, float* nmax) {
+// Squared norms of the rows and their maximum, for rows that are whole 16-byte vectors at 16-byte
+// aligned addresses.  *nmax is cleared beforehand; a norm is never below +0, so the bit patterns
+// order like the values and an unsigned maximum collects it, asked for only by a workgroup that
+// sees a smaller value there (a NaN norm is stored but left out of the maximum).  Rows of 256 bytes
+// or more take a wavefront each, NORM_ROWS rows per workgroup with the loads of all of a
+// wavefront's rows in flight together (index clamped, bits masked: no branch around a load);
+// shorter rows take a thread each.
+constexpr int NORM_ROWS = 32;
+constexpr int NORM_WAVE_VECS = 16;
+template <typename CT>
+__global__ __launch_bounds__(NT) void knn_norms(const CT* cb, int V, int d, float* norms, float* nmax) {
     __shared__ float red[NW];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x >> 6;
+    const int vecs = d * (int)sizeof(CT) / 16;   // 16-byte vectors per row
+    const uint4* cbv = reinterpret_cast<const uint4*>(cb);
     float m = 0.f;
-    for (int i = threadIdx.x; i < V; i += NT) m = fmaxf(m, norms[i]);
-    m = wave_max(m);
-    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x >> 6] = m;
+    if (vecs >= NORM_WAVE_VECS) {
+        constexpr int RPW = NORM_ROWS / NW;
+        float n[RPW];
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) n[q] = 0.f;
+        for (int c0 = 0; c0 < vecs; c0 += WAVE) {
+            const int c = c0 + lane;
+            const uint32_t mask = c < vecs ? 0xFFFFFFFFu : 0u;
+            const int cc = c < vecs ? c : vecs - 1;
+#pragma unroll
+            for (int q = 0; q < RPW; ++q) {
+                const int i = blockIdx.x * NORM_ROWS + q * NW + w;
+                uint4 v = cbv[(int64_t)(i < V ? i : V - 1) * vecs + cc];
+                v.x &= mask; v.y &= mask; v.z &= mask; v.w &= mask;
+                n[q] = sum_squares<CT>(v, n[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) {
+            const int i = blockIdx.x * NORM_ROWS + q * NW + w;
+            const float t = wave_sum(n[q]);
+            if (i < V) {
+                if (lane == 0) norms[i] = t;
+                m = fmaxf(m, t);
+            }
+        }
+    } else {
+        const int i = blockIdx.x * NT + threadIdx.x;
+        if (i < V) {
+            float n = 0.f;
+            for (int c = 0; c < vecs; ++c) n = sum_squares<CT>(cbv[(int64_t)i * vecs + c], n);
+            norms[i] = n;
+            m = fmaxf(m, n);
+        }
+    }
+    m = fmaxf(wave_max(m), 0.f);
+    if (lane == 0) red[w] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         float r = red[0];
-        for (int w = 1; w < NW; ++w) r = fmaxf(r, red[w]);
-        *nmax = r;
+        for (int v = 1; v < NW; ++v) r = fmaxf(r, red[v]);
+        unsigned int* target = reinterpret_cast<unsigned int*>(nmax);
+        const unsigned int bits = __float_as_uint(r);
+        if (__hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bits) atomicMax(target, bits);
     }
 }
 
@@ -987,7 +1039,10 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
     }
 }
 
-__global__ void knn_clear_stats(int* stats) { stats[threadIdx.x] = 0; }
+__global__ void knn_clear_stats(int* stats, float* nmax) {
+    stats[threadIdx.x] = 0;
+    if (threadIdx.x == 0) *nmax = 0.f;
+}
 __global__ void knn_copy_stats(const int* stats, int32_t* out) { *out = stats[0]; }
 
 template <int NS>
@@ -1005,9 +1060,9 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
     double* slow = reinterpret_cast<double*>(ws + L.slow);
     const CT* cb = static_cast<const CT*>(a.codebook);
     int* stats = reinterpret_cast<int*>(ws + L.stats);
-    hipLaunchKernelGGL(knn_clear_stats, dim3(1), dim3(64), 0, stream, stats);
     float* norms = reinterpret_cast<float*>(ws + L.norms);
     float* nmax = reinterpret_cast<float*>(ws + L.nmax);
+    hipLaunchKernelGGL(knn_clear_stats, dim3(1), dim3(64), 0, stream, stats, nmax);
     // matrix-core path: rows 16-byte aligned and coordinates in whole vectors
     const bool aligned = (reinterpret_cast<uintptr_t>(a.codebook) & 15) == 0;
     const bool mfma = aligned && (sizeof(CT) == 2 ? (a.d % 8) == 0 : (a.d % 4) == 0) && a.V >= 32;
@@ -1017,8 +1072,9 @@ static hipError_t build_typed(const KnnArgs& a, const KnnLayout& L, hipStream_t 
     const float gamma = (float)(a.d + 8) * 1.1920929e-7f;
     float err_rel, err_abs, err_norm;
     if (mfma) {
-        hipLaunchKernelGGL((knn_norms<CT>), dim3((a.V + NT - 1) / NT), dim3(NT), 0, stream, cb, a.V, a.d, norms);
-        hipLaunchKernelGGL(knn_norm_max, dim3(1), dim3(NT), 0, stream, norms, a.V, nmax);
+        const int per_wg = a.d * (int)sizeof(CT) / 16 >= NORM_WAVE_VECS ? NORM_ROWS : NT;
+        hipLaunchKernelGGL((knn_norms<CT>), dim3((a.V + per_wg - 1) / per_wg), dim3(NT), 0, stream, cb, a.V, a.d, norms,
+                           nmax);
         // n_i + n_j - 2 G: errors of the two norms and of G are each below gamma (n_i + n_j) / 2 ... gamma (n_i + n_j)
         err_rel = 0.f;
         err_abs = a.metric == 0 ? 0.f : 4.f * gamma;
