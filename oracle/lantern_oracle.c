@@ -72,6 +72,10 @@ static double sq_dist(const float* ci, const float* cj, int d) {
  * metric 0: squared l2 (the paper's choice, Section 5.1).
  * metric 1: cosine similarity, larger is nearer (ablation of Section 5.3.1);
  *           the key is -cos so that the same ascending order applies.
+ * A key that is not a number (the cosine with a code of zero norm, 0/0; a
+ * codebook entry that is itself NaN or infinite) stands for a similarity that
+ * does not exist: the paper does not treat it, and it is read here as the
+ * farthest possible, key +infinity, equal keys by the lower index as always.
  * Returns 0, or -1 on bad arguments. */
 int oracle_build_knn_rows(const float* codebook, int V, int d, int k, int metric,
                           int row_begin, int row_end, int32_t* out, int threads) {
@@ -116,6 +120,7 @@ int oracle_build_knn_rows(const float* codebook, int V, int d, int k, int metric
                         nj = sqrt(nj);
                         key = -(dot / (ni * nj));
                     }
+                    if (key != key) key = HUGE_VAL;
                     others[m].dist = key;
                     others[m].idx = j;
                     ++m;

@@ -94,6 +94,40 @@ def test_cosine_metric(oracle_mod):
     assert (a == b).mean() > 0.98
 
 
+def test_cosine_with_codes_of_zero_norm(oracle_mod):
+    """The cosine with a code of zero norm does not exist (0/0).  The reading taken: such a pair is the
+    farthest possible (key +infinity), equal keys by the lower index (Section 5.3.1 does not treat it).
+    Checked against a ranking built here from the finite similarities alone."""
+    rng = np.random.default_rng(31)
+    V, d = 40, 3
+    cb = rng.standard_normal((V, d)).astype(np.float32)
+    zeros = [5, 17, 39]
+    cb[zeros] = 0.0
+    got = oracle_mod.build_knn(cb, V, metric="cosine", threads=3)
+    c64 = cb.astype(np.float64)
+    nrm = np.linalg.norm(c64, axis=1)
+    for i in range(V):
+        assert got[i, 0] == i
+        if i in zeros:   # no similarity to anything: every other token, by index
+            want = [j for j in range(V) if j != i]
+        else:
+            live = [j for j in range(V) if j != i and j not in zeros]
+            cos = {j: float(c64[i] @ c64[j]) / (nrm[i] * nrm[j]) for j in live}
+            want = sorted(live, key=lambda j: (-cos[j], j)) + [j for j in zeros]
+        np.testing.assert_array_equal(got[i, 1:], want)
+    # the same reading for a key that is not a number under squared l2 (an infinite coordinate: inf - inf)
+    cb2 = rng.standard_normal((12, 2)).astype(np.float32)
+    cb2[4, 0] = np.inf
+    cb2[9, 0] = np.inf
+    got2 = oracle_mod.build_knn(cb2, 12, metric="l2")
+    for i in range(12):
+        if i in (4, 9):
+            np.testing.assert_array_equal(got2[i, 1:], [j for j in range(12) if j != i])   # all keys inf or NaN
+        else:
+            np.testing.assert_array_equal(sorted(got2[i, -2:]), [4, 9])                      # the two at infinity last
+            assert list(got2[i, -2:]) == [4, 9]
+
+
 def test_bad_arguments(oracle_mod):
     cb = np.zeros((4, 2), dtype=np.float32)
     for k in (0, 5):
