@@ -110,7 +110,10 @@ size_t lantern_build_knn_workspace_bytes(lantern_dtype cb_dtype, int V, int d, i
  *              distance that decides the order is the squared l2 distance
  *              evaluated in fp64 as sum over coordinates, in index order, of
  *              (c_i[t]-c_j[t])^2 with every operation rounded separately;
- *              equal distances are ordered by the lower token index.
+ *              equal distances are ordered by the lower token index.  A
+ *              distance that is not a number (infinite or NaN coordinates;
+ *              under the cosine key a code of zero norm, 0/0) counts as
+ *              +infinity: such a pair is the farthest possible.
  *   workspace  device memory of at least lantern_build_knn_workspace_bytes,
  *              256-byte aligned.  Scratch, except that when the work has
  *              finished its first int32 holds the number of rows whose

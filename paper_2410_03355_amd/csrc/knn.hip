@@ -285,7 +285,7 @@ __device__ double exact_key(const CT* cb, int d, int i, int j, int metric, bool 
                 acc = acc + sq;
             }
         }
-        return acc;
+        return acc == acc ? acc : (double)INFINITY;
     }
     double ni = 0.0, nj = 0.0, dot = 0.0;
     for (int t = 0; t < d; ++t) {
@@ -301,7 +301,8 @@ __device__ double exact_key(const CT* cb, int d, int i, int j, int metric, bool 
     ni = sqrt(ni);
     nj = sqrt(nj);
     const double den = ni * nj;
-    return -(dot / den);
+    const double key = -(dot / den);
+    return key == key ? key : (double)INFINITY;   // no similarity (a code of zero norm): the farthest
 }
 
 template <typename CT>
@@ -1022,7 +1023,7 @@ __global__ __launch_bounds__(NT) void knn_exact_rows(const CT* cb, int V, int d,
         if (tid == 0) atomicAdd(stats, 1);
         __syncthreads();
         for (int j = tid; j < V; j += NT)
-            buf[j] = (j == i) ? INFINITY : exact_key<CT>(cb, d, i, j, metric, false);
+            buf[j] = (j == i) ? NAN : exact_key<CT>(cb, d, i, j, metric, false);   // NaN: counted by no comparison below
         __threadfence_block();
         __syncthreads();
         int32_t* orow = out + (int64_t)i * k;

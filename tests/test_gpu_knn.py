@@ -175,6 +175,33 @@ def test_exact_ties_and_duplicates(oracle_mod, lantern_gpu):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("V,d,k,dtype,metric", [
+    (2166, 1, 1475, torch.float32, "cosine"),    # every key is -1, +1 or missing: all rows through the all-pairs pass
+    (500, 3, 500, torch.float32, "cosine"),      # direct keys, every token listed
+    (2048, 8, 100, torch.float32, "cosine"),     # contraction, whole rows
+    (2048, 8, 2048, torch.float32, "cosine"),
+    (8192, 8, 300, torch.float32, "cosine"),     # sampled thresholds and candidate lists
+    (4100, 16, 58, torch.bfloat16, "cosine"),
+    (1000, 4, 50, torch.float32, "l2"),          # infinite coordinates under squared l2 (inf - inf)
+])
+def test_keys_that_are_not_numbers(oracle_mod, lantern_gpu, V, d, k, dtype, metric):
+    """Codes of zero norm under the cosine key (0/0) and infinite coordinates under squared l2: such a pair
+    counts as the farthest possible, equal keys by the lower index, on both sides."""
+    g = torch.Generator().manual_seed(V + 13 * d + k)
+    cb = torch.randn(V, d, generator=g)
+    where = torch.randint(0, V, (5,), generator=g)
+    where[0], where[1] = 0, V - 1
+    if metric == "cosine":
+        cb[where] = 0.0
+        cb[8 * (V // 16)] = 0.0   # a stratum boundary of the token sample
+    else:
+        cb[where, 0] = float("inf")
+    cb = cb.to(dtype).contiguous()
+    got = _gpu_table(lantern_gpu, cb, k, metric=metric)
+    want = oracle_mod.build_knn(cb.float().numpy(), k, metric=metric, threads=16)
+    np.testing.assert_array_equal(got, want)
+
+
 def test_cosine_metric(oracle_mod, lantern_gpu):
     g = torch.Generator().manual_seed(77)
     cb = torch.randn(700, 12, generator=g) * (torch.rand(700, 1, generator=g) * 4 + 0.2)
