@@ -198,7 +198,12 @@ int lantern_build_knn_static(const void* codebook, lantern_dtype cb_dtype, int V
  * Decisions are exact with respect to fp64 evaluation of the rule above: a
  * fast fp32 pass settles every row whose comparisons clear a proven rounding
  * margin, and the remaining rows (and all rejected rows, whose inverse-CDF
- * bucket cannot be settled in fp32) are evaluated in fp64.  A rejected row
+ * bucket cannot be settled in fp32) are evaluated in fp64.  Two fp64
+ * evaluations that add in different orders agree to about 1e-15 relative, so
+ * a comparison whose sides are closer than that has no defined outcome: this
+ * is so by construction for delta = 1 with a table row that lists every token
+ * when t(xt) = 0, where the prefix sum equals delta in exact arithmetic.
+ * A rejected row
  * therefore costs many times an accepted one (about 23 us of one compute unit
  * at V = 16384); callers that walk chains or trees and use one resampled
  * token per walk should use lantern_decide_rows / lantern_resample_selected or
