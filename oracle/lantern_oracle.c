@@ -191,7 +191,10 @@ int oracle_diag_count(void) { return DIAG_COUNT; }
 /* Jensen-Shannon divergence (natural logarithm, Section 5.3.2) between a distorted target ta and
  * the target t, from the definition over the whole vocabulary:
  *     1/2 KL(ta || m) + 1/2 KL(t || m),   m = (ta + t) / 2,   0 ln 0 = 0.
- * Entries where the two agree have m equal to both, so both logarithms are ln 1 = 0 exactly. */
+ * Entries where the two agree have m equal to both, so both logarithms are ln 1 = 0 exactly.
+ * The divergence is never negative; when the mass moved is around one unit in the last place of
+ * t(xt) the two terms at xt cancel down to their rounding errors and the sum can come out below
+ * zero: such a value is returned as zero, so that no prefix ever passes a bound of zero. */
 static double jsd_full(const double* ta, const double* t, int V) {
     double kl_a = 0.0, kl_t = 0.0;
     for (int x = 0; x < V; ++x) {
@@ -200,7 +203,8 @@ static double jsd_full(const double* ta, const double* t, int V) {
         if (ta[x] > 0.0) kl_a = kl_a + ta[x] * log(ta[x] / m);
         if (t[x] > 0.0) kl_t = kl_t + t[x] * log(t[x] / m);
     }
-    return 0.5 * kl_a + 0.5 * kl_t;
+    double jsd = 0.5 * kl_a + 0.5 * kl_t;
+    return jsd < 0.0 ? 0.0 : jsd;
 }
 
 /*

@@ -86,3 +86,27 @@ def test_logits_path(oracle_mod):
         r = oracle_mod.verify_probs(t, g, tokens[i], table[tokens[i]], 0.03, un[i, 0], un[i, 1], divergence="jsd")
         assert diag["a_size"][i] == r["a_size"]
         assert diag["accept_prob"][i] == pytest.approx(r["accept_prob"], rel=1e-12)
+
+
+def test_a_bound_of_zero_takes_no_neighbour(oracle_mod):
+    """The divergence is positive as soon as any mass moves, so under a bound of zero the neighbourhood is the
+    token alone and the rule is standard speculative acceptance (Section 5.3.2 with Section 2).  When the moved
+    mass is around one unit in the last place of t(xt), the two logarithmic terms at xt cancel to their rounding
+    errors and the plain sum comes out negative (checked here with the same formula in numpy, for the first
+    case); the oracle must not take that for 'below zero'."""
+    t0, mv = 0.5348999931723383, 1.658202316445049e-16
+    mass = t0 + mv
+    mid = 0.5 * (mass + t0)
+    plain = 0.5 * mass * np.log(mass / mid) + 0.5 * (t0 * np.log(t0 / mid) + mv * np.log(2.0))
+    assert plain < 0.0          # the case is one where rounding alone would decide
+    rng = np.random.default_rng(3)
+    cases = [(t0, mv)] + [(float(a), float(a * b * 1.1e-16)) for a, b in
+                          zip(rng.uniform(0.1, 0.9, 3000), rng.uniform(0.2, 3.0, 3000))]
+    g = np.full(4, 0.25)
+    for t0, mv in cases:
+        t = np.array([t0, mv, 1.0 - t0 - mv, 0.0])
+        for u in (0.1, 0.9):
+            out = oracle_mod.verify_probs(t, g, 0, np.array([0, 1, 2], dtype=np.int32), 0.0, u, 0.5, divergence="jsd")
+            assert out["a_size"] == 1
+            assert out["accept"] == int(u * 0.25 < t0)      # u < min(1, t(xt) / g(xt))
+            assert out["mass"] == t0
