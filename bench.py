@@ -35,17 +35,17 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # (FETCH_SIZE scaled by the factor a plain 256 MiB copy gives in the same run).  Counters cannot be
 # read from inside this process, so the figure is a record of that run: it is reported only while the
 # library still has the version it was measured at, and with the file it comes from.
-_FETCH_SCALE = 262144.0 / 131091.2   # what FETCH_SIZE read for a 256 MiB copy in the same run
+_FETCH_SCALE = 262144.0 / 131092.4   # what FETCH_SIZE read for a 256 MiB copy in the same run
 MEASURED_TRAFFIC = {
     # (workload, variant, mode): (bytes per launch, library version, source)
-    ("stress", "plain", "sample"): ((130999.0 * _FETCH_SCALE + 240.1) * 1024, 226,
-                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 226)"),
-    ("stress", "reject", "sample"): ((167871.1 * _FETCH_SCALE + 13899.2) * 1024, 226,
-                                     "profiles/verify_fast_stress_plain.md (reject mix; version 226)"),
-    ("wide_latent", "plain", "sample"): ((124429.7 * _FETCH_SCALE + 240.5) * 1024, 226,
-                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 226)"),
-    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 226,
-                                    "profiles/greedy_fast_stress_plain.md (version 226)"),
+    ("stress", "plain", "sample"): ((130999.1 * _FETCH_SCALE + 240.1) * 1024, 227,
+                                    "profiles/verify_fast_stress_plain.md (FETCH_SIZE, WRITE_SIZE; version 227)"),
+    ("stress", "reject", "sample"): ((167881.8 * _FETCH_SCALE + 13853.8) * 1024, 227,
+                                     "profiles/verify_fast_stress_plain.md (reject mix; version 227)"),
+    ("wide_latent", "plain", "sample"): ((124415.7 * _FETCH_SCALE + 240.5) * 1024, 227,
+                                         "profiles/verify_fast_stress_plain.md (wide_latent; version 227)"),
+    ("stress", "plain", "greedy"): ((69193.6 * _FETCH_SCALE + 240.0) * 1024, 227,
+                                    "profiles/greedy_fast_stress_plain.md (version 227)"),
 }
 
 
@@ -55,12 +55,12 @@ MEASURED_TRAFFIC = {
 # contracted first: 2 V S d further flop), and so does the wide-latent table (a sample of 1024 tokens).
 MEASURED_KNN_SPLIT = {
     # workload: ({kernel: us per build}, extra contraction flop, library version, source)
-    "stress": ({"sample_contraction": 51.1, "thresholds": 36.2, "filter_contraction": 305.4, "selection": 381.7,
-                "exact_check": 4.0}, 2.0 * 16384 * 2048 * 8, 226,
-               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 226)"),
-    "wide_latent": ({"sample_contraction": 29.7, "thresholds": 12.8, "filter_contraction": 153.4, "selection": 129.0,
-                     "exact_check": 4.2}, 2.0 * 8192 * 1024 * 256, 226,
-                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 226)"),
+    "stress": ({"sample_contraction": 50.9, "thresholds": 36.7, "filter_contraction": 306.2, "selection": 380.4,
+                "exact_check": 4.1}, 2.0 * 16384 * 2048 * 8, 227,
+               "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 227)"),
+    "wide_latent": ({"sample_contraction": 30.5, "thresholds": 12.9, "filter_contraction": 157.6, "selection": 131.9,
+                     "exact_check": 4.1}, 2.0 * 8192 * 1024 * 256, 227,
+                    "profiles/knn_build_stress_and_wide_latent.md (kernel trace; version 227)"),
 }
 
 

@@ -225,6 +225,12 @@ int lantern_verify(const void* target_logits, const void* draft_logits, lantern_
  *   out_a_size      [N] int32  number of table slots taken into A
  *   out_path        [N] int32  0: settled by the fp32 pass, 1: evaluated in fp64
  * Unusable rows get NaN / -1 in the diagnostics.
+ * The three probabilities are binary32 values for inspection, not inputs of
+ * any decision: for a row settled by the fp32 pass they are formed from its
+ * fp32 terms (about 1e-5 relative for fp32 logits, 2e-3 for bf16), and where
+ * t(xt) or g(xt) lies below the smallest normal binary32 number (a token some
+ * 87 nats under the row's maximum) they lose precision or read zero, and
+ * out_accept_prob with them.  Decisions and out_a_size are not affected.
  */
 int lantern_verify_ex(const void* target_logits, const void* draft_logits,
                       lantern_dtype logits_dtype, int N, int V, int64_t row_stride_elems,

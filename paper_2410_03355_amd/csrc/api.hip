@@ -405,6 +405,6 @@ const char* lantern_status_string(int status) {
     }
 }
 
-int lantern_version(void) { return 226; }
+int lantern_version(void) { return 227; }
 
 }  // extern "C"

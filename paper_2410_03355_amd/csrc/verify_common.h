@@ -266,7 +266,10 @@ __device__ __forceinline__ double prefix_divergence64(int divergence, double t0,
     const double kl_a = mass > 0.0 ? mass * log(mass / mid) : 0.0;
     const double kl_t = t0 > 0.0 ? t0 * log(t0 / mid) : 0.0;
     const double members = moved * log(2.0);
-    return 0.5 * kl_a + 0.5 * (kl_t + members);
+    // never negative by definition; the two terms at the token cancel down to their rounding
+    // errors when the mass moved is around one unit in the last place of t0
+    const double jsd = 0.5 * kl_a + 0.5 * (kl_t + members);
+    return jsd < 0.0 ? 0.0 : jsd;
 }
 
 // Nearest-first walk of the neighbourhood in fp64 (Algorithm 2, inference part), by the

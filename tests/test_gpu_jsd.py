@@ -85,3 +85,21 @@ def test_cut_beyond_the_first_1024_slots(oracle_mod, lantern_gpu, divergence, de
     if delta < 0.5:
         assert (sizes < k).any()          # the cut itself lies beyond slot 1024
     assert (gout["path"] == 0).any()      # and the fp32 pass settles such rows
+
+
+@pytest.mark.parametrize("V,k,N,dtype,scale", [(2174, 255, 513, torch.float32, 30.0), (8, 8, 513, torch.float32, 8.0),
+                                               (20496, 1025, 512, torch.float32, 30.0),
+                                               (16384, 2019, 512, torch.bfloat16, 30.0)])
+def test_a_bound_of_zero_takes_no_neighbour(oracle_mod, lantern_gpu, V, k, N, dtype, scale):
+    """Widely spread logits put neighbours at 1e-17 of t(xt) and below, where the evaluated divergence is all
+    rounding error; with a bound of zero neither side may take one."""
+    g = torch.Generator().manual_seed(V + k)
+    tl = torch.randn(N, V, generator=g) * scale
+    dl = tl + torch.randn(N, V, generator=g) * scale
+    tok = tl.argmax(dim=1).to(torch.int32)          # t(xt) large: the neighbours' terms are far below its last place
+    tok[::3] = torch.randint(0, V, (len(tok[::3]),), generator=g, dtype=torch.int32)
+    table = random_table(V, k, seed=5)
+    un = torch.from_numpy(philox.uniforms(77, N, stream=3))
+    acc, res, diag, out = compare_verify(oracle_mod, lantern_gpu, tl.to(dtype), dl.to(dtype), tok, table, 0.0, un,
+                                         threads=16, label=f"jsd zero bound V={V}", divergence="jsd")
+    assert np.all(diag["a_size"] == 1) and np.all(out["a_size"] == 1)
