@@ -229,6 +229,28 @@ def time_knn_build(lantern, codebook, k, repeats=3):
     return knn, ms[len(ms) // 2]
 
 
+def time_random_table(lantern, V, k, seed=2410, repeats=3):
+    """Median of a few builds of the random-selection table (Section 5.3.1) between HIP events, after one
+    untimed call; the table is what the call must write (4 V k bytes), the pair keys are generated on the fly."""
+    import torch
+    lantern.build_random(V, k, seed)
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = lantern.build_random(V, k, seed)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+        del out
+    ms.sort()
+    mid = ms[len(ms) // 2]
+    return {"table": f"V={V} k={k}", "build_ms": mid, "algorithmic_bytes": 4 * V * k,
+            "hbm_frac": 4.0 * V * k / (mid * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "note": "timed with the table's allocation inside the call (a cached block after the first build)"}
+
+
 def knn_report(cfg, build_ms, version=None):
     """The build against the MFMA roofline of its contraction (2 V^2 d flop in the codebook's type) and
     against the HBM roofline of what it must move (codebook in, table out)."""
@@ -454,6 +476,7 @@ def main() -> int:
         wl = workloads.CONFIGS["wide_latent"]
         _, wl_ms = time_knn_build(lantern, workloads.make_codebook(wl, device=dev), wl.k)
         result["knn"][wl.name] = knn_report(wl, wl_ms, int(lib.lantern_version()))
+        result["random_table"] = time_random_table(lantern, cfg.V, cfg.k)
 
     if not args.no_cpu_baseline and args.mode == "sample" and args.divergence == "tvd":
         import numpy as np  # noqa: F401
